@@ -1,0 +1,417 @@
+// CPU oracle for the ModeT motion-decomposition operator.
+//
+// TEST INFRASTRUCTURE ONLY.  Plain, slow, fp64 loops written from the paper's definition:
+// windowed scores and softmax (Section 3.3.1, Eq. 3), the attention-weighted sum of the
+// integer offset grid V (Eq. 4-5), the derivatives of those two equations with respect to
+// Q and K (and the bias B), and the trilinear feature warp / 2x field upsampling used
+// between pyramid levels (Section 3.1).  It shares no code with the GPU library and is
+// called only by the tests, by the smoke check and by the benchmark's CPU-baseline leg.
+//
+// Layout: Q, K, src, out are [B, D, H, W, C] (channels last, head s owns channels
+// [s*d, (s+1)*d) with d = C / heads); phi, dphi are [B, D, H, W, heads, 3] with component
+// order (D, H, W); attn is [B, D, H, W, heads, k^3]; bias is [heads, k^3]; window offsets
+// are enumerated row-major with the D offset slowest: j = ((a+r)*k + (b+r))*k + (c+r).
+//
+// Readings of the paper that are built in here:
+//  * the moving (key) map is zero padded and a padded neighbour still takes part in the
+//    softmax with logit 0 (+ bias)  (Section 3.3.1, sentence after Eq. 3);
+//  * V_x = x - x_c, i.e. integer offsets -r..r per axis, r = (k-1)/2  (text after Eq. 4);
+//  * Eq. 3 prints no scale; `scale` multiplies the dot product (scale = 1 is Eq. 3 as
+//    printed, 1/sqrt(d) is the usual attention scaling).
+//
+// All inputs are widened exactly to double; every sum, exp and division is done in double.
+
+#include <cmath>
+#include <cstdint>
+#include <cstring>
+#include <vector>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+namespace {
+
+enum { IN_F32 = 0, IN_BF16 = 1, IN_F64 = 2 };
+
+struct Geo {
+  int B, D, H, W, C, heads, k, r, d, k3;
+};
+
+Geo make_geo(int B, int D, int H, int W, int C, int heads, int k) {
+  Geo g;
+  g.B = B; g.D = D; g.H = H; g.W = W; g.C = C; g.heads = heads; g.k = k;
+  g.r = (k - 1) / 2; g.d = C / heads; g.k3 = k * k * k;
+  return g;
+}
+
+inline double widen(float v) { return (double)v; }
+inline double widen(double v) { return v; }
+struct bf16 { uint16_t bits; };
+inline double widen(bf16 v) {
+  uint32_t u = (uint32_t)v.bits << 16;
+  float f;
+  std::memcpy(&f, &u, sizeof f);
+  return (double)f;
+}
+
+inline int64_t vox(const Geo& g, int b, int z, int y, int x) {
+  return (((int64_t)b * g.D + z) * g.H + y) * g.W + x;
+}
+inline bool inside(const Geo& g, int z, int y, int x) {
+  return z >= 0 && z < g.D && y >= 0 && y < g.H && x >= 0 && x < g.W;
+}
+
+// Eq. 3, the argument of the softmax: l[j] for the k^3 neighbours of voxel (b,z,y,x), head s.
+template <class T>
+void logits(const Geo& g, const T* Q, const T* K, const double* bias, double scale,
+            int b, int z, int y, int x, int s, double* l) {
+  const T* q = Q + vox(g, b, z, y, x) * g.C + s * g.d;
+  int j = 0;
+  for (int a = -g.r; a <= g.r; ++a)
+    for (int bb = -g.r; bb <= g.r; ++bb)
+      for (int c = -g.r; c <= g.r; ++c, ++j) {
+        double v = bias ? bias[s * g.k3 + j] : 0.0;
+        if (inside(g, z + a, y + bb, x + c)) {
+          const T* kk = K + vox(g, b, z + a, y + bb, x + c) * g.C + s * g.d;
+          double dot = 0.0;
+          for (int ch = 0; ch < g.d; ++ch) dot += widen(q[ch]) * widen(kk[ch]);
+          v += scale * dot;
+        }
+        l[j] = v;
+      }
+}
+
+// softmax over n values; returns log(sum(exp(l))).
+double softmax(const double* l, int n, double* w) {
+  double m = l[0];
+  for (int j = 1; j < n; ++j) m = l[j] > m ? l[j] : m;
+  double Z = 0.0;
+  for (int j = 0; j < n; ++j) { w[j] = std::exp(l[j] - m); Z += w[j]; }
+  for (int j = 0; j < n; ++j) w[j] /= Z;
+  return m + std::log(Z);
+}
+
+// Eq. 4: phi = sum_j w[j] * V[j],  V[j] = (a, b, c).
+void weighted_offsets(const Geo& g, const double* w, double* phi) {
+  phi[0] = phi[1] = phi[2] = 0.0;
+  int j = 0;
+  for (int a = -g.r; a <= g.r; ++a)
+    for (int bb = -g.r; bb <= g.r; ++bb)
+      for (int c = -g.r; c <= g.r; ++c, ++j) {
+        phi[0] += w[j] * a; phi[1] += w[j] * bb; phi[2] += w[j] * c;
+      }
+}
+
+// derivative of L = sum g.phi with respect to the logits of one window:
+// dl[j] = w[j] * (g.V[j] - g.phi)   (softmax Jacobian applied to t[j] = g.V[j]).
+void dlogits(const Geo& g, const double* w, const double* phi, const double* gr, double* dl) {
+  double gphi = gr[0] * phi[0] + gr[1] * phi[1] + gr[2] * phi[2];
+  int j = 0;
+  for (int a = -g.r; a <= g.r; ++a)
+    for (int bb = -g.r; bb <= g.r; ++bb)
+      for (int c = -g.r; c <= g.r; ++c, ++j) {
+        double t = gr[0] * a + gr[1] * bb + gr[2] * c;
+        dl[j] = w[j] * (t - gphi);
+      }
+}
+
+template <class T>
+void fwd_impl(const Geo& g, const T* Q, const T* K, const double* bias, double scale,
+              double* phi, double* attn, double* lse) {
+#pragma omp parallel
+  {
+    std::vector<double> l(g.k3), w(g.k3);
+#pragma omp for collapse(2) schedule(static)
+    for (int b = 0; b < g.B; ++b)
+      for (int z = 0; z < g.D; ++z)
+        for (int y = 0; y < g.H; ++y)
+          for (int x = 0; x < g.W; ++x)
+            for (int s = 0; s < g.heads; ++s) {
+              int64_t vn = vox(g, b, z, y, x) * g.heads + s;
+              logits(g, Q, K, bias, scale, b, z, y, x, s, l.data());
+              double ls = softmax(l.data(), g.k3, w.data());
+              weighted_offsets(g, w.data(), phi + vn * 3);
+              if (attn) std::memcpy(attn + vn * g.k3, w.data(), sizeof(double) * g.k3);
+              if (lse) lse[vn] = ls;
+            }
+  }
+}
+
+// literal, serial: every (query, neighbour) pair adds into dQ[query] and dK[neighbour].
+template <class T>
+void bwd_scatter_impl(const Geo& g, const T* Q, const T* K, const double* bias, double scale,
+                      const double* dphi, double* dQ, double* dK, double* dbias) {
+  int64_t n = (int64_t)g.B * g.D * g.H * g.W * g.C;
+  for (int64_t i = 0; i < n; ++i) dQ[i] = dK[i] = 0.0;
+  if (dbias) for (int i = 0; i < g.heads * g.k3; ++i) dbias[i] = 0.0;
+  std::vector<double> l(g.k3), w(g.k3), dl(g.k3);
+  for (int b = 0; b < g.B; ++b)
+    for (int z = 0; z < g.D; ++z)
+      for (int y = 0; y < g.H; ++y)
+        for (int x = 0; x < g.W; ++x)
+          for (int s = 0; s < g.heads; ++s) {
+            int64_t p = vox(g, b, z, y, x);
+            double phi[3];
+            logits(g, Q, K, bias, scale, b, z, y, x, s, l.data());
+            softmax(l.data(), g.k3, w.data());
+            weighted_offsets(g, w.data(), phi);
+            dlogits(g, w.data(), phi, dphi + (p * g.heads + s) * 3, dl.data());
+            int j = 0;
+            for (int a = -g.r; a <= g.r; ++a)
+              for (int bb = -g.r; bb <= g.r; ++bb)
+                for (int c = -g.r; c <= g.r; ++c, ++j) {
+                  if (dbias) dbias[s * g.k3 + j] += dl[j];
+                  if (!inside(g, z + a, y + bb, x + c)) continue;   // padding has no gradient
+                  int64_t q = vox(g, b, z + a, y + bb, x + c);
+                  for (int ch = 0; ch < g.d; ++ch) {
+                    int64_t ip = p * g.C + s * g.d + ch, iq = q * g.C + s * g.d + ch;
+                    dQ[ip] += scale * dl[j] * widen(K[iq]);
+                    dK[iq] += scale * dl[j] * widen(Q[ip]);
+                  }
+                }
+          }
+}
+
+// second derivation: first dl for every window, then each output element collects its terms.
+template <class T>
+void bwd_gather_impl(const Geo& g, const T* Q, const T* K, const double* bias, double scale,
+                     const double* dphi, double* dQ, double* dK) {
+  int64_t nvn = (int64_t)g.B * g.D * g.H * g.W * g.heads;
+  std::vector<double> DL((size_t)nvn * g.k3);
+#pragma omp parallel
+  {
+    std::vector<double> l(g.k3), w(g.k3);
+#pragma omp for collapse(2) schedule(static)
+    for (int b = 0; b < g.B; ++b)
+      for (int z = 0; z < g.D; ++z)
+        for (int y = 0; y < g.H; ++y)
+          for (int x = 0; x < g.W; ++x)
+            for (int s = 0; s < g.heads; ++s) {
+              int64_t vn = vox(g, b, z, y, x) * g.heads + s;
+              double phi[3];
+              logits(g, Q, K, bias, scale, b, z, y, x, s, l.data());
+              softmax(l.data(), g.k3, w.data());
+              weighted_offsets(g, w.data(), phi);
+              dlogits(g, w.data(), phi, dphi + vn * 3, DL.data() + vn * g.k3);
+            }
+#pragma omp for collapse(2) schedule(static)
+    for (int b = 0; b < g.B; ++b)
+      for (int z = 0; z < g.D; ++z)
+        for (int y = 0; y < g.H; ++y)
+          for (int x = 0; x < g.W; ++x)
+            for (int s = 0; s < g.heads; ++s) {
+              int64_t p = vox(g, b, z, y, x);
+              for (int ch = 0; ch < g.d; ++ch) {
+                double aq = 0.0, ak = 0.0;
+                int j = 0;
+                for (int a = -g.r; a <= g.r; ++a)
+                  for (int bb = -g.r; bb <= g.r; ++bb)
+                    for (int c = -g.r; c <= g.r; ++c, ++j) {
+                      // dQ[p]: neighbour p + o
+                      if (inside(g, z + a, y + bb, x + c))
+                        aq += DL[(size_t)(p * g.heads + s) * g.k3 + j] *
+                              widen(K[vox(g, b, z + a, y + bb, x + c) * g.C + s * g.d + ch]);
+                      // dK[p]: the query p - o sees this key under offset o
+                      if (inside(g, z - a, y - bb, x - c)) {
+                        int64_t qv = vox(g, b, z - a, y - bb, x - c);
+                        ak += DL[(size_t)(qv * g.heads + s) * g.k3 + j] * widen(Q[qv * g.C + s * g.d + ch]);
+                      }
+                    }
+                dQ[p * g.C + s * g.d + ch] = scale * aq;
+                dK[p * g.C + s * g.d + ch] = scale * ak;
+              }
+            }
+  }
+}
+
+void decode_vn(const Geo& g, int64_t vn, int& b, int& z, int& y, int& x, int& s) {
+  s = (int)(vn % g.heads); vn /= g.heads;
+  x = (int)(vn % g.W); vn /= g.W;
+  y = (int)(vn % g.H); vn /= g.H;
+  z = (int)(vn % g.D); vn /= g.D;
+  b = (int)vn;
+}
+
+template <class T>
+void fwd_at_impl(const Geo& g, const T* Q, const T* K, const double* bias, double scale,
+                 int64_t n, const int64_t* idx, double* phi, double* lse) {
+#pragma omp parallel
+  {
+    std::vector<double> l(g.k3), w(g.k3);
+#pragma omp for schedule(static)
+    for (int64_t i = 0; i < n; ++i) {
+      int b, z, y, x, s;
+      decode_vn(g, idx[i], b, z, y, x, s);
+      logits(g, Q, K, bias, scale, b, z, y, x, s, l.data());
+      double ls = softmax(l.data(), g.k3, w.data());
+      weighted_offsets(g, w.data(), phi + i * 3);
+      if (lse) lse[i] = ls;
+    }
+  }
+}
+
+// dQ and dK for the d channels of head s at the sampled voxels idx[i] (voxel*heads + s).
+template <class T>
+void bwd_at_impl(const Geo& g, const T* Q, const T* K, const double* bias, double scale,
+                 const double* dphi, int64_t n, const int64_t* idx, double* dQ, double* dK) {
+#pragma omp parallel
+  {
+    std::vector<double> l(g.k3), w(g.k3), dl(g.k3);
+#pragma omp for schedule(static)
+    for (int64_t i = 0; i < n; ++i) {
+      int b, z, y, x, s;
+      decode_vn(g, idx[i], b, z, y, x, s);
+      double phi[3];
+      // dQ at (b,z,y,x,s): its own window
+      logits(g, Q, K, bias, scale, b, z, y, x, s, l.data());
+      softmax(l.data(), g.k3, w.data());
+      weighted_offsets(g, w.data(), phi);
+      dlogits(g, w.data(), phi, dphi + idx[i] * 3, dl.data());
+      for (int ch = 0; ch < g.d; ++ch) dQ[i * g.d + ch] = dK[i * g.d + ch] = 0.0;
+      int j = 0;
+      for (int a = -g.r; a <= g.r; ++a)
+        for (int bb = -g.r; bb <= g.r; ++bb)
+          for (int c = -g.r; c <= g.r; ++c, ++j)
+            if (inside(g, z + a, y + bb, x + c))
+              for (int ch = 0; ch < g.d; ++ch)
+                dQ[i * g.d + ch] += scale * dl[j] * widen(K[vox(g, b, z + a, y + bb, x + c) * g.C + s * g.d + ch]);
+      // dK at (b,z,y,x,s): every query p = q - o that has this key in its window
+      j = 0;
+      for (int a = -g.r; a <= g.r; ++a)
+        for (int bb = -g.r; bb <= g.r; ++bb)
+          for (int c = -g.r; c <= g.r; ++c, ++j) {
+            int pz = z - a, py = y - bb, px = x - c;
+            if (!inside(g, pz, py, px)) continue;
+            int64_t pv = vox(g, b, pz, py, px);
+            logits(g, Q, K, bias, scale, b, pz, py, px, s, l.data());
+            softmax(l.data(), g.k3, w.data());
+            weighted_offsets(g, w.data(), phi);
+            dlogits(g, w.data(), phi, dphi + (pv * g.heads + s) * 3, dl.data());
+            for (int ch = 0; ch < g.d; ++ch)
+              dK[i * g.d + ch] += scale * dl[j] * widen(Q[pv * g.C + s * g.d + ch]);
+          }
+    }
+  }
+}
+
+// trilinear sample of a [D,H,W,C] volume (one batch item) at real coordinates, zero outside.
+template <class T>
+void sample_zero(const T* vol, int D, int H, int W, int C, double cz, double cy, double cx, double* out) {
+  double fz = std::floor(cz), fy = std::floor(cy), fx = std::floor(cx);
+  double tz = cz - fz, ty = cy - fy, tx = cx - fx;
+  for (int c = 0; c < C; ++c) out[c] = 0.0;
+  for (int dz = 0; dz < 2; ++dz)
+    for (int dy = 0; dy < 2; ++dy)
+      for (int dx = 0; dx < 2; ++dx) {
+        double z = fz + dz, y = fy + dy, x = fx + dx;
+        if (z < 0 || z > D - 1 || y < 0 || y > H - 1 || x < 0 || x > W - 1) continue;
+        double wgt = (dz ? tz : 1.0 - tz) * (dy ? ty : 1.0 - ty) * (dx ? tx : 1.0 - tx);
+        const T* v = vol + (((int64_t)z * H + (int64_t)y) * W + (int64_t)x) * C;
+        for (int c = 0; c < C; ++c) out[c] += wgt * widen(v[c]);
+      }
+}
+
+inline double clampd(double v, double lo, double hi) { return v < lo ? lo : (v > hi ? hi : v); }
+
+// displacement (fine-grid voxel units) at fine voxel (z,y,x) from a half-resolution field:
+// the coarse voxel i covers fine voxels 2i and 2i+1 (2x average pooling geometry), so the fine
+// centre z sits at coarse coordinate (z + 0.5)/2 - 0.5, clamped to the coarse grid; values x2.
+void upsampled_disp(const float* fc, int Dc, int Hc, int Wc, int z, int y, int x, double* u) {
+  double cz = clampd((z + 0.5) / 2.0 - 0.5, 0.0, Dc - 1.0);
+  double cy = clampd((y + 0.5) / 2.0 - 0.5, 0.0, Hc - 1.0);
+  double cx = clampd((x + 0.5) / 2.0 - 0.5, 0.0, Wc - 1.0);
+  sample_zero(fc, Dc, Hc, Wc, 3, cz, cy, cx, u);
+  u[0] *= 2.0; u[1] *= 2.0; u[2] *= 2.0;
+}
+
+template <class T>
+void warp_impl(const T* src, const float* field, int B, int D, int H, int W, int C, int half, double* out) {
+  int Dc = D / 2, Hc = H / 2, Wc = W / 2;
+#pragma omp parallel for collapse(2) schedule(static)
+  for (int b = 0; b < B; ++b)
+    for (int z = 0; z < D; ++z)
+      for (int y = 0; y < H; ++y)
+        for (int x = 0; x < W; ++x) {
+          double u[3];
+          int64_t p = (((int64_t)b * D + z) * H + y) * W + x;
+          if (half) {
+            upsampled_disp(field + (int64_t)b * Dc * Hc * Wc * 3, Dc, Hc, Wc, z, y, x, u);
+          } else {
+            for (int a = 0; a < 3; ++a) u[a] = (double)field[p * 3 + a];
+          }
+          sample_zero(src + (int64_t)b * D * H * W * C, D, H, W, C, z + u[0], y + u[1], x + u[2], out + p * C);
+        }
+}
+
+}  // namespace
+
+#define DISPATCH(dtype, CALL)                                            \
+  switch (dtype) {                                                       \
+    case IN_F32: { typedef float T; CALL; return 0; }                    \
+    case IN_BF16: { typedef bf16 T; CALL; return 0; }                    \
+    case IN_F64: { typedef double T; CALL; return 0; }                   \
+    default: return -1;                                                  \
+  }
+
+extern "C" {
+
+int oracle_modet_fwd(const void* Q, const void* K, const double* bias, int B, int D, int H, int W, int C,
+                     int heads, int k, double scale, int dtype, double* phi, double* attn, double* lse) {
+  Geo g = make_geo(B, D, H, W, C, heads, k);
+  DISPATCH(dtype, fwd_impl<T>(g, (const T*)Q, (const T*)K, bias, scale, phi, attn, lse));
+}
+
+int oracle_modet_bwd_scatter(const void* Q, const void* K, const double* bias, const double* dphi, int B, int D,
+                             int H, int W, int C, int heads, int k, double scale, int dtype, double* dQ,
+                             double* dK, double* dbias) {
+  Geo g = make_geo(B, D, H, W, C, heads, k);
+  DISPATCH(dtype, bwd_scatter_impl<T>(g, (const T*)Q, (const T*)K, bias, scale, dphi, dQ, dK, dbias));
+}
+
+int oracle_modet_bwd_gather(const void* Q, const void* K, const double* bias, const double* dphi, int B, int D,
+                            int H, int W, int C, int heads, int k, double scale, int dtype, double* dQ,
+                            double* dK) {
+  Geo g = make_geo(B, D, H, W, C, heads, k);
+  DISPATCH(dtype, bwd_gather_impl<T>(g, (const T*)Q, (const T*)K, bias, scale, dphi, dQ, dK));
+}
+
+int oracle_modet_fwd_at(const void* Q, const void* K, const double* bias, int B, int D, int H, int W, int C,
+                        int heads, int k, double scale, int dtype, int64_t n, const int64_t* idx, double* phi,
+                        double* lse) {
+  Geo g = make_geo(B, D, H, W, C, heads, k);
+  DISPATCH(dtype, fwd_at_impl<T>(g, (const T*)Q, (const T*)K, bias, scale, n, idx, phi, lse));
+}
+
+int oracle_modet_bwd_at(const void* Q, const void* K, const double* bias, const double* dphi, int B, int D, int H,
+                        int W, int C, int heads, int k, double scale, int dtype, int64_t n, const int64_t* idx,
+                        double* dQ, double* dK) {
+  Geo g = make_geo(B, D, H, W, C, heads, k);
+  DISPATCH(dtype, bwd_at_impl<T>(g, (const T*)Q, (const T*)K, bias, scale, dphi, n, idx, dQ, dK));
+}
+
+int oracle_warp(const void* src, const float* field, int B, int D, int H, int W, int C, int field_half_res,
+                int dtype, double* out) {
+  DISPATCH(dtype, warp_impl<T>((const T*)src, field, B, D, H, W, C, field_half_res, out));
+}
+
+// the 2x upsampled, x2 scaled field on its own: fine [B,D,H,W,3] from coarse [B,D/2,H/2,W/2,3].
+int oracle_upsample2x(const float* coarse, int B, int D, int H, int W, double* fine) {
+  int Dc = D / 2, Hc = H / 2, Wc = W / 2;
+  for (int b = 0; b < B; ++b)
+    for (int z = 0; z < D; ++z)
+      for (int y = 0; y < H; ++y)
+        for (int x = 0; x < W; ++x)
+          upsampled_disp(coarse + (int64_t)b * Dc * Hc * Wc * 3, Dc, Hc, Wc, z, y, x,
+                         fine + ((((int64_t)b * D + z) * H + y) * W + x) * 3);
+  return 0;
+}
+
+int oracle_threads(void) {
+#ifdef _OPENMP
+  return omp_get_max_threads();
+#else
+  return 1;
+#endif
+}
+
+}  // extern "C"
