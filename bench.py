@@ -1,0 +1,190 @@
+#!/usr/bin/env python3
+"""Benchmark of the ModeT hot path on one MI355X.
+
+A step is one modet_fwd (phi + log-normaliser) followed by one modet_bwd (dQ, dK) on the
+brain-MRI full-resolution level (1 x 160 x 192 x 224, C=8, 1 head, k=3, fp32, synthetic
+seeded inputs already resident in HBM).  Prints ONE JSON line:
+
+  value      voxel-neighbourhoods/s = B*D*H*W*heads / (time of fwd + bwd)
+  roofline   the dominant kernel (the backward) against the 8 TB/s HBM peak, from its
+             algorithmic bytes and its live HIP-event duration inside the timed region
+  cpu_baseline   the CPU oracle (fp64 loops, OpenMP over slabs) on the same inputs
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
+# command (see profiles/), scaled by the copy-kernel calibration; None until measured.
+MEASURED_TRAFFIC_BYTES = {3: None}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=3, choices=[1, 2, 3, 5])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--generic", action="store_true", help="force the generic kernels")
+    ap.add_argument("--recompute-stats", action="store_true", help="do not hand phi/lse of the forward to the backward")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (--gpus 1); a multi-GPU figure is not produced.",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2403_16526_amd import modet, synth
+
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    torch.cuda.set_device(0)
+    cfg = synth.CONFIGS[args.config]
+    t0 = time.time()
+    c = synth.make_config(args.config)
+    t_gen = time.time() - t0
+    B, D, H, W, C, heads, k, dtype = (c[n] for n in ("B", "D", "H", "W", "C", "heads", "k", "dtype"))
+    nvox = B * D * H * W
+    nvn = nvox * heads
+    esz = 2 if dtype == "bf16" else 4
+
+    def up(a):
+        if a.dtype == np.uint16:
+            return torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
+        return torch.from_numpy(a).cuda()
+
+    Q, K, g = up(c["Q"]), up(c["K"]), up(c["dphi"])
+    f32 = dict(device="cuda", dtype=torch.float32)
+    phi = torch.empty((B, D, H, W, heads, 3), **f32)
+    lse = torch.empty((B, D, H, W, heads), **f32)
+    dQ = torch.empty((B, D, H, W, C), **f32)
+    dK = torch.empty((B, D, H, W, C), **f32)
+    in_dt = modet.MODET_BF16 if dtype == "bf16" else modet.MODET_F32
+    have_stats = not args.recompute_stats
+    wsb = modet.modet_bwd_workspace_bytes(B, D, H, W, C, heads, k, in_dt, have_stats)
+    ws = torch.empty(max(wsb, 16), device="cuda", dtype=torch.uint8)
+    if args.generic:
+        modet.modet_set_kernel_path(1)
+
+    def fwd():
+        modet.modet_fwd(Q, K, heads, k, out=(phi, lse))
+
+    def bwd():
+        if have_stats:
+            modet.modet_bwd(Q, K, g, heads, k, phi=phi, lse=lse, out=(dQ, dK), workspace=ws)
+        else:
+            modet.modet_bwd(Q, K, g, heads, k, out=(dQ, dK), workspace=ws)
+
+    for _ in range(args.warmup):
+        fwd()
+        bwd()
+    torch.cuda.synchronize()
+
+    # timed region: exactly `steps` steps; HIP events on the launch stream bracket every call
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        ev[i][0].record()
+        fwd()
+        ev[i][1].record()
+        bwd()
+        ev[i][2].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    t_fwd = sum(e[0].elapsed_time(e[1]) for e in ev) / args.steps          # ms
+    t_bwd = sum(e[1].elapsed_time(e[2]) for e in ev) / args.steps
+    ms_per_step = wall * 1e3 / args.steps
+
+    # algorithmic bytes (each tensor moved once, no stored attention)
+    fwd_bytes = nvox * (2 * C * esz + 12 * heads)
+    bwd_bytes = nvox * (2 * C * esz + 12 * heads + 8 * C)
+    dom_bytes, dom_ms, dom_name = (bwd_bytes, t_bwd, "modet_bwd") if t_bwd >= t_fwd else (fwd_bytes, t_fwd, "modet_fwd")
+    achieved = dom_bytes / (dom_ms * 1e-3) / 1e9
+    roofline = {"bound": "hbm", "kernel": dom_name, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                "traffic": MEASURED_TRAFFIC_BYTES.get(args.config),
+                "algorithmic_bytes": dom_bytes, "avg_launch_ms": round(dom_ms, 4)}
+
+    # a plain device copy of the same byte count: the attainable ceiling on this machine
+    nb = (fwd_bytes + bwd_bytes) // 2
+    a = torch.empty(nb // 4, **f32)
+    b = torch.empty_like(a)
+    for _ in range(3):
+        b.copy_(a)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(10):
+        b.copy_(a)
+    e1.record()
+    torch.cuda.synchronize()
+    copy_gbs = 2 * nb * 10 / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    del a, b
+
+    # warp at the same shape (reported beside the metric, not part of `value`)
+    field = torch.from_numpy(synth.smooth_real_field(synth.BASE_SEED + args.config, B, D, H, W, 1.5)).cuda()
+    Kw = torch.empty_like(K)
+    for _ in range(3):
+        modet.modet_warp(K, field, out=Kw)
+    e0.record()
+    for _ in range(10):
+        modet.modet_warp(K, field, out=Kw)
+    e1.record()
+    torch.cuda.synchronize()
+    t_warp = e0.elapsed_time(e1) / 10
+    warp_bytes = nvox * (2 * C * esz + 12)
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        # bounded sample: a slab of D planes sized so the oracle runs for roughly 10-20 s
+        Ds = D if nvn * (k ** 3) <= 6_881_280 * 27 else max(2 * k, int(D * 6_881_280 * 27 / (nvn * k ** 3)))
+        sl = slice(0, Ds)
+        Qs, Ks, gs = c["Q"][:, sl].copy(), c["K"][:, sl].copy(), c["dphi"][:, sl].copy()
+        best = 1e30
+        for _ in range(2):
+            t0 = time.perf_counter()
+            oracle.modet_fwd(Qs, Ks, heads, k, dtype=dtype)
+            oracle.modet_bwd(Qs, Ks, gs, heads, k, dtype=dtype, form="gather")
+            best = min(best, time.perf_counter() - t0)
+        cpu = {"value": round(B * Ds * H * W * heads / best, 1), "unit": "voxel-neighbourhoods/s",
+               "cores": oracle.threads(), "kind": "oracle",
+               "sample": f"fwd+bwd(gather form) of the fp64 oracle on planes 0..{Ds - 1} of {D} "
+                         f"({B}x{Ds}x{H}x{W}), best of 2, {best:.2f} s"}
+
+    value = nvn / (wall / args.steps)
+    line = {
+        "metric": "ModeT fwd+bwd voxel-neighbourhoods/sec and achieved HBM GB/s (% of peak), 1 GPU",
+        "value": round(value, 1), "unit": "voxel-neighbourhoods/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32" if dtype == "f32" else "bf16-in/f32-acc", "data": "synthetic",
+        "config": {"workload": f"config {args.config}: {cfg['name']} B={B} {D}x{H}x{W} C={C} heads={heads} k={k} "
+                               f"{dtype}, fwd(phi,lse)+bwd(dQ,dK)",
+                   "kernel_path": "generic" if args.generic else "auto",
+                   "stats_from_forward": have_stats},
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "fwd_ms": round(t_fwd, 4), "bwd_ms": round(t_bwd, 4),
+        "hbm_gbs_fwd_bwd": round((fwd_bytes + bwd_bytes) / ((t_fwd + t_bwd) * 1e-3) / 1e9, 1),
+        "hbm_frac_fwd_bwd": round((fwd_bytes + bwd_bytes) / ((t_fwd + t_bwd) * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+        "hbm_gbs_fwd": round(fwd_bytes / (t_fwd * 1e-3) / 1e9, 1),
+        "hbm_gbs_bwd": round(bwd_bytes / (t_bwd * 1e-3) / 1e9, 1),
+        "pairs_per_s": round(value * k ** 3, 1),
+        "device_copy_gbs": round(copy_gbs, 1),
+        "warp": {"ms": round(t_warp, 4), "gbs": round(warp_bytes / (t_warp * 1e-3) / 1e9, 1)},
+        "input_gen_s": round(t_gen, 1),
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,120 @@
+/* libmodet -- the ModeT motion-decomposition operator on AMD MI355X (gfx950).
+ *
+ * C ABI.  Every pointer named Q, K, bias, phi, attn, lse, dphi, dQ, dK, dbias, src, field,
+ * out, workspace is a DEVICE pointer owned by the caller (for instance the storage of a
+ * torch tensor).  The library never allocates, frees or retains memory and never
+ * synchronises: work is enqueued on `stream` (a hipStream_t passed as void*; NULL is the
+ * default stream) and the call returns at once.  Inputs and outputs must not alias.
+ * All base pointers must be 16-byte aligned.
+ *
+ * Layout (row-major, last index fastest):
+ *   Q, K, dQ, dK, src, out : [B, D, H, W, C]      channels last; head s owns channels
+ *                                                 [s*d, (s+1)*d), d = C / heads
+ *   phi, dphi              : [B, D, H, W, heads, 3]   components ordered (D, H, W), voxel units
+ *   attn                   : [B, D, H, W, heads, k^3]
+ *   lse                    : [B, D, H, W, heads]
+ *   bias, dbias            : [heads, k^3]
+ *   window offset index    : j = ((a+r)*k + (b+r))*k + (c+r), offsets a,b,c in -r..r along
+ *                            D,H,W, r = (k-1)/2
+ *
+ * Every function returns MODET_OK or a negative MODET_ERR_* code; nothing throws or
+ * aborts.  All argument validation happens on the host before any HIP call.
+ */
+#ifndef MODET_H
+#define MODET_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { MODET_F32 = 0, MODET_BF16 = 1 } modet_dtype;
+
+enum {
+  MODET_OK = 0,
+  MODET_ERR_NULL = -1,        /* a required pointer is NULL */
+  MODET_ERR_SHAPE = -2,       /* extent < 1, C not divisible by heads, even k, odd extent with half-res field */
+  MODET_ERR_UNSUPPORTED = -3, /* dtype / k / head size outside what the kernels cover */
+  MODET_ERR_ALIGN = -4,       /* a pointer is not 16-byte aligned */
+  MODET_ERR_WORKSPACE = -5,   /* workspace missing or too small */
+  MODET_ERR_LAUNCH = -6       /* the HIP runtime reported an error at launch */
+};
+
+/* Forward pass: paper Section 3.3.1, Eq. 3 (neighbourhood attention) and Eq. 4-5 (sub-fields).
+ *
+ * For every voxel p of Q (features of the fixed image), every head s and every offset o of
+ * the k x k x k window:  l_o = scale * <Q[p, s], K[p+o, s]> + bias[s, o], where K (features
+ * of the moving image) is zero outside the volume and such a padded neighbour still takes
+ * part in the softmax with logit bias[s,o] (or 0).  w = softmax_o(l);
+ * phi[p, s, :] = sum_o w_o * o  (the constant offset grid V of Eq. 4 is never materialised).
+ *
+ *   Q, K   in   in_dtype (fp32, or bf16 bit patterns; accumulation is fp32 either way)
+ *   bias   in   nullable; NULL means all zeros (the paper's initial state of B)
+ *   phi    out  fp32, fully written
+ *   attn   out  nullable; the softmax weights w (fp32)
+ *   lse    out  nullable; log(sum_o exp(l_o)) in fp32 -- pass it to modet_bwd to save the
+ *               statistics pass there
+ *   k      odd, 1..7;  scale <= 0 selects 1/sqrt(d)  (scale = 1 is Eq. 3 exactly as printed)
+ */
+int modet_fwd(const void* Q, const void* K, const float* bias, float* phi, float* attn, float* lse,
+              int B, int D, int H, int W, int C, int heads, int k, float scale,
+              modet_dtype in_dtype, void* stream);
+
+/* Backward pass of Eq. 3-4 with respect to Q and K (and optionally B): the gradients the
+ * pairwise-optimisation loop of Section 3.1 / Eq. 1 needs every iteration.  With g = dphi:
+ *   dl_o(p,s) = w_o * (g.o - g.phi)
+ *   dQ[p, s]  = scale * sum_o dl_o(p,s) * K[p+o, s]          (in-bounds p+o only)
+ *   dK[q, s]  = scale * sum_o dl_o(q-o, s) * Q[q-o, s]        (in-bounds q-o only)
+ *   dbias[s,o] = sum_p dl_o(p,s)
+ * Softmax weights are recomputed from Q and K, never stored.
+ *
+ *   phi, lse   in   nullable, both or neither: the outputs of modet_fwd for the same inputs.
+ *                   When NULL the library recomputes them into `workspace`.
+ *   dQ, dK     out  fp32, fully overwritten (no zeroing by the caller needed)
+ *   dbias      out  nullable, fully overwritten
+ *   workspace       at least modet_bwd_workspace_bytes(...) bytes, 16-byte aligned; may be
+ *                   NULL when that size is 0
+ */
+int modet_bwd(const void* Q, const void* K, const float* bias, const float* dphi,
+              const float* phi, const float* lse, float* dQ, float* dK, float* dbias,
+              int B, int D, int H, int W, int C, int heads, int k, float scale,
+              modet_dtype in_dtype, void* workspace, size_t workspace_bytes, void* stream);
+
+/* Bytes of scratch modet_bwd needs.  have_stats != 0 means phi and lse will be passed in.
+ * Returns 0 for invalid shapes (modet_bwd itself reports the error). */
+size_t modet_bwd_workspace_bytes(int B, int D, int H, int W, int C, int heads, int k,
+                                 modet_dtype in_dtype, int have_stats);
+
+/* Trilinear feature warp between pyramid levels: paper Section 3.1 (the moving feature map
+ * of the next level is deformed by the upsampled total field before it enters ModeT).
+ *
+ *   out[b, p, c] = trilinear(src[b, :, c], p + u(p)),   zero outside the volume,
+ * integer coordinates are voxel centres, u in voxel units ordered (D, H, W).
+ *   field_half_res == 0:  field is [B, D, H, W, 3] and u(p) = field[b, p].
+ *   field_half_res == 1:  field is [B, D/2, H/2, W/2, 3] (D, H, W even) and
+ *       u(p) = 2 * trilinear(field, clamp((p + 0.5)/2 - 0.5, 0, size-1)): the 2x upsampling of
+ *       the coarser level's field fused into the warp, values doubled because they are in
+ *       voxel units of their own grid.
+ *   src, out in `dtype` (bf16 output is rounded to nearest even); field is fp32.
+ *   C must be a multiple of 4 (fp32) or 8 (bf16), or equal to 3 (fp32: warping a field).
+ */
+int modet_warp(const void* src, const float* field, void* out,
+               int B, int D, int H, int W, int C, int field_half_res,
+               modet_dtype dtype, void* stream);
+
+/* Kernel selection, for tests and profiling.  0 = automatic (LDS-tiled kernels where the
+ * shape is covered, generic otherwise), 1 = always the generic kernels.  Returns the
+ * previous value.  Process-wide, not thread safe. */
+int modet_set_kernel_path(int path);
+
+/* 1 if the (head size, k, dtype) combination runs on the LDS-tiled kernels under path 0. */
+int modet_has_tiled_kernels(int C, int heads, int k, modet_dtype in_dtype);
+
+const char* modet_status_string(int status);
+int modet_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MODET_H */

@@ -1,0 +1,148 @@
+// C ABI of libmodet: argument validation on the host (before any HIP call) and dispatch to the
+// kernels.  See include/modet.h for the contract of every entry point.
+#include "../../include/modet.h"
+#include "modet_common.hpp"
+
+#include <math.h>
+
+using namespace modet;
+
+namespace {
+
+int g_kernel_path = 0;   // 0 = automatic, 1 = generic kernels only
+
+inline bool misaligned(const void* p) { return p && (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+int check_op_shape(int B, int D, int H, int W, int C, int heads, int k, int dtype) {
+  if (B < 1 || D < 1 || H < 1 || W < 1 || C < 1 || heads < 1) return MODET_ERR_SHAPE;
+  if (C % heads != 0) return MODET_ERR_SHAPE;
+  if (k < 1 || (k & 1) == 0) return MODET_ERR_SHAPE;
+  if (k > 7) return MODET_ERR_UNSUPPORTED;
+  if (dtype != MODET_F32 && dtype != MODET_BF16) return MODET_ERR_UNSUPPORTED;
+  // 32-bit lane indexing inside a batch item and over windows
+  const long long nvox = (long long)B * D * H * W;
+  if (nvox * C >= (1LL << 31) || nvox * heads * 3 >= (1LL << 31)) return MODET_ERR_UNSUPPORTED;
+  return MODET_OK;
+}
+
+Geo make_geo(int B, int D, int H, int W, int C, int heads, int k, float scale) {
+  Geo g;
+  g.B = B; g.D = D; g.H = H; g.W = W; g.C = C; g.heads = heads; g.k = k;
+  g.r = (k - 1) / 2; g.d = C / heads; g.k3 = k * k * k;
+  g.nvox = (long long)B * D * H * W;
+  g.nvn = g.nvox * heads;
+  g.scale = scale > 0.f ? scale : 1.0f / sqrtf((float)g.d);
+  return g;
+}
+
+inline size_t round16(size_t n) { return (n + 15) & ~(size_t)15; }
+
+}  // namespace
+
+extern "C" {
+
+int modet_fwd(const void* Q, const void* K, const float* bias, float* phi, float* attn, float* lse,
+              int B, int D, int H, int W, int C, int heads, int k, float scale,
+              modet_dtype in_dtype, void* stream) {
+  if (!Q || !K || !phi) return MODET_ERR_NULL;
+  int rc = check_op_shape(B, D, H, W, C, heads, k, (int)in_dtype);
+  if (rc != MODET_OK) return rc;
+  if (misaligned(Q) || misaligned(K) || misaligned(bias) || misaligned(phi) || misaligned(attn) || misaligned(lse))
+    return MODET_ERR_ALIGN;
+  const Geo g = make_geo(B, D, H, W, C, heads, k, scale);
+  hipStream_t st = (hipStream_t)stream;
+  hipError_t e;
+  if (g_kernel_path == 0 && !attn && tiled_supported(g.d, k, (int)in_dtype))
+    e = launch_fwd_tiled(g, (int)in_dtype, Q, K, bias, phi, lse, st);
+  else
+    e = launch_fwd_generic(g, (int)in_dtype, Q, K, bias, phi, attn, lse, st);
+  return e == hipSuccess ? MODET_OK : MODET_ERR_LAUNCH;
+}
+
+size_t modet_bwd_workspace_bytes(int B, int D, int H, int W, int C, int heads, int k,
+                                 modet_dtype in_dtype, int have_stats) {
+  if (check_op_shape(B, D, H, W, C, heads, k, (int)in_dtype) != MODET_OK) return 0;
+  if (have_stats) return 0;
+  const size_t nvn = (size_t)B * D * H * W * heads;
+  return round16(nvn * 3 * sizeof(float)) + round16(nvn * sizeof(float));   // phi, lse
+}
+
+int modet_bwd(const void* Q, const void* K, const float* bias, const float* dphi,
+              const float* phi, const float* lse, float* dQ, float* dK, float* dbias,
+              int B, int D, int H, int W, int C, int heads, int k, float scale,
+              modet_dtype in_dtype, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!Q || !K || !dphi || !dQ || !dK) return MODET_ERR_NULL;
+  if ((phi == nullptr) != (lse == nullptr)) return MODET_ERR_NULL;
+  int rc = check_op_shape(B, D, H, W, C, heads, k, (int)in_dtype);
+  if (rc != MODET_OK) return rc;
+  if (misaligned(Q) || misaligned(K) || misaligned(bias) || misaligned(dphi) || misaligned(phi) ||
+      misaligned(lse) || misaligned(dQ) || misaligned(dK) || misaligned(dbias) || misaligned(workspace))
+    return MODET_ERR_ALIGN;
+  const size_t need = modet_bwd_workspace_bytes(B, D, H, W, C, heads, k, in_dtype, phi != nullptr);
+  if (need > 0 && (!workspace || workspace_bytes < need)) return MODET_ERR_WORKSPACE;
+  const Geo g = make_geo(B, D, H, W, C, heads, k, scale);
+  hipStream_t st = (hipStream_t)stream;
+  const bool tiled = g_kernel_path == 0 && tiled_supported(g.d, k, (int)in_dtype);
+  hipError_t e = hipSuccess;
+  if (!phi) {   // statistics pass: the forward kernel writes phi and lse into the workspace
+    float* wphi = (float*)workspace;
+    float* wlse = (float*)((char*)workspace + round16((size_t)g.nvn * 3 * sizeof(float)));
+    e = tiled ? launch_fwd_tiled(g, (int)in_dtype, Q, K, bias, wphi, wlse, st)
+              : launch_fwd_generic(g, (int)in_dtype, Q, K, bias, wphi, nullptr, wlse, st);
+    if (e != hipSuccess) return MODET_ERR_LAUNCH;
+    phi = wphi;
+    lse = wlse;
+  }
+  e = tiled ? launch_bwd_tiled(g, (int)in_dtype, Q, K, bias, dphi, phi, lse, dQ, dK, st)
+            : launch_bwd_generic(g, (int)in_dtype, Q, K, bias, dphi, phi, lse, dQ, dK, st);
+  if (e != hipSuccess) return MODET_ERR_LAUNCH;
+  if (dbias) {
+    e = launch_dbias(g, (int)in_dtype, Q, K, bias, dphi, phi, lse, dbias, st);
+    if (e != hipSuccess) return MODET_ERR_LAUNCH;
+  }
+  return MODET_OK;
+}
+
+int modet_warp(const void* src, const float* field, void* out,
+               int B, int D, int H, int W, int C, int field_half_res,
+               modet_dtype dtype, void* stream) {
+  if (!src || !field || !out) return MODET_ERR_NULL;
+  if (B < 1 || D < 1 || H < 1 || W < 1 || C < 1) return MODET_ERR_SHAPE;
+  if (field_half_res != 0 && field_half_res != 1) return MODET_ERR_SHAPE;
+  if (field_half_res && ((D | H | W) & 1)) return MODET_ERR_SHAPE;
+  if (dtype != MODET_F32 && dtype != MODET_BF16) return MODET_ERR_UNSUPPORTED;
+  if (dtype == MODET_BF16 ? (C % 8 != 0) : (C % 4 != 0 && C != 3)) return MODET_ERR_UNSUPPORTED;
+  if ((long long)B * D * H * W * C >= (1LL << 31)) return MODET_ERR_UNSUPPORTED;
+  if (misaligned(src) || misaligned(field) || misaligned(out)) return MODET_ERR_ALIGN;
+  hipError_t e = launch_warp(src, field, out, B, D, H, W, C, field_half_res, (int)dtype, (hipStream_t)stream);
+  return e == hipSuccess ? MODET_OK : MODET_ERR_LAUNCH;
+}
+
+int modet_set_kernel_path(int path) {
+  int old = g_kernel_path;
+  g_kernel_path = path == 1 ? 1 : 0;
+  return old;
+}
+
+int modet_has_tiled_kernels(int C, int heads, int k, modet_dtype in_dtype) {
+  if (C < 1 || heads < 1 || C % heads != 0) return 0;
+  return tiled_supported(C / heads, k, (int)in_dtype) ? 1 : 0;
+}
+
+const char* modet_status_string(int status) {
+  switch (status) {
+    case MODET_OK: return "ok";
+    case MODET_ERR_NULL: return "a required pointer is NULL (or only one of phi/lse was given)";
+    case MODET_ERR_SHAPE: return "invalid shape: extents must be >= 1, C divisible by heads, k odd, "
+                                 "even extents for a half-resolution field";
+    case MODET_ERR_UNSUPPORTED: return "unsupported dtype, window size, channel count or tensor size";
+    case MODET_ERR_ALIGN: return "pointers must be 16-byte aligned";
+    case MODET_ERR_WORKSPACE: return "workspace missing or smaller than modet_bwd_workspace_bytes()";
+    case MODET_ERR_LAUNCH: return "HIP reported an error when launching a kernel";
+    default: return "unknown status";
+  }
+}
+
+int modet_version(void) { return 100; }
+
+}  // extern "C"

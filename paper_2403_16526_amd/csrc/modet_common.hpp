@@ -1,0 +1,49 @@
+// Shared declarations of the libmodet HIP sources (kernels + C ABI).  gfx950 only.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace modet {
+
+struct Geo {
+  int B, D, H, W, C, heads, k, r, d, k3;
+  long long nvox;   // B*D*H*W
+  long long nvn;    // nvox*heads
+  float scale;      // multiplies the dot product (natural-log units)
+};
+
+typedef uint16_t bf16_t;   // bfloat16 bit pattern
+
+__device__ __forceinline__ float ldf(const float* p, long long i) { return p[i]; }
+__device__ __forceinline__ float ldf(const bf16_t* p, long long i) {
+  return __uint_as_float(((uint32_t)p[i]) << 16);
+}
+
+// fp32 -> bf16 bits, round to nearest even (finite inputs)
+__device__ __forceinline__ bf16_t f2bf(float f) {
+  uint32_t u = __float_as_uint(f);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (bf16_t)(u >> 16);
+}
+
+// ---- launchers (each returns hipGetLastError() of its launches) ------------------------
+// generic kernels: any head size, k in {1,3,5,7}, fp32 / bf16 inputs
+hipError_t launch_fwd_generic(const Geo& g, int dtype, const void* Q, const void* K, const float* bias,
+                              float* phi, float* attn, float* lse, hipStream_t st);
+hipError_t launch_bwd_generic(const Geo& g, int dtype, const void* Q, const void* K, const float* bias,
+                              const float* dphi, const float* phi, const float* lse, float* dQ, float* dK,
+                              hipStream_t st);
+hipError_t launch_dbias(const Geo& g, int dtype, const void* Q, const void* K, const float* bias,
+                        const float* dphi, const float* phi, const float* lse, float* dbias, hipStream_t st);
+hipError_t launch_warp(const void* src, const float* field, void* out, int B, int D, int H, int W, int C,
+                       int half, int dtype, hipStream_t st);
+
+// LDS-tiled kernels (head size 8)
+bool tiled_supported(int d, int k, int dtype);
+hipError_t launch_fwd_tiled(const Geo& g, int dtype, const void* Q, const void* K, const float* bias,
+                            float* phi, float* lse, hipStream_t st);
+hipError_t launch_bwd_tiled(const Geo& g, int dtype, const void* Q, const void* K, const float* bias,
+                            const float* dphi, const float* phi, const float* lse, float* dQ, float* dK,
+                            hipStream_t st);
+
+}  // namespace modet

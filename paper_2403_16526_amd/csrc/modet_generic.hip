@@ -1,0 +1,244 @@
+// Generic ModeT kernels: one lane per (voxel, head) window, keys read straight from global
+// memory.  They cover every head size, k in {1,3,5,7} and both input types, produce the
+// optional attention map, and serve as the fallback for shapes the LDS-tiled kernels do
+// not cover.  Paper: Section 3.3.1, Eq. 3 (scores + softmax) and Eq. 4-5 (weighted offsets);
+// the backward is the derivative of those two equations.
+#include "modet_common.hpp"
+
+namespace modet {
+namespace {
+
+constexpr int kThreads = 256;
+
+__device__ __forceinline__ void decode_vn(const Geo& g, long long vn, int& b, int& z, int& y, int& x, int& s,
+                                          long long& v) {
+  s = (int)(vn % g.heads);
+  v = vn / g.heads;
+  long long t = v;
+  x = (int)(t % g.W); t /= g.W;
+  y = (int)(t % g.H); t /= g.H;
+  z = (int)(t % g.D);
+  b = (int)(t / g.D);
+}
+
+__device__ __forceinline__ bool inside(const Geo& g, int z, int y, int x) {
+  return (unsigned)z < (unsigned)g.D && (unsigned)y < (unsigned)g.H && (unsigned)x < (unsigned)g.W;
+}
+
+template <class T>
+__device__ __forceinline__ float dot_d(const T* q, const T* kk, int d) {
+  float acc = 0.f;
+  for (int c = 0; c < d; ++c) acc = fmaf(ldf(q, c), ldf(kk, c), acc);
+  return acc;
+}
+
+// Eq. 3 + Eq. 4 for one window per lane; online softmax (running max) so no logit is stored.
+template <class T>
+__global__ void __launch_bounds__(kThreads)
+fwd_generic_kernel(Geo g, const T* __restrict__ Q, const T* __restrict__ K, const float* __restrict__ bias,
+                   float* __restrict__ phi, float* __restrict__ attn, float* __restrict__ lse) {
+  long long vn = (long long)blockIdx.x * kThreads + threadIdx.x;
+  if (vn >= g.nvn) return;
+  int b, z, y, x, s; long long v;
+  decode_vn(g, vn, b, z, y, x, s, v);
+  const T* q = Q + v * g.C + s * g.d;
+  const int r = g.r;
+  float m = -INFINITY, Z = 0.f, S0 = 0.f, S1 = 0.f, S2 = 0.f;
+  int j = 0;
+  for (int a = -r; a <= r; ++a)
+    for (int bb = -r; bb <= r; ++bb)
+      for (int c = -r; c <= r; ++c, ++j) {
+        float l = bias ? bias[s * g.k3 + j] : 0.f;
+        if (inside(g, z + a, y + bb, x + c)) {
+          long long nb = v + ((long long)a * g.H + bb) * g.W + c;
+          l = fmaf(g.scale, dot_d(q, K + nb * g.C + s * g.d, g.d), l);
+        }
+        if (l > m) {
+          float al = expf(m - l);
+          Z *= al; S0 *= al; S1 *= al; S2 *= al;
+          m = l;
+        }
+        float e = expf(l - m);
+        Z += e; S0 = fmaf(e, (float)a, S0); S1 = fmaf(e, (float)bb, S1); S2 = fmaf(e, (float)c, S2);
+      }
+  float inv = 1.f / Z;
+  phi[vn * 3 + 0] = S0 * inv;
+  phi[vn * 3 + 1] = S1 * inv;
+  phi[vn * 3 + 2] = S2 * inv;
+  if (lse) lse[vn] = m + logf(Z);
+  if (attn) {
+    j = 0;
+    for (int a = -r; a <= r; ++a)
+      for (int bb = -r; bb <= r; ++bb)
+        for (int c = -r; c <= r; ++c, ++j) {
+          float l = bias ? bias[s * g.k3 + j] : 0.f;
+          if (inside(g, z + a, y + bb, x + c)) {
+            long long nb = v + ((long long)a * g.H + bb) * g.W + c;
+            l = fmaf(g.scale, dot_d(q, K + nb * g.C + s * g.d, g.d), l);
+          }
+          attn[vn * g.k3 + j] = expf(l - m) * inv;
+        }
+  }
+}
+
+// dQ (KEYSIDE = false): lane owns CH channels of one head of query voxel p and walks its window.
+// dK (KEYSIDE = true) : lane owns CH channels of key voxel q and walks the queries p = q - o that
+//                       see it under offset o.  Weights come from w = exp(l - lse[p]).
+template <class T, int CH, bool KEYSIDE>
+__global__ void __launch_bounds__(kThreads)
+grad_generic_kernel(Geo g, const T* __restrict__ Q, const T* __restrict__ K, const float* __restrict__ bias,
+                    const float* __restrict__ dphi, const float* __restrict__ phi,
+                    const float* __restrict__ lse, float* __restrict__ out) {
+  const int nchunk = g.d / CH;
+  long long idx = (long long)blockIdx.x * kThreads + threadIdx.x;
+  if (idx >= g.nvn * nchunk) return;
+  const int chunk = (int)(idx % nchunk);
+  const long long vn = idx / nchunk;
+  int b, z, y, x, s; long long v;
+  decode_vn(g, vn, b, z, y, x, s, v);
+  const int r = g.r, c0 = s * g.d + chunk * CH;
+  float acc[CH];
+#pragma unroll
+  for (int i = 0; i < CH; ++i) acc[i] = 0.f;
+  float g0 = 0.f, g1 = 0.f, g2 = 0.f, gphi = 0.f, ls = 0.f;
+  if (!KEYSIDE) {
+    g0 = dphi[vn * 3]; g1 = dphi[vn * 3 + 1]; g2 = dphi[vn * 3 + 2];
+    gphi = g0 * phi[vn * 3] + g1 * phi[vn * 3 + 1] + g2 * phi[vn * 3 + 2];
+    ls = lse[vn];
+  }
+  int j = 0;
+  for (int a = -r; a <= r; ++a)
+    for (int bb = -r; bb <= r; ++bb)
+      for (int c = -r; c <= r; ++c, ++j) {
+        const int oz = KEYSIDE ? z - a : z + a, oy = KEYSIDE ? y - bb : y + bb, ox = KEYSIDE ? x - c : x + c;
+        if (!inside(g, oz, oy, ox)) continue;   // a padded key has no gradient and feeds none
+        const long long ov = v + (KEYSIDE ? -1 : 1) * (((long long)a * g.H + bb) * g.W + c);
+        const long long pv = KEYSIDE ? ov : v;    // query voxel of the pair
+        const long long qv = KEYSIDE ? v : ov;    // key voxel of the pair
+        if (KEYSIDE) {
+          const long long pvn = pv * g.heads + s;
+          g0 = dphi[pvn * 3]; g1 = dphi[pvn * 3 + 1]; g2 = dphi[pvn * 3 + 2];
+          gphi = g0 * phi[pvn * 3] + g1 * phi[pvn * 3 + 1] + g2 * phi[pvn * 3 + 2];
+          ls = lse[pvn];
+        }
+        float l = bias ? bias[s * g.k3 + j] : 0.f;
+        l = fmaf(g.scale, dot_d(Q + pv * g.C + s * g.d, K + qv * g.C + s * g.d, g.d), l);
+        const float w = expf(l - ls);
+        const float dl = w * (g0 * (float)a + g1 * (float)bb + g2 * (float)c - gphi);
+        const T* other = KEYSIDE ? Q + pv * g.C + c0 : K + qv * g.C + c0;
+#pragma unroll
+        for (int i = 0; i < CH; ++i) acc[i] = fmaf(dl, ldf(other, i), acc[i]);
+      }
+#pragma unroll
+  for (int i = 0; i < CH; ++i) out[v * g.C + c0 + i] = g.scale * acc[i];
+}
+
+__global__ void fill_zero_kernel(float* p, int n) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = 0.f;
+}
+
+// dbias[s, j] = sum over voxels of dl_j(p, s): per-block partial sums in LDS, one global atomic per
+// entry and block.  Accumulation order is not fixed, so the result is reproducible only to rounding.
+template <class T>
+__global__ void __launch_bounds__(kThreads)
+dbias_kernel(Geo g, const T* __restrict__ Q, const T* __restrict__ K, const float* __restrict__ bias,
+             const float* __restrict__ dphi, const float* __restrict__ phi, const float* __restrict__ lse,
+             float* __restrict__ dbias, long long per_block) {
+  extern __shared__ float part[];
+  const int nent = g.heads * g.k3;
+  for (int i = threadIdx.x; i < nent; i += kThreads) part[i] = 0.f;
+  __syncthreads();
+  const long long lo = (long long)blockIdx.x * per_block;
+  const long long hi = lo + per_block < g.nvn ? lo + per_block : g.nvn;
+  const int r = g.r;
+  for (long long vn = lo + threadIdx.x; vn < hi; vn += kThreads) {
+    int b, z, y, x, s; long long v;
+    decode_vn(g, vn, b, z, y, x, s, v);
+    const float g0 = dphi[vn * 3], g1 = dphi[vn * 3 + 1], g2 = dphi[vn * 3 + 2];
+    const float gphi = g0 * phi[vn * 3] + g1 * phi[vn * 3 + 1] + g2 * phi[vn * 3 + 2];
+    const float ls = lse[vn];
+    const T* q = Q + v * g.C + s * g.d;
+    int j = 0;
+    for (int a = -r; a <= r; ++a)
+      for (int bb = -r; bb <= r; ++bb)
+        for (int c = -r; c <= r; ++c, ++j) {
+          float l = bias ? bias[s * g.k3 + j] : 0.f;
+          if (inside(g, z + a, y + bb, x + c)) {
+            long long nb = v + ((long long)a * g.H + bb) * g.W + c;
+            l = fmaf(g.scale, dot_d(q, K + nb * g.C + s * g.d, g.d), l);
+          }
+          const float dl = expf(l - ls) * (g0 * (float)a + g1 * (float)bb + g2 * (float)c - gphi);
+          atomicAdd(&part[s * g.k3 + j], dl);
+        }
+  }
+  __syncthreads();
+  for (int i = threadIdx.x; i < nent; i += kThreads) atomicAdd(&dbias[i], part[i]);
+}
+
+inline unsigned blocks_for(long long n) { return (unsigned)((n + kThreads - 1) / kThreads); }
+
+template <class T, bool KEYSIDE>
+void launch_grad(const Geo& g, const T* Q, const T* K, const float* bias, const float* dphi, const float* phi,
+                 const float* lse, float* out, hipStream_t st) {
+  int ch = 1;
+  for (int c : {8, 6, 4, 3, 2}) if (g.d % c == 0) { ch = c; break; }
+  const long long n = g.nvn * (g.d / ch);
+  dim3 grid(blocks_for(n)), block(kThreads);
+#define MODET_GRAD(CH_) \
+  hipLaunchKernelGGL((grad_generic_kernel<T, CH_, KEYSIDE>), grid, block, 0, st, g, Q, K, bias, dphi, phi, lse, out)
+  switch (ch) {
+    case 8: MODET_GRAD(8); break;
+    case 6: MODET_GRAD(6); break;
+    case 4: MODET_GRAD(4); break;
+    case 3: MODET_GRAD(3); break;
+    case 2: MODET_GRAD(2); break;
+    default: MODET_GRAD(1); break;
+  }
+#undef MODET_GRAD
+}
+
+}  // namespace
+
+hipError_t launch_fwd_generic(const Geo& g, int dtype, const void* Q, const void* K, const float* bias,
+                              float* phi, float* attn, float* lse, hipStream_t st) {
+  dim3 grid(blocks_for(g.nvn)), block(kThreads);
+  if (dtype == 0)
+    hipLaunchKernelGGL((fwd_generic_kernel<float>), grid, block, 0, st, g, (const float*)Q, (const float*)K, bias,
+                       phi, attn, lse);
+  else
+    hipLaunchKernelGGL((fwd_generic_kernel<bf16_t>), grid, block, 0, st, g, (const bf16_t*)Q, (const bf16_t*)K,
+                       bias, phi, attn, lse);
+  return hipGetLastError();
+}
+
+hipError_t launch_bwd_generic(const Geo& g, int dtype, const void* Q, const void* K, const float* bias,
+                              const float* dphi, const float* phi, const float* lse, float* dQ, float* dK,
+                              hipStream_t st) {
+  if (dtype == 0) {
+    launch_grad<float, false>(g, (const float*)Q, (const float*)K, bias, dphi, phi, lse, dQ, st);
+    launch_grad<float, true>(g, (const float*)Q, (const float*)K, bias, dphi, phi, lse, dK, st);
+  } else {
+    launch_grad<bf16_t, false>(g, (const bf16_t*)Q, (const bf16_t*)K, bias, dphi, phi, lse, dQ, st);
+    launch_grad<bf16_t, true>(g, (const bf16_t*)Q, (const bf16_t*)K, bias, dphi, phi, lse, dK, st);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_dbias(const Geo& g, int dtype, const void* Q, const void* K, const float* bias,
+                        const float* dphi, const float* phi, const float* lse, float* dbias, hipStream_t st) {
+  const int nent = g.heads * g.k3;
+  hipLaunchKernelGGL(fill_zero_kernel, dim3((nent + 255) / 256), dim3(256), 0, st, dbias, nent);
+  long long per_block = 8192;
+  unsigned nblk = (unsigned)((g.nvn + per_block - 1) / per_block);
+  size_t shm = sizeof(float) * (size_t)nent;
+  if (dtype == 0)
+    hipLaunchKernelGGL((dbias_kernel<float>), dim3(nblk), dim3(kThreads), shm, st, g, (const float*)Q,
+                       (const float*)K, bias, dphi, phi, lse, dbias, per_block);
+  else
+    hipLaunchKernelGGL((dbias_kernel<bf16_t>), dim3(nblk), dim3(kThreads), shm, st, g, (const bf16_t*)Q,
+                       (const bf16_t*)K, bias, dphi, phi, lse, dbias, per_block);
+  return hipGetLastError();
+}
+
+}  // namespace modet

@@ -1,0 +1,134 @@
+// Trilinear feature warp between pyramid levels (paper Section 3.1): the moving features of the
+// next level are resampled at p + u(p), where u is the total displacement field, either given at
+// this resolution or given at half resolution and upsampled x2 (values doubled) on the fly.
+// One lane handles VEC consecutive channels of one voxel, so a wavefront reads whole contiguous
+// channel rows of each of the 8 corners; the work is pure gather bandwidth.
+#include "modet_common.hpp"
+
+namespace modet {
+namespace {
+
+constexpr int kThreads = 256;
+
+template <class T, int VEC> struct Vec;
+template <> struct Vec<float, 4> {
+  static __device__ __forceinline__ void load(const float* p, float* v) {
+    float4 t = *reinterpret_cast<const float4*>(p);
+    v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+  }
+  static __device__ __forceinline__ void store(float* p, const float* v) {
+    *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
+  }
+};
+template <> struct Vec<float, 1> {
+  static __device__ __forceinline__ void load(const float* p, float* v) { v[0] = p[0]; }
+  static __device__ __forceinline__ void store(float* p, const float* v) { p[0] = v[0]; }
+};
+template <> struct Vec<bf16_t, 8> {
+  static __device__ __forceinline__ void load(const bf16_t* p, float* v) {
+    uint4 t = *reinterpret_cast<const uint4*>(p);
+    uint32_t w[4] = {t.x, t.y, t.z, t.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      v[2 * i] = __uint_as_float(w[i] << 16);
+      v[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u);
+    }
+  }
+  static __device__ __forceinline__ void store(bf16_t* p, const float* v) {
+    uint32_t w[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) w[i] = (uint32_t)f2bf(v[2 * i]) | ((uint32_t)f2bf(v[2 * i + 1]) << 16);
+    *reinterpret_cast<uint4*>(p) = make_uint4(w[0], w[1], w[2], w[3]);
+  }
+};
+
+// displacement at fine voxel (z,y,x) from the half-resolution field fc[Dc,Hc,Wc,3] of one batch item:
+// the fine voxel centre sits at coarse coordinate (i + 0.5)/2 - 0.5 = i/2 - 0.25, clamped to the grid.
+__device__ __forceinline__ void upsampled_disp(const float* __restrict__ fc, int Dc, int Hc, int Wc, int z, int y,
+                                               int x, float* u) {
+  float cz = fminf(fmaxf(0.5f * z - 0.25f, 0.f), (float)(Dc - 1));
+  float cy = fminf(fmaxf(0.5f * y - 0.25f, 0.f), (float)(Hc - 1));
+  float cx = fminf(fmaxf(0.5f * x - 0.25f, 0.f), (float)(Wc - 1));
+  int z0 = (int)cz, y0 = (int)cy, x0 = (int)cx;       // coordinates are >= 0: truncation is floor
+  float tz = cz - z0, ty = cy - y0, tx = cx - x0;
+  int z1 = min(z0 + 1, Dc - 1), y1 = min(y0 + 1, Hc - 1), x1 = min(x0 + 1, Wc - 1);  // weight 0 when clamped
+  u[0] = u[1] = u[2] = 0.f;
+#pragma unroll
+  for (int c = 0; c < 8; ++c) {
+    int zi = (c & 4) ? z1 : z0, yi = (c & 2) ? y1 : y0, xi = (c & 1) ? x1 : x0;
+    float w = ((c & 4) ? tz : 1.f - tz) * ((c & 2) ? ty : 1.f - ty) * ((c & 1) ? tx : 1.f - tx);
+    const float* p = fc + (((long long)zi * Hc + yi) * Wc + xi) * 3;
+    u[0] = fmaf(w, p[0], u[0]); u[1] = fmaf(w, p[1], u[1]); u[2] = fmaf(w, p[2], u[2]);
+  }
+  u[0] *= 2.f; u[1] *= 2.f; u[2] *= 2.f;
+}
+
+template <class T, int VEC, bool HALF>
+__global__ void __launch_bounds__(kThreads)
+warp_kernel(const T* __restrict__ src, const float* __restrict__ field, T* __restrict__ out, int B, int D, int H,
+            int W, int C, long long total) {
+  long long idx = (long long)blockIdx.x * kThreads + threadIdx.x;
+  if (idx >= total) return;
+  const int nchunk = C / VEC;
+  const int chunk = (int)(idx % nchunk);
+  long long v = idx / nchunk, t = v;
+  const int x = (int)(t % W); t /= W;
+  const int y = (int)(t % H); t /= H;
+  const int z = (int)(t % D);
+  const int b = (int)(t / D);
+  float u[3];
+  if (HALF) {
+    const int Dc = D / 2, Hc = H / 2, Wc = W / 2;
+    upsampled_disp(field + (long long)b * Dc * Hc * Wc * 3, Dc, Hc, Wc, z, y, x, u);
+  } else {
+    u[0] = field[v * 3]; u[1] = field[v * 3 + 1]; u[2] = field[v * 3 + 2];
+  }
+  // split u into integer and fractional parts first: the fraction is then exact in fp32
+  const float fz = floorf(u[0]), fy = floorf(u[1]), fx = floorf(u[2]);
+  const float tz = u[0] - fz, ty = u[1] - fy, tx = u[2] - fx;
+  // clamp the integer part far outside the volume so z + fz cannot overflow an int
+  const int z0 = z + (int)fminf(fmaxf(fz, -1.0e6f), 1.0e6f);
+  const int y0 = y + (int)fminf(fmaxf(fy, -1.0e6f), 1.0e6f);
+  const int x0 = x + (int)fminf(fmaxf(fx, -1.0e6f), 1.0e6f);
+  const T* sb = src + (long long)b * D * H * W * C + chunk * VEC;
+  float acc[VEC];
+#pragma unroll
+  for (int i = 0; i < VEC; ++i) acc[i] = 0.f;
+#pragma unroll
+  for (int c = 0; c < 8; ++c) {
+    const int zi = z0 + ((c >> 2) & 1), yi = y0 + ((c >> 1) & 1), xi = x0 + (c & 1);
+    if ((unsigned)zi < (unsigned)D && (unsigned)yi < (unsigned)H && (unsigned)xi < (unsigned)W) {
+      const float w = ((c & 4) ? tz : 1.f - tz) * ((c & 2) ? ty : 1.f - ty) * ((c & 1) ? tx : 1.f - tx);
+      float val[VEC];
+      Vec<T, VEC>::load(sb + (((long long)zi * H + yi) * W + xi) * C, val);
+#pragma unroll
+      for (int i = 0; i < VEC; ++i) acc[i] = fmaf(w, val[i], acc[i]);
+    }
+  }
+  Vec<T, VEC>::store(out + v * C + chunk * VEC, acc);
+}
+
+template <class T, int VEC>
+hipError_t launch_t(const void* src, const float* field, void* out, int B, int D, int H, int W, int C, int half,
+                    hipStream_t st) {
+  const long long total = (long long)B * D * H * W * (C / VEC);
+  dim3 grid((unsigned)((total + kThreads - 1) / kThreads)), block(kThreads);
+  if (half)
+    hipLaunchKernelGGL((warp_kernel<T, VEC, true>), grid, block, 0, st, (const T*)src, field, (T*)out, B, D, H, W,
+                       C, total);
+  else
+    hipLaunchKernelGGL((warp_kernel<T, VEC, false>), grid, block, 0, st, (const T*)src, field, (T*)out, B, D, H, W,
+                       C, total);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_warp(const void* src, const float* field, void* out, int B, int D, int H, int W, int C,
+                       int half, int dtype, hipStream_t st) {
+  if (dtype == 1) return launch_t<bf16_t, 8>(src, field, out, B, D, H, W, C, half, st);
+  if (C % 4 == 0) return launch_t<float, 4>(src, field, out, B, D, H, W, C, half, st);
+  return launch_t<float, 1>(src, field, out, B, D, H, W, C, half, st);
+}
+
+}  // namespace modet

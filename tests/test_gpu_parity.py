@@ -1,0 +1,176 @@
+"""GPU parity: libmodet (through the C ABI binding) against the CPU oracle, element by element on
+small seeded cases that span several tiles and ragged tails, plus the degenerate shapes."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2403_16526_amd import synth
+from parity_util import assert_close, up
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def modet():
+    assert torch.cuda.is_available(), "needs the MI355X"
+    from paper_2403_16526_amd import modet as m
+    return m
+
+
+# (B, D, H, W, C, heads, k, dtype)
+SMALL = [
+    (1, 16, 16, 16, 8, 1, 3, "f32"),        # config 1
+    (2, 9, 19, 70, 8, 1, 3, "f32"),         # ragged in every axis, W spans two 64-lane rows
+    (1, 5, 11, 131, 8, 1, 3, "f32"),
+    (1, 7, 13, 37, 32, 4, 3, "f32"),        # config 2 style heads
+    (1, 6, 10, 21, 64, 8, 3, "f32"),        # coarsest pyramid level style
+    (1, 12, 9, 23, 16, 2, 3, "f32"),
+    (1, 9, 12, 21, 16, 2, 5, "bf16"),       # config 5 style
+    (2, 6, 21, 40, 8, 1, 5, "f32"),
+    (1, 7, 8, 9, 8, 1, 3, "bf16"),
+    (1, 1, 1, 1, 8, 1, 3, "f32"),           # a single voxel: every neighbour is padding
+    (1, 2, 3, 1, 8, 1, 3, "f32"),           # thinner than the window
+    (1, 1, 40, 3, 16, 2, 5, "f32"),
+    (1, 5, 6, 7, 12, 2, 3, "f32"),          # the paper's small model: 6 channels per head
+    (1, 4, 5, 6, 24, 2, 3, "bf16"),         # the paper's large model: 12 channels per head
+    (1, 4, 5, 6, 8, 1, 1, "f32"),           # k = 1
+    (1, 5, 6, 9, 4, 1, 7, "f32"),
+]
+
+
+def run_case(modet, shape, path, with_bias=False, stats="pass"):
+    B, D, H, W, C, heads, k, dtype = shape
+    keys = "displaced" if min(D, H, W) >= 4 else "iid"
+    c = synth.make_case(B, D, H, W, C, heads, k, dtype=dtype, keys=keys, m=(k - 1) // 2, seed=1000 + D * H + W)
+    bias = (0.5 * synth.normal(77, 0, (heads, k ** 3))).astype(np.float32) if with_bias else None
+    ref_phi, ref_attn, ref_lse = oracle.modet_fwd(c["Q"], c["K"], heads, k, bias=bias, dtype=dtype, want_attn=True,
+                                                  want_lse=True)
+    ref_dQ, ref_dK, ref_db = oracle.modet_bwd(c["Q"], c["K"], c["dphi"], heads, k, bias=bias, dtype=dtype,
+                                              form="scatter", want_dbias=True)
+    Q, K, g, tb = up(c["Q"], dtype), up(c["K"], dtype), up(c["dphi"]), up(bias)
+    old = modet.modet_set_kernel_path(path)
+    try:
+        phi, lse = modet.modet_fwd(Q, K, heads, k, bias=tb, want_lse=True)
+        phi2, attn = modet.modet_fwd(Q, K, heads, k, bias=tb, want_attn=True)
+        if stats == "pass":
+            dQ, dK, db = modet.modet_bwd(Q, K, g, heads, k, bias=tb, phi=phi, lse=lse, want_dbias=True)
+        else:
+            dQ, dK, db = modet.modet_bwd(Q, K, g, heads, k, bias=tb, want_dbias=True)
+        torch.cuda.synchronize()
+    finally:
+        modet.modet_set_kernel_path(old)
+    tag = f"{shape} path={path} bias={with_bias} stats={stats}"
+    assert_close(phi.cpu().numpy(), ref_phi, dtype, "phi " + tag)
+    assert_close(phi2.cpu().numpy(), ref_phi, dtype, "phi(attn call) " + tag)
+    assert_close(attn.cpu().numpy(), ref_attn, dtype, "attn " + tag)
+    assert_close(lse.cpu().numpy(), ref_lse, dtype, "lse " + tag)
+    assert_close(dQ.cpu().numpy(), ref_dQ, dtype, "dQ " + tag)
+    assert_close(dK.cpu().numpy(), ref_dK, dtype, "dK " + tag)
+    # dbias is a sum over all voxels: its rounding grows with the number of terms
+    assert_close(db.cpu().numpy(), ref_db, dtype, "dbias " + tag, scale=10.0)
+
+
+@pytest.mark.parametrize("shape", SMALL, ids=lambda s: "x".join(map(str, s)))
+@pytest.mark.parametrize("path", [0, 1], ids=["auto", "generic"])
+def test_small_cases_match_oracle(modet, shape, path):
+    run_case(modet, shape, path)
+
+
+@pytest.mark.parametrize("shape", [SMALL[1], SMALL[3], SMALL[6], SMALL[12]], ids=lambda s: "x".join(map(str, s)))
+@pytest.mark.parametrize("path", [0, 1], ids=["auto", "generic"])
+def test_bias_and_recomputed_statistics(modet, shape, path):
+    run_case(modet, shape, path, with_bias=True, stats="recompute")
+
+
+def test_explicit_scale_and_peaked_attention(modet):
+    """large scale: attention is one-hot on the planted integer offset (sign / axis order on the GPU)."""
+    B, D, H, W, heads, d, k = 1, 8, 9, 70, 1, 8, 3
+    Q = synth.normal(5, 0, (B, D, H, W, heads, d), dtype=np.float64)
+    Q = (Q / np.linalg.norm(Q, axis=-1, keepdims=True)).reshape(B, D, H, W, heads * d).astype(np.float32)
+    o = (1, -1, 1)
+    K = np.zeros_like(Q)
+    K[:, 1:, :-1, 1:] = Q[:, :-1, 1:, :-1]            # K[p + o] = Q[p]
+    for path in (0, 1):
+        old = modet.modet_set_kernel_path(path)
+        phi = modet.modet_fwd(up(Q), up(K), heads, k, scale=1.0e4).cpu().numpy()
+        modet.modet_set_kernel_path(old)
+        np.testing.assert_allclose(phi[:, :-1, 1:, :-1, 0], np.broadcast_to(np.array(o, np.float32),
+                                                                            phi[:, :-1, 1:, :-1, 0].shape), atol=1e-5)
+        ref = oracle.modet_fwd(Q, K, heads, k, scale=1.0e4)
+        # logits are ~1e4 here: fp32 rounding of the logit itself is ~1e-3, so only a loose bound holds
+        assert np.abs(phi - ref).max() < 5e-2
+
+
+def test_zero_query_is_uniform_everywhere(modet):
+    K = up(synth.normal(6, 0, (1, 6, 7, 66, 8)))
+    for path in (0, 1):
+        old = modet.modet_set_kernel_path(path)
+        phi, lse = modet.modet_fwd(torch.zeros_like(K), K, 1, 3, want_lse=True)
+        modet.modet_set_kernel_path(old)
+        assert phi.abs().max().item() <= 1e-7
+        np.testing.assert_allclose(lse.cpu().numpy(), np.log(27.0), rtol=1e-6)
+
+
+def test_backward_is_deterministic(modet):
+    c = synth.make_case(1, 12, 21, 70, 8, 1, 3, keys="displaced", m=1, seed=9)
+    Q, K, g = up(c["Q"]), up(c["K"]), up(c["dphi"])
+    a = modet.modet_bwd(Q, K, g, 1, 3)
+    b = modet.modet_bwd(Q, K, g, 1, 3)
+    assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
+
+
+def test_outputs_are_fully_overwritten(modet):
+    c = synth.make_case(1, 6, 9, 67, 8, 1, 3, seed=10)
+    Q, K, g = up(c["Q"]), up(c["K"]), up(c["dphi"])
+    dQ = torch.full(Q.shape, float("nan"), device="cuda")
+    dK = torch.full(Q.shape, float("nan"), device="cuda")
+    modet.modet_bwd(Q, K, g, 1, 3, out=(dQ, dK))
+    ref = oracle.modet_bwd(c["Q"], c["K"], c["dphi"], 1, 3)
+    assert_close(dQ.cpu().numpy(), ref[0], "f32", "dQ")
+    assert_close(dK.cpu().numpy(), ref[1], "f32", "dK")
+
+
+def test_errors_surface_as_exceptions(modet):
+    Q = torch.zeros((1, 4, 4, 4, 8), device="cuda")
+    with pytest.raises(modet.ModetError) as e:
+        modet.modet_fwd(Q, Q.clone(), 3, 3)
+    assert e.value.status == -2
+    with pytest.raises(modet.ModetError):
+        modet.modet_fwd(Q, Q.clone(), 1, 4)
+
+
+# ---- warp -------------------------------------------------------------------------------------
+@pytest.mark.parametrize("B,D,H,W,C,dtype,half", [
+    (1, 6, 7, 9, 8, "f32", False), (2, 8, 10, 12, 8, "f32", True), (1, 5, 9, 33, 32, "f32", False),
+    (1, 6, 8, 10, 3, "f32", False), (1, 6, 8, 10, 3, "f32", True), (1, 8, 6, 14, 16, "bf16", True),
+    (1, 4, 5, 70, 16, "bf16", False), (1, 1, 1, 1, 4, "f32", False), (1, 2, 2, 2, 4, "f32", True),
+])
+def test_warp_matches_oracle(modet, B, D, H, W, C, dtype, half):
+    src = synth.normal(61, 0, (B, D, H, W, C))
+    fshape = (B, D // 2, H // 2, W // 2, 3) if half else (B, D, H, W, 3)
+    field = (1.7 * synth.normal(62, 0, fshape)).astype(np.float32)
+    field.reshape(-1)[::7] = np.round(field.reshape(-1)[::7])          # some exactly-integer displacements
+    field.reshape(-1)[::11] *= 6.0                                      # some samples far outside
+    if dtype == "bf16":
+        src = synth.to_bf16_bits(src)
+    ref = oracle.warp(src, field, field_half_res=half, dtype=dtype)
+    out = modet.modet_warp(up(src, dtype), up(field), field_half_res=half)
+    got = out.float().cpu().numpy()
+    if dtype == "bf16":
+        # the output is rounded to bf16: half an ulp of bf16 (2^-9 relative) on top of fp32 accumulation
+        assert_close(got, ref, "bf16", "warp bf16")
+    else:
+        assert_close(got, ref, "f32", "warp f32")
+
+
+def test_warp_identity_and_integer_shift_are_exact(modet):
+    src = synth.normal(63, 0, (1, 6, 7, 40, 8))
+    z = torch.zeros((1, 6, 7, 40, 3), device="cuda")
+    assert torch.equal(modet.modet_warp(up(src), z), up(src))
+    u = z.clone()
+    u[..., 0], u[..., 1], u[..., 2] = 1.0, -2.0, 3.0
+    out = modet.modet_warp(up(src), u).cpu().numpy()
+    exp = np.zeros_like(src)
+    exp[:, 0:5, 2:7, 0:37] = src[:, 1:6, 0:5, 3:40]
+    assert np.array_equal(out, exp)
