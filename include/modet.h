@@ -108,7 +108,8 @@ int modet_warp(const void* src, const float* field, void* out,
  * previous value.  Process-wide, not thread safe. */
 int modet_set_kernel_path(int path);
 
-/* 1 if the (head size, k, dtype) combination runs on the LDS-tiled kernels under path 0. */
+/* Bit 0: modet_fwd, bit 1: modet_bwd run on the LDS-tiled kernels for this (head size, heads, k,
+ * dtype) under path 0 (without bias and attention output). */
 int modet_has_tiled_kernels(int C, int heads, int k, modet_dtype in_dtype);
 
 const char* modet_status_string(int status);

@@ -52,7 +52,7 @@ int modet_fwd(const void* Q, const void* K, const float* bias, float* phi, float
   const Geo g = make_geo(B, D, H, W, C, heads, k, scale);
   hipStream_t st = (hipStream_t)stream;
   hipError_t e;
-  if (g_kernel_path == 0 && !attn && tiled_supported(g.d, k, (int)in_dtype))
+  if (g_kernel_path == 0 && !attn && tiled_fwd_supported(g.d, heads, k, (int)in_dtype, bias != nullptr))
     e = launch_fwd_tiled(g, (int)in_dtype, Q, K, bias, phi, lse, st);
   else
     e = launch_fwd_generic(g, (int)in_dtype, Q, K, bias, phi, attn, lse, st);
@@ -82,18 +82,19 @@ int modet_bwd(const void* Q, const void* K, const float* bias, const float* dphi
   if (need > 0 && (!workspace || workspace_bytes < need)) return MODET_ERR_WORKSPACE;
   const Geo g = make_geo(B, D, H, W, C, heads, k, scale);
   hipStream_t st = (hipStream_t)stream;
-  const bool tiled = g_kernel_path == 0 && tiled_supported(g.d, k, (int)in_dtype);
+  const bool tiled_f = g_kernel_path == 0 && tiled_fwd_supported(g.d, heads, k, (int)in_dtype, bias != nullptr);
+  const bool tiled_b = g_kernel_path == 0 && tiled_bwd_supported(g.d, heads, k, (int)in_dtype, bias != nullptr);
   hipError_t e = hipSuccess;
   if (!phi) {   // statistics pass: the forward kernel writes phi and lse into the workspace
     float* wphi = (float*)workspace;
     float* wlse = (float*)((char*)workspace + round16((size_t)g.nvn * 3 * sizeof(float)));
-    e = tiled ? launch_fwd_tiled(g, (int)in_dtype, Q, K, bias, wphi, wlse, st)
+    e = tiled_f ? launch_fwd_tiled(g, (int)in_dtype, Q, K, bias, wphi, wlse, st)
               : launch_fwd_generic(g, (int)in_dtype, Q, K, bias, wphi, nullptr, wlse, st);
     if (e != hipSuccess) return MODET_ERR_LAUNCH;
     phi = wphi;
     lse = wlse;
   }
-  e = tiled ? launch_bwd_tiled(g, (int)in_dtype, Q, K, bias, dphi, phi, lse, dQ, dK, st)
+  e = tiled_b ? launch_bwd_tiled(g, (int)in_dtype, Q, K, bias, dphi, phi, lse, dQ, dK, st)
             : launch_bwd_generic(g, (int)in_dtype, Q, K, bias, dphi, phi, lse, dQ, dK, st);
   if (e != hipSuccess) return MODET_ERR_LAUNCH;
   if (dbias) {
@@ -126,7 +127,8 @@ int modet_set_kernel_path(int path) {
 
 int modet_has_tiled_kernels(int C, int heads, int k, modet_dtype in_dtype) {
   if (C < 1 || heads < 1 || C % heads != 0) return 0;
-  return tiled_supported(C / heads, k, (int)in_dtype) ? 1 : 0;
+  return (tiled_fwd_supported(C / heads, heads, k, (int)in_dtype, false) ? 1 : 0) |
+         (tiled_bwd_supported(C / heads, heads, k, (int)in_dtype, false) ? 2 : 0);
 }
 
 const char* modet_status_string(int status) {

@@ -39,7 +39,8 @@ hipError_t launch_warp(const void* src, const float* field, void* out, int B, in
                        int half, int dtype, hipStream_t st);
 
 // LDS-tiled kernels (head size 8)
-bool tiled_supported(int d, int k, int dtype);
+bool tiled_fwd_supported(int d, int heads, int k, int dtype, bool has_bias);
+bool tiled_bwd_supported(int d, int heads, int k, int dtype, bool has_bias);
 hipError_t launch_fwd_tiled(const Geo& g, int dtype, const void* Q, const void* K, const float* bias,
                             float* phi, float* lse, hipStream_t st);
 hipError_t launch_bwd_tiled(const Geo& g, int dtype, const void* Q, const void* K, const float* bias,

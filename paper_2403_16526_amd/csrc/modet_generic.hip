@@ -25,10 +25,13 @@ __device__ __forceinline__ bool inside(const Geo& g, int z, int y, int x) {
   return (unsigned)z < (unsigned)g.D && (unsigned)y < (unsigned)g.H && (unsigned)x < (unsigned)g.W;
 }
 
+// The dot product is accumulated in fp64: a logit of magnitude ~10 carries ~1e-6 of rounding when summed
+// in fp32, which the softmax turns into a 1e-6 relative error of every weight; fp64 FMAs issue at the
+// same rate as unpacked fp32 ones on this chip.
 template <class T>
-__device__ __forceinline__ float dot_d(const T* q, const T* kk, int d) {
-  float acc = 0.f;
-  for (int c = 0; c < d; ++c) acc = fmaf(ldf(q, c), ldf(kk, c), acc);
+__device__ __forceinline__ double dot_d(const T* q, const T* kk, int d) {
+  double acc = 0.0;
+  for (int c = 0; c < d; ++c) acc = fma((double)ldf(q, c), (double)ldf(kk, c), acc);
   return acc;
 }
 
@@ -43,40 +46,41 @@ fwd_generic_kernel(Geo g, const T* __restrict__ Q, const T* __restrict__ K, cons
   decode_vn(g, vn, b, z, y, x, s, v);
   const T* q = Q + v * g.C + s * g.d;
   const int r = g.r;
-  float m = -INFINITY, Z = 0.f, S0 = 0.f, S1 = 0.f, S2 = 0.f;
+  double m = -INFINITY;          // running maximum, kept in fp64 like the logits
+  float Z = 0.f, S0 = 0.f, S1 = 0.f, S2 = 0.f;
   int j = 0;
   for (int a = -r; a <= r; ++a)
     for (int bb = -r; bb <= r; ++bb)
       for (int c = -r; c <= r; ++c, ++j) {
-        float l = bias ? bias[s * g.k3 + j] : 0.f;
+        double l = bias ? (double)bias[s * g.k3 + j] : 0.0;
         if (inside(g, z + a, y + bb, x + c)) {
           long long nb = v + ((long long)a * g.H + bb) * g.W + c;
-          l = fmaf(g.scale, dot_d(q, K + nb * g.C + s * g.d, g.d), l);
+          l = fma((double)g.scale, dot_d(q, K + nb * g.C + s * g.d, g.d), l);
         }
         if (l > m) {
-          float al = expf(m - l);
+          float al = expf((float)(m - l));
           Z *= al; S0 *= al; S1 *= al; S2 *= al;
           m = l;
         }
-        float e = expf(l - m);
+        float e = expf((float)(l - m));
         Z += e; S0 = fmaf(e, (float)a, S0); S1 = fmaf(e, (float)bb, S1); S2 = fmaf(e, (float)c, S2);
       }
   float inv = 1.f / Z;
   phi[vn * 3 + 0] = S0 * inv;
   phi[vn * 3 + 1] = S1 * inv;
   phi[vn * 3 + 2] = S2 * inv;
-  if (lse) lse[vn] = m + logf(Z);
+  if (lse) lse[vn] = (float)(m + (double)logf(Z));
   if (attn) {
     j = 0;
     for (int a = -r; a <= r; ++a)
       for (int bb = -r; bb <= r; ++bb)
         for (int c = -r; c <= r; ++c, ++j) {
-          float l = bias ? bias[s * g.k3 + j] : 0.f;
+          double l = bias ? (double)bias[s * g.k3 + j] : 0.0;
           if (inside(g, z + a, y + bb, x + c)) {
             long long nb = v + ((long long)a * g.H + bb) * g.W + c;
-            l = fmaf(g.scale, dot_d(q, K + nb * g.C + s * g.d, g.d), l);
+            l = fma((double)g.scale, dot_d(q, K + nb * g.C + s * g.d, g.d), l);
           }
-          attn[vn * g.k3 + j] = expf(l - m) * inv;
+          attn[vn * g.k3 + j] = expf((float)(l - m)) * inv;
         }
   }
 }
@@ -121,9 +125,9 @@ grad_generic_kernel(Geo g, const T* __restrict__ Q, const T* __restrict__ K, con
           gphi = g0 * phi[pvn * 3] + g1 * phi[pvn * 3 + 1] + g2 * phi[pvn * 3 + 2];
           ls = lse[pvn];
         }
-        float l = bias ? bias[s * g.k3 + j] : 0.f;
-        l = fmaf(g.scale, dot_d(Q + pv * g.C + s * g.d, K + qv * g.C + s * g.d, g.d), l);
-        const float w = expf(l - ls);
+        const double l = fma((double)g.scale, dot_d(Q + pv * g.C + s * g.d, K + qv * g.C + s * g.d, g.d),
+                             bias ? (double)bias[s * g.k3 + j] : 0.0);
+        const float w = expf((float)(l - (double)ls));
         const float dl = w * (g0 * (float)a + g1 * (float)bb + g2 * (float)c - gphi);
         const T* other = KEYSIDE ? Q + pv * g.C + c0 : K + qv * g.C + c0;
 #pragma unroll
@@ -163,12 +167,12 @@ dbias_kernel(Geo g, const T* __restrict__ Q, const T* __restrict__ K, const floa
     for (int a = -r; a <= r; ++a)
       for (int bb = -r; bb <= r; ++bb)
         for (int c = -r; c <= r; ++c, ++j) {
-          float l = bias ? bias[s * g.k3 + j] : 0.f;
+          double l = bias ? (double)bias[s * g.k3 + j] : 0.0;
           if (inside(g, z + a, y + bb, x + c)) {
             long long nb = v + ((long long)a * g.H + bb) * g.W + c;
-            l = fmaf(g.scale, dot_d(q, K + nb * g.C + s * g.d, g.d), l);
+            l = fma((double)g.scale, dot_d(q, K + nb * g.C + s * g.d, g.d), l);
           }
-          const float dl = expf(l - ls) * (g0 * (float)a + g1 * (float)bb + g2 * (float)c - gphi);
+          const float dl = expf((float)(l - (double)ls)) * (g0 * (float)a + g1 * (float)bb + g2 * (float)c - gphi);
           atomicAdd(&part[s * g.k3 + j], dl);
         }
   }

@@ -13,7 +13,7 @@ import os
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libmodet.so")
+LIB_PATH = os.environ.get("MODET_LIBRARY") or os.path.join(_HERE, "libmodet.so")   # override: another build of libmodet
 
 MODET_F32, MODET_BF16 = 0, 1
 MODET_OK = 0
@@ -62,8 +62,9 @@ def modet_set_kernel_path(path: int) -> int:
     return int(_lib.modet_set_kernel_path(int(path)))
 
 
-def modet_has_tiled_kernels(C: int, heads: int, k: int, dtype: int = MODET_F32) -> bool:
-    return bool(_lib.modet_has_tiled_kernels(C, heads, k, dtype))
+def modet_has_tiled_kernels(C: int, heads: int, k: int, dtype: int = MODET_F32) -> int:
+    """bit 0: forward, bit 1: backward run on the LDS-tiled kernels."""
+    return int(_lib.modet_has_tiled_kernels(C, heads, k, dtype))
 
 
 def _check(rc: int):
