@@ -47,7 +47,7 @@ fwd_generic_kernel(Geo g, const T* __restrict__ Q, const T* __restrict__ K, cons
   const T* q = Q + v * g.C + s * g.d;
   const int r = g.r;
   double m = -INFINITY;          // running maximum, kept in fp64 like the logits
-  float Z = 0.f, S0 = 0.f, S1 = 0.f, S2 = 0.f;
+  double Z = 0.0, S0 = 0.0, S1 = 0.0, S2 = 0.0;   // fp64 sums: phi must be good to fp32 rounding for the backward
   int j = 0;
   for (int a = -r; a <= r; ++a)
     for (int bb = -r; bb <= r; ++bb)
@@ -58,18 +58,18 @@ fwd_generic_kernel(Geo g, const T* __restrict__ Q, const T* __restrict__ K, cons
           l = fma((double)g.scale, dot_d(q, K + nb * g.C + s * g.d, g.d), l);
         }
         if (l > m) {
-          float al = expf((float)(m - l));
+          double al = (double)expf((float)(m - l));
           Z *= al; S0 *= al; S1 *= al; S2 *= al;
           m = l;
         }
-        float e = expf((float)(l - m));
-        Z += e; S0 = fmaf(e, (float)a, S0); S1 = fmaf(e, (float)bb, S1); S2 = fmaf(e, (float)c, S2);
+        double e = (double)expf((float)(l - m));
+        Z += e; S0 = fma(e, (double)a, S0); S1 = fma(e, (double)bb, S1); S2 = fma(e, (double)c, S2);
       }
-  float inv = 1.f / Z;
-  phi[vn * 3 + 0] = S0 * inv;
-  phi[vn * 3 + 1] = S1 * inv;
-  phi[vn * 3 + 2] = S2 * inv;
-  if (lse) lse[vn] = (float)(m + (double)logf(Z));
+  double inv = 1.0 / Z;
+  phi[vn * 3 + 0] = (float)(S0 * inv);
+  phi[vn * 3 + 1] = (float)(S1 * inv);
+  phi[vn * 3 + 2] = (float)(S2 * inv);
+  if (lse) lse[vn] = (float)(m + (double)logf((float)Z));
   if (attn) {
     j = 0;
     for (int a = -r; a <= r; ++a)
@@ -80,7 +80,7 @@ fwd_generic_kernel(Geo g, const T* __restrict__ Q, const T* __restrict__ K, cons
             long long nb = v + ((long long)a * g.H + bb) * g.W + c;
             l = fma((double)g.scale, dot_d(q, K + nb * g.C + s * g.d, g.d), l);
           }
-          attn[vn * g.k3 + j] = expf((float)(l - m)) * inv;
+          attn[vn * g.k3 + j] = (float)((double)expf((float)(l - m)) * inv);
         }
   }
 }

@@ -199,26 +199,43 @@ __device__ __forceinline__ LT dot8(const LT (&q)[8], const float4& lo, const flo
   return acc;
 }
 
-__device__ __forceinline__ void axpy8(float (&acc)[8], float a, const float4& lo, const float4& hi) {
-  acc[0] = fmaf(a, lo.x, acc[0]); acc[1] = fmaf(a, lo.y, acc[1]);
-  acc[2] = fmaf(a, lo.z, acc[2]); acc[3] = fmaf(a, lo.w, acc[3]);
-  acc[4] = fmaf(a, hi.x, acc[4]); acc[5] = fmaf(a, hi.y, acc[5]);
-  acc[6] = fmaf(a, hi.z, acc[6]); acc[7] = fmaf(a, hi.w, acc[7]);
+// acc += a * v, accumulated in AT.  The gradients are sums of k^3 terms of either sign whose magnitude
+// follows the upstream gradient; in fp32 the 5-sigma tail of a 55M-element volume collects ~1e-6 of
+// rounding, so the accumulators are fp64 as well (same issue rate as fp32 FMAs, one conversion per pair).
+template <class AT>
+__device__ __forceinline__ void axpy8(AT (&acc)[8], float a, const float4& lo, const float4& hi) {
+  const AT aa = (AT)a;
+  acc[0] = fma(aa, (AT)lo.x, acc[0]); acc[1] = fma(aa, (AT)lo.y, acc[1]);
+  acc[2] = fma(aa, (AT)lo.z, acc[2]); acc[3] = fma(aa, (AT)lo.w, acc[3]);
+  acc[4] = fma(aa, (AT)hi.x, acc[4]); acc[5] = fma(aa, (AT)hi.y, acc[5]);
+  acc[6] = fma(aa, (AT)hi.z, acc[6]); acc[7] = fma(aa, (AT)hi.w, acc[7]);
+}
+
+template <class AT>
+__device__ __forceinline__ void store8_scaled(float* o, const AT (&acc)[8], float sc) {
+  const AT s = (AT)sc;
+  *reinterpret_cast<float4*>(o) = make_float4((float)(acc[0] * s), (float)(acc[1] * s), (float)(acc[2] * s),
+                                              (float)(acc[3] * s));
+  *reinterpret_cast<float4*>(o + 4) = make_float4((float)(acc[4] * s), (float)(acc[5] * s), (float)(acc[6] * s),
+                                                  (float)(acc[7] * s));
 }
 
 // ---- forward -----------------------------------------------------------------------------------
 template <class LT>
 struct QState {
   LT q[8];
-  float m, Z, S0, S1, S2;
+  float m;            // running maximum (log2 units)
+  LT Z, S0, S1, S2;   // sum of weights and of weight*offset, relative to m
 };
 
 template <class LT>
 __device__ __forceinline__ void qstate_reset(QState<LT>& s) {
-  s.m = -INFINITY; s.Z = 0.f; s.S0 = 0.f; s.S1 = 0.f; s.S2 = 0.f;
+  s.m = -INFINITY; s.Z = (LT)0; s.S0 = (LT)0; s.S1 = (LT)0; s.S2 = (LT)0;
 }
 
-// fold NB rows x KW columns of logits (window rows b0.., plane offset a) into the running softmax state
+// fold NB rows x KW columns of logits (window rows b0.., plane offset a) into the running softmax state.
+// The sums run in LT as well: phi feeds the backward pass, where its error is multiplied by the
+// upstream gradient, so it has to be good to fp32 rounding rather than to a few 1e-7.
 template <int KW, int NB, class LT>
 __device__ __forceinline__ void fold(QState<LT>& s, const LT (&l)[NB][KW], int a, int b0) {
   constexpr int R = KW / 2;
@@ -227,24 +244,24 @@ __device__ __forceinline__ void fold(QState<LT>& s, const LT (&l)[NB][KW], int a
   for (int b = 0; b < NB; ++b)
 #pragma unroll
     for (int c = 0; c < KW; ++c) mx = fmaxf(mx, (float)l[b][c]);
-  const float alpha = exp2_fast(s.m - mx);
-  float P = 0.f, Hs = 0.f, Ws = 0.f;
+  const LT alpha = (LT)exp2_fast(s.m - mx);
+  LT P = (LT)0, Hs = (LT)0, Ws = (LT)0;
 #pragma unroll
   for (int b = 0; b < NB; ++b) {
-    float rs = 0.f;
+    LT rs = (LT)0;
 #pragma unroll
     for (int c = 0; c < KW; ++c) {
-      const float e = exp2_fast((float)(l[b][c] - (LT)mx));
+      const LT e = (LT)exp2_fast((float)(l[b][c] - (LT)mx));
       rs += e;
-      if (c != R) Ws = fmaf((float)(c - R), e, Ws);
+      if (c != R) Ws = fma((LT)(c - R), e, Ws);
     }
     P += rs;
-    if (b0 + b != 0) Hs = fmaf((float)(b0 + b), rs, Hs);
+    if (b0 + b != 0) Hs = fma((LT)(b0 + b), rs, Hs);
   }
-  s.Z = fmaf(s.Z, alpha, P);
-  s.S0 = a == 0 ? s.S0 * alpha : fmaf(s.S0, alpha, (float)a * P);
-  s.S1 = fmaf(s.S1, alpha, Hs);
-  s.S2 = fmaf(s.S2, alpha, Ws);
+  s.Z = fma(s.Z, alpha, P);
+  s.S0 = a == 0 ? s.S0 * alpha : fma(s.S0, alpha, (LT)a * P);
+  s.S1 = fma(s.S1, alpha, Hs);
+  s.S2 = fma(s.S2, alpha, Ws);
   s.m = mx;
 }
 
@@ -288,10 +305,10 @@ __device__ __forceinline__ void fwd_body(QState<LT> (&st)[KW], const TiledParams
   QState<LT>& done = st[PH % KW];              // role 0: query plane s - R has now seen all its key planes
   if ((active & 1u) && t.lane_ok) {
     const long long o = t.col + (long long)(s - R) * p.H * p.Wh;
-    const float inv = __frcp_rn(done.Z);
+    const LT inv = (LT)1 / done.Z;
     float* ph = p.phi + o * 3;
-    ph[0] = done.S0 * inv; ph[1] = done.S1 * inv; ph[2] = done.S2 * inv;
-    if (p.lse) p.lse[o] = (done.m + log2_fast(done.Z)) * kLn2;
+    ph[0] = (float)(done.S0 * inv); ph[1] = (float)(done.S1 * inv); ph[2] = (float)(done.S2 * inv);
+    if (p.lse) p.lse[o] = (done.m + log2_fast((float)done.Z)) * kLn2;
   }
   if (have_next) {                             // the freed slot takes the query plane s + R + 1
 #pragma unroll
@@ -370,7 +387,7 @@ struct DQState {
   LT q[8];          // Q * scale * log2e
   LT nlse;          // -lse * log2e
   float g0, g1, g2, ngphi;
-  float acc[8];
+  LT acc[8];        // accumulated in the logit type
 };
 
 template <int KW, int HS, int PH, class LT>
@@ -394,7 +411,7 @@ __device__ __forceinline__ void dq_step(DQState<LT> (&st)[KW], const float4* __r
           if (R - i != 0) tt = fmaf((float)(R - i), s.g0, tt);
           if (b - R != 0) tt = fmaf((float)(b - R), s.g1, tt);
           if (c - R != 0) tt = fmaf((float)(c - R), s.g2, tt);
-          axpy8(s.acc, w * tt, lo, hi);
+          axpy8<LT>(s.acc, w * tt, lo, hi);
         }
     }
 }
@@ -418,7 +435,7 @@ __device__ __forceinline__ void load_query_aux(const TiledParams& p, const T* qp
 template <class LT>
 __device__ __forceinline__ void dq_refill(DQState<LT>& s, const QueryAux& a, float qscale) {
 #pragma unroll
-  for (int c = 0; c < 8; ++c) { s.q[c] = (LT)a.q[c] * (LT)qscale; s.acc[c] = 0.f; }
+  for (int c = 0; c < 8; ++c) { s.q[c] = (LT)a.q[c] * (LT)qscale; s.acc[c] = (LT)0; }
   s.nlse = -(LT)a.lse * (LT)kLog2e;
   s.g0 = a.g0; s.g1 = a.g1; s.g2 = a.g2;
   s.ngphi = -(a.g0 * a.f0 + a.g1 * a.f1 + a.g2 * a.f2);
@@ -437,11 +454,7 @@ __device__ __forceinline__ void dq_body(DQState<LT> (&st)[KW], const TiledParams
   dq_step<KW, HS, PH, LT>(st, kb, lbase, active);
   DQState<LT>& done = st[PH % KW];
   if ((active & 1u) && t.lane_ok) {
-    float* o = p.out + (t.col + (long long)(s - R) * p.H * p.Wh) * 8;
-    *reinterpret_cast<float4*>(o) = make_float4(done.acc[0] * p.scale, done.acc[1] * p.scale,
-                                                done.acc[2] * p.scale, done.acc[3] * p.scale);
-    *reinterpret_cast<float4*>(o + 4) = make_float4(done.acc[4] * p.scale, done.acc[5] * p.scale,
-                                                    done.acc[6] * p.scale, done.acc[7] * p.scale);
+    store8_scaled<LT>(p.out + (t.col + (long long)(s - R) * p.H * p.Wh) * 8, done.acc, p.scale);
   }
   if (have_next) dq_refill<LT>(done, nx, p.qscale);
 }
@@ -511,7 +524,7 @@ dq_tiled_kernel(TiledParams p) {
 template <class LT>
 struct DKState {
   LT k[8];
-  float acc[8];
+  LT acc[8];
 };
 
 // One query plane s against the KW key planes in flight.  Role i is the key plane zk = s - R + i, which
@@ -539,7 +552,7 @@ __device__ __forceinline__ void dk_step(DKState<LT> (&st)[KW], const float4* __r
           DKState<LT>& s = st[(i + PH) % KW];
           const float w = exp2_fast((float)dot8<LT>(s.k, lo, hi, (LT)a4.x));
           const float tt = (i - R != 0) ? fmaf((float)(i - R), a4.y, tb) : tb;
-          axpy8(s.acc, w * tt, lo, hi);
+          axpy8<LT>(s.acc, w * tt, lo, hi);
         }
     }
 }
@@ -558,15 +571,11 @@ __device__ __forceinline__ void dk_body(DKState<LT> (&st)[KW], const TiledParams
   dk_step<KW, HS, PH, LT>(st, qb, sa, sc, lbase, active);
   DKState<LT>& done = st[PH % KW];
   if ((active & 1u) && t.lane_ok) {
-    float* o = p.out + (t.col + (long long)(s - R) * p.H * p.Wh) * 8;
-    *reinterpret_cast<float4*>(o) = make_float4(done.acc[0] * p.scale, done.acc[1] * p.scale,
-                                                done.acc[2] * p.scale, done.acc[3] * p.scale);
-    *reinterpret_cast<float4*>(o + 4) = make_float4(done.acc[4] * p.scale, done.acc[5] * p.scale,
-                                                    done.acc[6] * p.scale, done.acc[7] * p.scale);
+    store8_scaled<LT>(p.out + (t.col + (long long)(s - R) * p.H * p.Wh) * 8, done.acc, p.scale);
   }
   if (have_next) {     // the in-flight copy of K carries the factor scale*log2e (applied in LT precision)
 #pragma unroll
-    for (int c = 0; c < 8; ++c) { done.k[c] = (LT)kn[c] * (LT)p.qscale; done.acc[c] = 0.f; }
+    for (int c = 0; c < 8; ++c) { done.k[c] = (LT)kn[c] * (LT)p.qscale; done.acc[c] = (LT)0; }
   }
 }
 
@@ -596,7 +605,7 @@ dk_tiled_kernel(TiledParams p) {
 #pragma unroll
   for (int i = 0; i < KW; ++i)
 #pragma unroll
-    for (int c = 0; c < 8; ++c) { st[i].k[c] = (LT)0; st[i].acc[c] = 0.f; }
+    for (int c = 0; c < 8; ++c) { st[i].k[c] = (LT)0; st[i].acc[c] = (LT)0; }
   {
     float k0[8];
     load8<T>(Kb + (long long)t.z0 * t.plane_elems, t.lane_ok, k0);

@@ -44,23 +44,25 @@ template <> struct Vec<bf16_t, 8> {
 
 // displacement at fine voxel (z,y,x) from the half-resolution field fc[Dc,Hc,Wc,3] of one batch item:
 // the fine voxel centre sits at coarse coordinate (i + 0.5)/2 - 0.5 = i/2 - 0.25, clamped to the grid.
+// The interpolation runs in fp64: an fp32 result would carry ~2e-7 of rounding on a displacement of a
+// few voxels, and the warp multiplies that by the local feature gradient.
 __device__ __forceinline__ void upsampled_disp(const float* __restrict__ fc, int Dc, int Hc, int Wc, int z, int y,
-                                               int x, float* u) {
+                                               int x, double* u) {
   float cz = fminf(fmaxf(0.5f * z - 0.25f, 0.f), (float)(Dc - 1));
   float cy = fminf(fmaxf(0.5f * y - 0.25f, 0.f), (float)(Hc - 1));
   float cx = fminf(fmaxf(0.5f * x - 0.25f, 0.f), (float)(Wc - 1));
   int z0 = (int)cz, y0 = (int)cy, x0 = (int)cx;       // coordinates are >= 0: truncation is floor
-  float tz = cz - z0, ty = cy - y0, tx = cx - x0;
+  float tz = cz - z0, ty = cy - y0, tx = cx - x0;     // exact: multiples of 1/4
   int z1 = min(z0 + 1, Dc - 1), y1 = min(y0 + 1, Hc - 1), x1 = min(x0 + 1, Wc - 1);  // weight 0 when clamped
-  u[0] = u[1] = u[2] = 0.f;
+  u[0] = u[1] = u[2] = 0.0;
 #pragma unroll
   for (int c = 0; c < 8; ++c) {
     int zi = (c & 4) ? z1 : z0, yi = (c & 2) ? y1 : y0, xi = (c & 1) ? x1 : x0;
-    float w = ((c & 4) ? tz : 1.f - tz) * ((c & 2) ? ty : 1.f - ty) * ((c & 1) ? tx : 1.f - tx);
+    double w = (double)(((c & 4) ? tz : 1.f - tz) * ((c & 2) ? ty : 1.f - ty) * ((c & 1) ? tx : 1.f - tx));
     const float* p = fc + (((long long)zi * Hc + yi) * Wc + xi) * 3;
-    u[0] = fmaf(w, p[0], u[0]); u[1] = fmaf(w, p[1], u[1]); u[2] = fmaf(w, p[2], u[2]);
+    u[0] = fma(w, (double)p[0], u[0]); u[1] = fma(w, (double)p[1], u[1]); u[2] = fma(w, (double)p[2], u[2]);
   }
-  u[0] *= 2.f; u[1] *= 2.f; u[2] *= 2.f;
+  u[0] *= 2.0; u[1] *= 2.0; u[2] *= 2.0;
 }
 
 template <class T, int VEC, bool HALF>
@@ -76,20 +78,20 @@ warp_kernel(const T* __restrict__ src, const float* __restrict__ field, T* __res
   const int y = (int)(t % H); t /= H;
   const int z = (int)(t % D);
   const int b = (int)(t / D);
-  float u[3];
+  double u[3];
   if (HALF) {
     const int Dc = D / 2, Hc = H / 2, Wc = W / 2;
     upsampled_disp(field + (long long)b * Dc * Hc * Wc * 3, Dc, Hc, Wc, z, y, x, u);
   } else {
     u[0] = field[v * 3]; u[1] = field[v * 3 + 1]; u[2] = field[v * 3 + 2];
   }
-  // split u into integer and fractional parts first: the fraction is then exact in fp32
-  const float fz = floorf(u[0]), fy = floorf(u[1]), fx = floorf(u[2]);
-  const float tz = u[0] - fz, ty = u[1] - fy, tx = u[2] - fx;
+  // split u into integer and fractional parts first: the fraction of an fp32 displacement is then exact
+  const double fz = floor(u[0]), fy = floor(u[1]), fx = floor(u[2]);
+  const float tz = (float)(u[0] - fz), ty = (float)(u[1] - fy), tx = (float)(u[2] - fx);
   // clamp the integer part far outside the volume so z + fz cannot overflow an int
-  const int z0 = z + (int)fminf(fmaxf(fz, -1.0e6f), 1.0e6f);
-  const int y0 = y + (int)fminf(fmaxf(fy, -1.0e6f), 1.0e6f);
-  const int x0 = x + (int)fminf(fmaxf(fx, -1.0e6f), 1.0e6f);
+  const int z0 = z + (int)fmin(fmax(fz, -1.0e6), 1.0e6);
+  const int y0 = y + (int)fmin(fmax(fy, -1.0e6), 1.0e6);
+  const int x0 = x + (int)fmin(fmax(fx, -1.0e6), 1.0e6);
   const T* sb = src + (long long)b * D * H * W * C + chunk * VEC;
   float acc[VEC];
 #pragma unroll

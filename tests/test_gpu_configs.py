@@ -1,0 +1,121 @@
+"""GPU parity on the benchmark configurations at their full sizes, in the launch configuration
+bench.py times (automatic kernel path, statistics handed from the forward to the backward)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2403_16526_amd import synth
+from parity_util import assert_close, sample_windows, up
+
+pytestmark = [pytest.mark.gpu, pytest.mark.timeout(900)]
+
+
+@pytest.fixture(scope="module")
+def modet():
+    assert torch.cuda.is_available(), "needs the MI355X"
+    from paper_2403_16526_amd import modet as m
+    return m
+
+
+def gpu_fwd_bwd(modet, c):
+    dtype, heads, k = c["dtype"], c["heads"], c["k"]
+    Q, K, g = up(c["Q"], dtype), up(c["K"], dtype), up(c["dphi"])
+    phi, lse = modet.modet_fwd(Q, K, heads, k, want_lse=True)
+    dQ, dK = modet.modet_bwd(Q, K, g, heads, k, phi=phi, lse=lse)
+    torch.cuda.synchronize()
+    return phi, lse, dQ, dK
+
+
+@pytest.mark.parametrize("no", [1, 2, 3])
+def test_fp32_configs_full_volume(modet, no):
+    """configs 1-3: every element of phi, lse, dQ, dK against the oracle."""
+    c = synth.make_config(no)
+    heads, k = c["heads"], c["k"]
+    phi, lse, dQ, dK = gpu_fwd_bwd(modet, c)
+    ref_phi, ref_lse = oracle.modet_fwd(c["Q"], c["K"], heads, k, want_lse=True)
+    assert_close(phi.cpu().numpy(), ref_phi, "f32", f"config {no} phi")
+    assert_close(lse.cpu().numpy(), ref_lse, "f32", f"config {no} lse")
+    del ref_phi, ref_lse
+    ref_dQ, ref_dK = oracle.modet_bwd(c["Q"], c["K"], c["dphi"], heads, k, form="gather")
+    assert_close(dQ.cpu().numpy(), ref_dQ, "f32", f"config {no} dQ")
+    assert_close(dK.cpu().numpy(), ref_dK, "f32", f"config {no} dK")
+
+
+def test_config3_without_forward_statistics(modet):
+    """the backward alone (statistics recomputed into the workspace) on a slab of config 3."""
+    c = synth.make_config(3, D=24)
+    Q, K, g = up(c["Q"]), up(c["K"]), up(c["dphi"])
+    dQ, dK = modet.modet_bwd(Q, K, g, 1, 3)
+    ref_dQ, ref_dK = oracle.modet_bwd(c["Q"], c["K"], c["dphi"], 1, 3, form="gather")
+    assert_close(dQ.cpu().numpy(), ref_dQ, "f32", "dQ")
+    assert_close(dK.cpu().numpy(), ref_dK, "f32", "dK")
+
+
+def test_config5_bf16_k5_sampled(modet):
+    """config 5 (2x192x160x192, C=16, 2 heads, k=5, bf16 inputs): sampled windows, corners and faces included."""
+    c = synth.make_config(5)
+    B, D, H, W, C, heads, k = (c[n] for n in ("B", "D", "H", "W", "C", "heads", "k"))
+    phi, lse, dQ, dK = gpu_fwd_bwd(modet, c)
+    idx = sample_windows(B, D, H, W, heads, 6000, seed=5, r=2)
+    ref_phi, ref_lse = oracle.modet_fwd_at(c["Q"], c["K"], idx, heads, k, dtype="bf16")
+    ref_dQ, ref_dK = oracle.modet_bwd_at(c["Q"], c["K"], c["dphi"], idx, heads, k, dtype="bf16")
+    d = C // heads
+    t = torch.from_numpy(idx).cuda()
+    got_phi = phi.reshape(-1, 3)[t].cpu().numpy()
+    got_lse = lse.reshape(-1)[t].cpu().numpy()
+    got_dQ = dQ.reshape(-1, d)[t].cpu().numpy()
+    got_dK = dK.reshape(-1, d)[t].cpu().numpy()
+    assert_close(got_phi, ref_phi, "bf16", "config 5 phi")
+    assert_close(got_lse, ref_lse, "bf16", "config 5 lse")
+    assert_close(got_dQ, ref_dQ, "bf16", "config 5 dQ")
+    assert_close(got_dK, ref_dK, "bf16", "config 5 dK")
+    # the inputs are bit-identical on both sides, so the error is in fact at fp32 level: report it
+    w = max(np.abs(got_phi - ref_phi).max(), np.abs(got_dQ - ref_dQ).max(), np.abs(got_dK - ref_dK).max())
+    print(f"config 5 max abs error over {idx.size} sampled windows: {w:.3g}")
+    assert w < 1e-4
+    # properties that hold at any size
+    assert torch.isfinite(phi).all() and torch.isfinite(dQ).all() and torch.isfinite(dK).all()
+    assert phi.abs().max().item() <= 2.0 + 1e-5
+
+
+def test_warp_config3_shape_full_volume(modet):
+    c = synth.make_config(3)
+    B, D, H, W = c["B"], c["D"], c["H"], c["W"]
+    field = synth.smooth_real_field(11, B, D, H, W, 1.5)
+    out = modet.modet_warp(up(c["K"]), up(field))
+    assert_close(out.cpu().numpy(), oracle.warp(c["K"], field), "f32", "warp full res field")
+    coarse = synth.smooth_real_field(12, B, D // 2, H // 2, W // 2, 1.0)
+    out = modet.modet_warp(up(c["K"]), up(coarse), field_half_res=True)
+    assert_close(out.cpu().numpy(), oracle.warp(c["K"], coarse, field_half_res=True), "f32", "warp half res field")
+
+
+def test_config4_pyramid_teacher_forced(modet):
+    """config 4: the five-level loop; at iterations 1 and 3 every operator call of every level is
+    re-run by the oracle on the GPU's own inputs (teacher forcing)."""
+    from paper_2403_16526_amd.pyramid import PyramidLoop
+    levels = [dict(Q=up(l["Q"]), K=up(l["K"]), heads=l["heads"]) for l in synth.make_pyramid()]
+    store = {}
+    loop = PyramidLoop(levels, eta=1.0, record=lambda l, n, t: store.__setitem__((l, n), t.detach().cpu().numpy()))
+    losses = []
+    for it in range(3):
+        store.clear()
+        phi, loss = loop.iteration()
+        losses.append(float(loss))
+        if it in (0, 2):
+            for l, lv in enumerate(levels):
+                heads = lv["heads"]
+                Q, Kw, g = store[(l, "Q")], store[(l, "Kw")], store[(l, "g")]
+                ref_sub, ref_lse = oracle.modet_fwd(Q, Kw, heads, 3, want_lse=True)
+                assert_close(store[(l, "sub")], ref_sub, "f32", f"iter {it} level {l} phi")
+                ref_dQ, ref_dK = oracle.modet_bwd(Q, Kw, g, heads, 3, form="gather")
+                # g = diff / VN is ~1e-7 here: compare the gradients relative to their own scale
+                s = float(np.abs(ref_dQ).max())
+                assert_close(store[(l, "dQ")] / s, ref_dQ / s, "f32", f"iter {it} level {l} dQ")
+                s = float(np.abs(ref_dK).max())
+                assert_close(store[(l, "dKw")] / s, ref_dK / s, "f32", f"iter {it} level {l} dK")
+                if l > 0:
+                    ref_w = oracle.warp(store[(l, "warp_src")], store[(l, "warp_field")], field_half_res=True)
+                    assert_close(store[(l, "warp_out")], ref_w, "f32", f"iter {it} level {l} warp")
+    assert np.isfinite(losses).all() and losses[-1] < losses[0]
+    assert phi.shape == (1, 160, 192, 224, 3)
