@@ -18,11 +18,17 @@
 //   * dK      : lane owns a key column, Q planes and per-query statistics (lse, g, g.phi) in LDS;
 //               it gathers over the queries that see the key, so no atomics and a fixed summation
 //               order (bit-reproducible).
-//   * Logits are accumulated in fp64 (template parameter LT): an fp32 sum of eight products leaves
-//     ~1e-6 of rounding on a logit of magnitude ~10, which the softmax turns into a 1e-6 relative
-//     error of the weights; fp64 FMAs issue at the rate of unpacked fp32 ones on this chip.
-//     Logits are kept in log2 units (Q is pre-multiplied by scale*log2(e)).
+//   * Logits are accumulated in fp64 for fp32 inputs (template parameter LT): an fp32 sum of eight
+//     products leaves ~1e-6 of rounding on a logit of magnitude ~10, which the softmax turns into a
+//     1e-6 relative error of the weights.  An fp64 FMA costs two fp32 issue slots on this chip, so fp64
+//     is confined to the dot product, the subtraction of the softmax reference and the running softmax
+//     sums of the forward; everything else is fp32.  Logits are kept in log2 units (the in-flight
+//     operand is pre-multiplied by scale*log2(e)).
 #include "modet_common.hpp"
+#include <type_traits>
+#ifdef MODET_TUNING_ENV
+#include <stdlib.h>
+#endif
 
 namespace modet {
 namespace {
@@ -30,7 +36,11 @@ namespace {
 constexpr int TX = 32, TY = 8, NT = TX * TY;
 constexpr float kLog2e = 1.4426950408889634f, kLn2 = 0.6931471805599453f;
 
+#ifdef MODET_KO_EXP
+__device__ __forceinline__ float exp2_fast(float x) { return x * 0.5f; }
+#else
 __device__ __forceinline__ float exp2_fast(float x) { return __builtin_amdgcn_exp2f(x); }
+#endif
 __device__ __forceinline__ float log2_fast(float x) { return __builtin_amdgcn_logf(x); }
 
 struct TiledParams {
@@ -76,15 +86,45 @@ __device__ __forceinline__ Tile make_tile(const TiledParams& p) {
 }
 
 // ---- plane staging -----------------------------------------------------------------------------
-// LDS holds, per position of the haloed patch, the 8 channels split in two float4 halves stored in
-// separate arrays (lane-consecutive 16-byte reads are then bank-conflict free).
+// LDS holds, per position of the haloed patch, the 8 channels split into 16-byte chunks that are stored in
+// separate arrays: chunk c of position pos sits at [c*NPOS + pos], so lane-consecutive 16-byte reads are
+// bank-conflict free.  The element type is fp32 (2 chunks) or fp64 (4 chunks, converted once when staged).
 template <int KW, int HS>
 struct Patch {
   static constexpr int R = KW / 2;
   static constexpr int PC = TX + 2 * R * HS, PR = TY + 2 * R, NPOS = PC * PR;
-  static constexpr int NV = 2 * NPOS;                 // float4 slots per plane
-  static constexpr int NL = (NV + NT - 1) / NT;       // float4 loads per lane per plane
+  static constexpr int NV = 2 * NPOS;                 // 4-channel loads per plane
+  static constexpr int NL = (NV + NT - 1) / NT;       // 4-channel loads per lane per plane
   static constexpr int NS = (NPOS + NT - 1) / NT;     // positions per lane per plane (statistics)
+};
+
+template <class ET> struct Lds;
+template <> struct Lds<float> {
+  typedef float4 chunk;
+  static constexpr int CH = 2;     // chunks per position
+  static __device__ __forceinline__ void put4(chunk* buf, int npos, int pos, int hv, const float4& v) {
+    buf[hv * npos + pos] = v;
+  }
+  static __device__ __forceinline__ void get8(const chunk* buf, int npos, int pos, float (&v)[8]) {
+    const float4 a = buf[pos], b = buf[npos + pos];
+    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+  }
+};
+template <> struct Lds<double> {
+  typedef double2 chunk;
+  static constexpr int CH = 4;
+  static __device__ __forceinline__ void put4(chunk* buf, int npos, int pos, int hv, const float4& v) {
+    buf[(2 * hv) * npos + pos] = make_double2((double)v.x, (double)v.y);
+    buf[(2 * hv + 1) * npos + pos] = make_double2((double)v.z, (double)v.w);
+  }
+  static __device__ __forceinline__ void get8(const chunk* buf, int npos, int pos, double (&v)[8]) {
+#ifdef MODET_KO_LDS
+    const double2 a = make_double2(pos * 0.5, 1.0), b = make_double2(npos * 0.25, 2.0), c = a, d = b;
+#else
+    const double2 a = buf[pos], b = buf[npos + pos], c = buf[2 * npos + pos], d = buf[3 * npos + pos];
+#endif
+    v[0] = a.x; v[1] = a.y; v[2] = b.x; v[3] = b.y; v[4] = c.x; v[5] = c.y; v[6] = d.x; v[7] = d.y;
+  }
 };
 
 template <class T> struct Ld;
@@ -99,11 +139,12 @@ template <> struct Ld<bf16_t> {
   }
 };
 
-template <int KW, int HS, class T>
+// stages one haloed plane of an [.., H, Wh, 8] tensor: global -> registers (fetch), registers -> LDS (commit)
+template <int KW, int HS, class T, class ET>
 struct Stager {
   typedef Patch<KW, HS> P;
   int goff[P::NL];      // element offset inside a plane, or -1: outside the volume / unused slot
-  int loff[P::NL];      // float4 index inside an LDS plane buffer, or -1 when unused
+  int loff[P::NL];      // (position << 1 | half) inside the patch, or -1 when unused
   float4 v[P::NL];
 
   __device__ __forceinline__ void init(int tid, int y0, int xs0, int H, int Wh) {
@@ -116,7 +157,7 @@ struct Stager {
       const bool used = e < P::NV;
       const bool in = used && gy >= 0 && gy < H && gx >= 0 && gx < Wh;
       goff[i] = in ? (gy * Wh + gx) * 8 + hv * 4 : -1;
-      loff[i] = used ? hv * P::NPOS + pos : -1;
+      loff[i] = used ? (pos << 1 | hv) : -1;
     }
   }
   // plane == nullptr: the plane lies outside the volume (zero padding)
@@ -125,10 +166,10 @@ struct Stager {
     for (int i = 0; i < P::NL; ++i)
       v[i] = (plane && goff[i] >= 0) ? Ld<T>::vec4(plane + goff[i]) : make_float4(0.f, 0.f, 0.f, 0.f);
   }
-  __device__ __forceinline__ void commit(float4* buf) const {
+  __device__ __forceinline__ void commit(typename Lds<ET>::chunk* buf) const {
 #pragma unroll
     for (int i = 0; i < P::NL; ++i)
-      if (loff[i] >= 0) buf[loff[i]] = v[i];
+      if (loff[i] >= 0) Lds<ET>::put4(buf, P::NPOS, loff[i] >> 1, loff[i] & 1, v[i]);
   }
 };
 
@@ -188,437 +229,342 @@ __device__ __forceinline__ void load8(const T* p, bool ok, float (&q)[8]) {
   }
 }
 
-// init + sum_c q[c] * v[c], accumulated in LT
+// sum_c q[c] * v[c] (+ init), accumulated in LT
 template <class LT>
-__device__ __forceinline__ LT dot8(const LT (&q)[8], const float4& lo, const float4& hi, LT init) {
+__device__ __forceinline__ LT dot8(const LT (&q)[8], const LT (&v)[8]) {
+  LT acc = q[0] * v[0];
+#pragma unroll
+  for (int c = 1; c < 8; ++c) acc = fma(q[c], v[c], acc);
+  return acc;
+}
+template <class LT>
+__device__ __forceinline__ LT dot8(const LT (&q)[8], const LT (&v)[8], LT init) {
   LT acc = init;
-  acc = fma(q[0], (LT)lo.x, acc); acc = fma(q[1], (LT)lo.y, acc);
-  acc = fma(q[2], (LT)lo.z, acc); acc = fma(q[3], (LT)lo.w, acc);
-  acc = fma(q[4], (LT)hi.x, acc); acc = fma(q[5], (LT)hi.y, acc);
-  acc = fma(q[6], (LT)hi.z, acc); acc = fma(q[7], (LT)hi.w, acc);
+#pragma unroll
+  for (int c = 0; c < 8; ++c) acc = fma(q[c], v[c], acc);
   return acc;
 }
 
-// acc += a * v, accumulated in AT.  The gradients are sums of k^3 terms of either sign whose magnitude
-// follows the upstream gradient; in fp32 the 5-sigma tail of a 55M-element volume collects ~1e-6 of
-// rounding, so the accumulators are fp64 as well (same issue rate as fp32 FMAs, one conversion per pair).
-template <class AT>
-__device__ __forceinline__ void axpy8(AT (&acc)[8], float a, const float4& lo, const float4& hi) {
-  const AT aa = (AT)a;
-  acc[0] = fma(aa, (AT)lo.x, acc[0]); acc[1] = fma(aa, (AT)lo.y, acc[1]);
-  acc[2] = fma(aa, (AT)lo.z, acc[2]); acc[3] = fma(aa, (AT)lo.w, acc[3]);
-  acc[4] = fma(aa, (AT)hi.x, acc[4]); acc[5] = fma(aa, (AT)hi.y, acc[5]);
-  acc[6] = fma(aa, (AT)hi.z, acc[6]); acc[7] = fma(aa, (AT)hi.w, acc[7]);
+__device__ __forceinline__ void axpy8(float (&acc)[8], float a, const float (&v)[8]) {
+#pragma unroll
+  for (int c = 0; c < 8; ++c) acc[c] = fmaf(a, v[c], acc[c]);
 }
 
-template <class AT>
-__device__ __forceinline__ void store8_scaled(float* o, const AT (&acc)[8], float sc) {
-  const AT s = (AT)sc;
-  *reinterpret_cast<float4*>(o) = make_float4((float)(acc[0] * s), (float)(acc[1] * s), (float)(acc[2] * s),
-                                              (float)(acc[3] * s));
-  *reinterpret_cast<float4*>(o + 4) = make_float4((float)(acc[4] * s), (float)(acc[5] * s), (float)(acc[6] * s),
-                                                  (float)(acc[7] * s));
+template <class LT, class ET>
+__device__ __forceinline__ void widen8(const ET (&v)[8], LT (&w)[8]) {
+#pragma unroll
+  for (int c = 0; c < 8; ++c) w[c] = (LT)v[c];
 }
 
-// ---- forward -----------------------------------------------------------------------------------
-template <class LT>
-struct QState {
-  LT q[8];
-  float m;            // running maximum (log2 units)
-  LT Z, S0, S1, S2;   // sum of weights and of weight*offset, relative to m
-};
-
-template <class LT>
-__device__ __forceinline__ void qstate_reset(QState<LT>& s) {
-  s.m = -INFINITY; s.Z = (LT)0; s.S0 = (LT)0; s.S1 = (LT)0; s.S2 = (LT)0;
+__device__ __forceinline__ void store8_scaled(float* o, const float (&acc)[8], float sc) {
+  *reinterpret_cast<float4*>(o) = make_float4(acc[0] * sc, acc[1] * sc, acc[2] * sc, acc[3] * sc);
+  *reinterpret_cast<float4*>(o + 4) = make_float4(acc[4] * sc, acc[5] * sc, acc[6] * sc, acc[7] * sc);
 }
 
-// fold NB rows x KW columns of logits (window rows b0.., plane offset a) into the running softmax state.
-// The sums run in LT as well: phi feeds the backward pass, where its error is multiplied by the
-// upstream gradient, so it has to be good to fp32 rounding rather than to a few 1e-7.
-template <int KW, int NB, class LT>
-__device__ __forceinline__ void fold(QState<LT>& s, const LT (&l)[NB][KW], int a, int b0) {
+template <int KW>
+__device__ __forceinline__ unsigned active_roles(int s, int z0, int z1) {
   constexpr int R = KW / 2;
-  float mx = s.m;
+  unsigned active = 0;
 #pragma unroll
-  for (int b = 0; b < NB; ++b)
+  for (int i = 0; i < KW; ++i) {
+    const int z = s - R + i;
+    if (z >= z0 && z < z1) active |= 1u << i;
+  }
+  return active;
+}
+
+// =================================================================================================
+// Policies.  A policy names the operand staged in LDS, the per-lane state of one in-flight plane (one
+// "role"), and the arithmetic of one step.  Role i (state slot (i+PH)%KW) is the in-flight plane
+// z = s - R + i while LDS plane s is current; it is complete after step z + R.
+// =================================================================================================
+
+// ---- forward: lane owns a query column; K planes in LDS (in LT); online softmax per window row --------
+template <int KW_, int HS_, class T_, class LT>
+struct FwdPolicy {
+  static constexpr int KW = KW_, HS = HS_, R = KW_ / 2;
+  typedef T_ T;
+  typedef LT ET;                           // LDS element type: no conversions in the inner loop
+  typedef Patch<KW, HS> P;
+  static constexpr bool kStats = false;
+  struct State {
+    LT q[8];            // Q * scale * log2e
+    float m;            // running maximum (log2 units)
+    LT Z, S0, S1, S2;   // sum of weights and of weight*offset, relative to m.  Kept in LT: phi feeds the
+  };                    // backward, where its error is multiplied by the upstream gradient
+  struct Pre { float q[8]; };
+
+  static __device__ __forceinline__ const T* lds_operand(const TiledParams& p) { return (const T*)p.K; }
+  static __device__ __forceinline__ const T* own_operand(const TiledParams& p) { return (const T*)p.Q; }
+
+  static __device__ __forceinline__ void reset(State& s) {
 #pragma unroll
-    for (int c = 0; c < KW; ++c) mx = fmaxf(mx, (float)l[b][c]);
-  const LT alpha = (LT)exp2_fast(s.m - mx);
-  LT P = (LT)0, Hs = (LT)0, Ws = (LT)0;
+    for (int c = 0; c < 8; ++c) s.q[c] = (LT)0;
+    s.m = -INFINITY; s.Z = (LT)0; s.S0 = (LT)0; s.S1 = (LT)0; s.S2 = (LT)0;
+  }
+  static __device__ __forceinline__ void prefetch(const TiledParams&, const T* own, long long, bool ok, Pre& pre) {
+    load8<T>(own, ok, pre.q);
+  }
+  static __device__ __forceinline__ void refill(State& s, const Pre& pre, const TiledParams& p) {
 #pragma unroll
-  for (int b = 0; b < NB; ++b) {
-    LT rs = (LT)0;
+    for (int c = 0; c < 8; ++c) s.q[c] = (LT)pre.q[c] * (LT)p.qscale;
+    s.m = -INFINITY; s.Z = (LT)0; s.S0 = (LT)0; s.S1 = (LT)0; s.S2 = (LT)0;
+  }
+  // fold one window row (in-plane offsets (b, -R..R), plane offset a) into the running softmax
+  static __device__ __forceinline__ void fold_row(State& s, const LT (&l)[KW], int a, int b) {
+    float mx = s.m;
+#pragma unroll
+    for (int c = 0; c < KW; ++c) mx = fmaxf(mx, (float)l[c]);
+    const float alpha = exp2_fast(s.m - mx);
+    float rs = 0.f, ws = 0.f;
 #pragma unroll
     for (int c = 0; c < KW; ++c) {
-      const LT e = (LT)exp2_fast((float)(l[b][c] - (LT)mx));
+      const float e = exp2_fast((float)(l[c] - (LT)mx));
       rs += e;
-      if (c != R) Ws = fma((LT)(c - R), e, Ws);
+      if (c != R) ws = fmaf((float)(c - R), e, ws);
     }
-    P += rs;
-    if (b0 + b != 0) Hs = fma((LT)(b0 + b), rs, Hs);
+    const LT al = (LT)alpha, rr = (LT)rs;
+    s.Z = fma(s.Z, al, rr);
+    s.S0 = a == 0 ? s.S0 * al : fma(s.S0, al, (LT)a * rr);
+    s.S1 = b == 0 ? s.S1 * al : fma(s.S1, al, (LT)b * rr);
+    s.S2 = fma(s.S2, al, (LT)ws);
+    s.m = mx;
   }
-  s.Z = fma(s.Z, alpha, P);
-  s.S0 = a == 0 ? s.S0 * alpha : fma(s.S0, alpha, (LT)a * P);
-  s.S1 = fma(s.S1, alpha, Hs);
-  s.S2 = fma(s.S2, alpha, Ws);
-  s.m = mx;
-}
-
-// One K plane against the KW query planes in flight.  Role i (slot (i+PH)%KW) is the query plane
-// zq = s - R + i, which sees key plane s under the D offset a = R - i.
-template <int KW, int HS, int PH, int NB, class LT>
-__device__ __forceinline__ void fwd_step(QState<LT> (&st)[KW], const float4* __restrict__ kb, int lbase,
-                                         unsigned active) {
-  typedef Patch<KW, HS> P;
-  constexpr int R = KW / 2;
-  LT l[KW][NB][KW];   // [role][row][col]; only NB rows are live at a time
+  template <int PH, bool FULL, class Sh>
+  static __device__ __forceinline__ void step(State (&st)[KW], const Sh& sh, int cur, int lbase, unsigned active) {
+    const typename Lds<ET>::chunk* kb = sh.main[cur];
 #pragma unroll
-  for (int b = 0; b < KW; ++b) {
+    for (int b = 0; b < KW; ++b) {
+      LT l[KW][KW];   // [role][col] of this window row
 #pragma unroll
-    for (int c = 0; c < KW; ++c) {
-      const int idx = lbase + b * P::PC + c * HS;
-      const float4 lo = kb[idx], hi = kb[P::NPOS + idx];
+      for (int c = 0; c < KW; ++c) {
+        LT kv[8];
+        Lds<ET>::get8(kb, P::NPOS, lbase + b * P::PC + c * HS, kv);
 #pragma unroll
-      for (int i = 0; i < KW; ++i)
-        if (active & (1u << i)) l[i][b % NB][c] = dot8<LT>(st[(i + PH) % KW].q, lo, hi, (LT)0);
-    }
-    if ((b + 1) % NB == 0) {
-#pragma unroll
-      for (int i = 0; i < KW; ++i)
-        if (active & (1u << i)) fold<KW, NB, LT>(st[(i + PH) % KW], l[i], R - i, b + 1 - NB - R);
-    }
-  }
-}
-
-template <int KW, int HS, class T, class LT, int PH>
-__device__ __forceinline__ void fwd_body(QState<LT> (&st)[KW], const TiledParams& p, const Tile& t,
-                                         const float4* kb, int lbase, int s, float (&qn)[8], bool have_next) {
-  constexpr int R = KW / 2;
-  unsigned active = 0;
-#pragma unroll
-  for (int i = 0; i < KW; ++i) {
-    const int zq = s - R + i;
-    if (zq >= t.z0 && zq < t.z1) active |= 1u << i;
-  }
-  fwd_step<KW, HS, PH, (KW == 3 ? 3 : 1), LT>(st, kb, lbase, active);
-  QState<LT>& done = st[PH % KW];              // role 0: query plane s - R has now seen all its key planes
-  if ((active & 1u) && t.lane_ok) {
-    const long long o = t.col + (long long)(s - R) * p.H * p.Wh;
-    const LT inv = (LT)1 / done.Z;
-    float* ph = p.phi + o * 3;
-    ph[0] = (float)(done.S0 * inv); ph[1] = (float)(done.S1 * inv); ph[2] = (float)(done.S2 * inv);
-    if (p.lse) p.lse[o] = (done.m + log2_fast((float)done.Z)) * kLn2;
-  }
-  if (have_next) {                             // the freed slot takes the query plane s + R + 1
-#pragma unroll
-    for (int c = 0; c < 8; ++c) done.q[c] = (LT)qn[c] * (LT)p.qscale;
-    qstate_reset(done);
-  }
-}
-
-template <int KW, int HS, class T, class LT>
-__global__ void __launch_bounds__(NT)
-fwd_tiled_kernel(TiledParams p) {
-  typedef Patch<KW, HS> P;
-  constexpr int R = KW / 2;
-  constexpr bool ROT = (KW == 3);
-  __shared__ float4 kbuf[2][P::NV];
-
-  const Tile t = make_tile(p);
-  const T* Kb = (const T*)p.K + (long long)t.b * p.D * t.plane_elems;
-  const T* Qb = (const T*)p.Q + (long long)t.b * p.D * t.plane_elems + ((long long)t.y * p.Wh + t.xs) * 8;
-  const int lbase = t.ty * P::PC + t.tx;      // window corner (b = c = -R) of this lane inside the patch
-
-  Stager<KW, HS, T> stg;
-  stg.init(threadIdx.x, t.y0, t.xs0, p.H, p.Wh);
-
-  QState<LT> st[KW];
-#pragma unroll
-  for (int i = 0; i < KW; ++i) {
-#pragma unroll
-    for (int c = 0; c < 8; ++c) st[i].q[c] = (LT)0;
-    qstate_reset(st[i]);
-  }
-  {
-    float q0[8];
-    load8<T>(Qb + (long long)t.z0 * t.plane_elems, t.lane_ok, q0);
-#pragma unroll
-    for (int c = 0; c < 8; ++c) st[KW - 1].q[c] = (LT)q0[c] * (LT)p.qscale;
-  }
-  const int s_first = t.z0 - R, s_last = t.z1 - 1 + R;
-  stg.fetch(s_first >= 0 ? Kb + (long long)s_first * t.plane_elems : nullptr);
-  stg.commit(kbuf[0]);
-  __syncthreads();
-
-  int ph = 0;
-  for (int s = s_first; s <= s_last; ++s) {
-    const int cur = (s - s_first) & 1;
-    const int sn = s + 1;
-    if (sn <= s_last) stg.fetch((sn >= 0 && sn < p.D) ? Kb + (long long)sn * t.plane_elems : nullptr);
-    const int zn = s + R + 1;
-    const bool have_next = zn < t.z1;
-    float qn[8];
-    load8<T>(Qb + (long long)zn * t.plane_elems, t.lane_ok && have_next, qn);
-
-    if (ROT) {
-      switch (ph) {
-        case 0: fwd_body<KW, HS, T, LT, 0>(st, p, t, kbuf[cur], lbase, s, qn, have_next); break;
-        case 1: fwd_body<KW, HS, T, LT, 1>(st, p, t, kbuf[cur], lbase, s, qn, have_next); break;
-        default: fwd_body<KW, HS, T, LT, 2 % KW>(st, p, t, kbuf[cur], lbase, s, qn, have_next); break;
+        for (int i = 0; i < KW; ++i)
+          if (FULL || (active & (1u << i))) l[i][c] = dot8<LT>(st[(i + PH) % KW].q, kv);
       }
-      ph = ph == KW - 1 ? 0 : ph + 1;
-    } else {
-      fwd_body<KW, HS, T, LT, 0>(st, p, t, kbuf[cur], lbase, s, qn, have_next);
-      // rotate by moving: role i+1 becomes role i, the refilled slot 0 becomes role KW-1
-      QState<LT> tmp = st[0];
 #pragma unroll
-      for (int i = 0; i + 1 < KW; ++i) st[i] = st[i + 1];
-      st[KW - 1] = tmp;
+      for (int i = 0; i < KW; ++i)
+        if (FULL || (active & (1u << i))) fold_row(st[(i + PH) % KW], l[i], R - i, b - R);
     }
-    if (sn <= s_last) stg.commit(kbuf[cur ^ 1]);
-    __syncthreads();
   }
-}
-
-// ---- backward, dQ: lane owns a query column, K planes in LDS -----------------------------------------
-template <class LT>
-struct DQState {
-  LT q[8];          // Q * scale * log2e
-  LT nlse;          // -lse * log2e
-  float g0, g1, g2, ngphi;
-  LT acc[8];        // accumulated in the logit type
+  static __device__ __forceinline__ void store(const State& s, const TiledParams& p, long long w) {
+    const LT inv = (LT)1 / s.Z;
+    float* ph = p.phi + w * 3;
+    ph[0] = (float)(s.S0 * inv); ph[1] = (float)(s.S1 * inv); ph[2] = (float)(s.S2 * inv);
+    if (p.lse) p.lse[w] = (s.m + log2_fast((float)s.Z)) * kLn2;
+  }
 };
 
-template <int KW, int HS, int PH, class LT>
-__device__ __forceinline__ void dq_step(DQState<LT> (&st)[KW], const float4* __restrict__ kb, int lbase,
-                                        unsigned active) {
+// ---- backward, dQ: lane owns a query column; K planes in LDS (fp32); w = exp(l - lse) ----------------
+template <int KW_, int HS_, class T_, class LT>
+struct DqPolicy {
+  static constexpr int KW = KW_, HS = HS_, R = KW_ / 2;
+  typedef T_ T;
+  typedef float ET;                        // the fp32 copy is needed for the fp32 accumulation anyway
   typedef Patch<KW, HS> P;
-  constexpr int R = KW / 2;
-#pragma unroll
-  for (int b = 0; b < KW; ++b)
-#pragma unroll
-    for (int c = 0; c < KW; ++c) {
-      const int idx = lbase + b * P::PC + c * HS;
-      const float4 lo = kb[idx], hi = kb[P::NPOS + idx];
-#pragma unroll
-      for (int i = 0; i < KW; ++i)
-        if (active & (1u << i)) {
-          DQState<LT>& s = st[(i + PH) % KW];
-          const float w = exp2_fast((float)dot8<LT>(s.q, lo, hi, s.nlse));
-          // t = g.o - g.phi with o = (R - i, b - R, c - R)
-          float tt = s.ngphi;
-          if (R - i != 0) tt = fmaf((float)(R - i), s.g0, tt);
-          if (b - R != 0) tt = fmaf((float)(b - R), s.g1, tt);
-          if (c - R != 0) tt = fmaf((float)(c - R), s.g2, tt);
-          axpy8<LT>(s.acc, w * tt, lo, hi);
-        }
-    }
-}
+  static constexpr bool kStats = false;
+  struct State {
+    LT q[8];          // Q * scale * log2e
+    LT nlse;          // -lse * log2e
+    float g0, g1, g2, ngphi;
+    float acc[8];
+  };
+  struct Pre { float q[8]; float lse, g0, g1, g2, f0, f1, f2; };
 
-struct QueryAux { float q[8]; float lse, g0, g1, g2, f0, f1, f2; };
+  static __device__ __forceinline__ const T* lds_operand(const TiledParams& p) { return (const T*)p.K; }
+  static __device__ __forceinline__ const T* own_operand(const TiledParams& p) { return (const T*)p.Q; }
 
-template <class T>
-__device__ __forceinline__ void load_query_aux(const TiledParams& p, const T* qptr, long long w, bool ok,
-                                               QueryAux& a) {
-  load8<T>(qptr, ok, a.q);
-  if (ok) {
-    a.lse = p.lse_in[w];
-    const float* g = p.dphi + w * 3;
-    const float* f = p.phi_in + w * 3;
-    a.g0 = g[0]; a.g1 = g[1]; a.g2 = g[2]; a.f0 = f[0]; a.f1 = f[1]; a.f2 = f[2];
-  } else {
-    a.lse = a.g0 = a.g1 = a.g2 = a.f0 = a.f1 = a.f2 = 0.f;
+  static __device__ __forceinline__ void reset(State& s) {
+#pragma unroll
+    for (int c = 0; c < 8; ++c) { s.q[c] = (LT)0; s.acc[c] = 0.f; }
+    s.nlse = (LT)0; s.g0 = s.g1 = s.g2 = s.ngphi = 0.f;
   }
-}
-
-template <class LT>
-__device__ __forceinline__ void dq_refill(DQState<LT>& s, const QueryAux& a, float qscale) {
-#pragma unroll
-  for (int c = 0; c < 8; ++c) { s.q[c] = (LT)a.q[c] * (LT)qscale; s.acc[c] = (LT)0; }
-  s.nlse = -(LT)a.lse * (LT)kLog2e;
-  s.g0 = a.g0; s.g1 = a.g1; s.g2 = a.g2;
-  s.ngphi = -(a.g0 * a.f0 + a.g1 * a.f1 + a.g2 * a.f2);
-}
-
-template <int KW, int HS, class T, class LT, int PH>
-__device__ __forceinline__ void dq_body(DQState<LT> (&st)[KW], const TiledParams& p, const Tile& t,
-                                        const float4* kb, int lbase, int s, const QueryAux& nx, bool have_next) {
-  constexpr int R = KW / 2;
-  unsigned active = 0;
-#pragma unroll
-  for (int i = 0; i < KW; ++i) {
-    const int zq = s - R + i;
-    if (zq >= t.z0 && zq < t.z1) active |= 1u << i;
-  }
-  dq_step<KW, HS, PH, LT>(st, kb, lbase, active);
-  DQState<LT>& done = st[PH % KW];
-  if ((active & 1u) && t.lane_ok) {
-    store8_scaled<LT>(p.out + (t.col + (long long)(s - R) * p.H * p.Wh) * 8, done.acc, p.scale);
-  }
-  if (have_next) dq_refill<LT>(done, nx, p.qscale);
-}
-
-template <int KW, int HS, class T, class LT>
-__global__ void __launch_bounds__(NT)
-dq_tiled_kernel(TiledParams p) {
-  typedef Patch<KW, HS> P;
-  constexpr int R = KW / 2;
-  constexpr bool ROT = (KW == 3);
-  __shared__ float4 kbuf[2][P::NV];
-
-  const Tile t = make_tile(p);
-  const T* Kb = (const T*)p.K + (long long)t.b * p.D * t.plane_elems;
-  const T* Qb = (const T*)p.Q + (long long)t.b * p.D * t.plane_elems + ((long long)t.y * p.Wh + t.xs) * 8;
-  const long long pw = (long long)p.H * p.Wh;
-  const int lbase = t.ty * P::PC + t.tx;
-
-  Stager<KW, HS, T> stg;
-  stg.init(threadIdx.x, t.y0, t.xs0, p.H, p.Wh);
-
-  DQState<LT> st[KW];
-  {
-    QueryAux zero;
-    load_query_aux<T>(p, Qb, 0, false, zero);
-#pragma unroll
-    for (int i = 0; i < KW; ++i) dq_refill<LT>(st[i], zero, p.qscale);
-    QueryAux a0;
-    load_query_aux<T>(p, Qb + (long long)t.z0 * t.plane_elems, t.col + t.z0 * pw, t.lane_ok, a0);
-    dq_refill<LT>(st[KW - 1], a0, p.qscale);
-  }
-  const int s_first = t.z0 - R, s_last = t.z1 - 1 + R;
-  stg.fetch(s_first >= 0 ? Kb + (long long)s_first * t.plane_elems : nullptr);
-  stg.commit(kbuf[0]);
-  __syncthreads();
-
-  int ph = 0;
-  for (int s = s_first; s <= s_last; ++s) {
-    const int cur = (s - s_first) & 1;
-    const int sn = s + 1;
-    if (sn <= s_last) stg.fetch((sn >= 0 && sn < p.D) ? Kb + (long long)sn * t.plane_elems : nullptr);
-    const int zn = s + R + 1;
-    const bool have_next = zn < t.z1;
-    QueryAux nx;
-    load_query_aux<T>(p, Qb + (long long)zn * t.plane_elems, t.col + zn * pw, t.lane_ok && have_next, nx);
-
-    if (ROT) {
-      switch (ph) {
-        case 0: dq_body<KW, HS, T, LT, 0>(st, p, t, kbuf[cur], lbase, s, nx, have_next); break;
-        case 1: dq_body<KW, HS, T, LT, 1>(st, p, t, kbuf[cur], lbase, s, nx, have_next); break;
-        default: dq_body<KW, HS, T, LT, 2 % KW>(st, p, t, kbuf[cur], lbase, s, nx, have_next); break;
-      }
-      ph = ph == KW - 1 ? 0 : ph + 1;
+  static __device__ __forceinline__ void prefetch(const TiledParams& p, const T* own, long long w, bool ok,
+                                                  Pre& a) {
+    load8<T>(own, ok, a.q);
+    if (ok) {
+      a.lse = p.lse_in[w];
+      const float* g = p.dphi + w * 3;
+      const float* f = p.phi_in + w * 3;
+      a.g0 = g[0]; a.g1 = g[1]; a.g2 = g[2]; a.f0 = f[0]; a.f1 = f[1]; a.f2 = f[2];
     } else {
-      dq_body<KW, HS, T, LT, 0>(st, p, t, kbuf[cur], lbase, s, nx, have_next);
-      DQState<LT> tmp = st[0];
-#pragma unroll
-      for (int i = 0; i + 1 < KW; ++i) st[i] = st[i + 1];
-      st[KW - 1] = tmp;
+      a.lse = a.g0 = a.g1 = a.g2 = a.f0 = a.f1 = a.f2 = 0.f;
     }
-    if (sn <= s_last) stg.commit(kbuf[cur ^ 1]);
-    __syncthreads();
   }
-}
-
-// ---- backward, dK: lane owns a key column; Q planes + per-query statistics in LDS --------------------
-template <class LT>
-struct DKState {
-  LT k[8];
-  LT acc[8];
+  static __device__ __forceinline__ void refill(State& s, const Pre& a, const TiledParams& p) {
+#pragma unroll
+    for (int c = 0; c < 8; ++c) { s.q[c] = (LT)a.q[c] * (LT)p.qscale; s.acc[c] = 0.f; }
+    s.nlse = -(LT)a.lse * (LT)kLog2e;
+    s.g0 = a.g0; s.g1 = a.g1; s.g2 = a.g2;
+    s.ngphi = -(a.g0 * a.f0 + a.g1 * a.f1 + a.g2 * a.f2);
+  }
+  template <int PH, bool FULL, class Sh>
+  static __device__ __forceinline__ void step(State (&st)[KW], const Sh& sh, int cur, int lbase, unsigned active) {
+    const typename Lds<ET>::chunk* kb = sh.main[cur];
+#pragma unroll
+    for (int b = 0; b < KW; ++b)
+#pragma unroll
+      for (int c = 0; c < KW; ++c) {
+        float kf[8];
+        Lds<ET>::get8(kb, P::NPOS, lbase + b * P::PC + c * HS, kf);
+        LT kv[8];
+        widen8<LT, float>(kf, kv);
+#pragma unroll
+        for (int i = 0; i < KW; ++i)
+          if (FULL || (active & (1u << i))) {
+            State& s = st[(i + PH) % KW];
+            const float w = exp2_fast((float)dot8<LT>(s.q, kv, s.nlse));
+            // t = g.o - g.phi with o = (R - i, b - R, c - R)
+            float tt = s.ngphi;
+            if (R - i != 0) tt = fmaf((float)(R - i), s.g0, tt);
+            if (b - R != 0) tt = fmaf((float)(b - R), s.g1, tt);
+            if (c - R != 0) tt = fmaf((float)(c - R), s.g2, tt);
+            axpy8(s.acc, w * tt, kf);
+          }
+      }
+  }
+  static __device__ __forceinline__ void store(const State& s, const TiledParams& p, long long w) {
+    store8_scaled(p.out + w * 8, s.acc, p.scale);
+  }
 };
 
-// One query plane s against the KW key planes in flight.  Role i is the key plane zk = s - R + i, which
-// the queries of plane s see under the D offset a = i - R.  The query at patch position (row, col) =
-// (ty + r, tx + cc*HS) sees this lane's key under the in-plane offset (b, c) = (R - r, R - cc).
-template <int KW, int HS, int PH, class LT>
-__device__ __forceinline__ void dk_step(DKState<LT> (&st)[KW], const float4* __restrict__ qb,
-                                        const float4* __restrict__ sa, const float* __restrict__ sc, int lbase,
-                                        unsigned active) {
+// ---- backward, dK: lane owns a key column; Q planes (fp32) + per-query statistics in LDS ----------------
+// The query at patch position (row, col) = (ty + r, tx + cc*HS) sees this lane's key of role i under the
+// offset (a, b, c) = (i - R, R - r, R - cc).
+template <int KW_, int HS_, class T_, class LT>
+struct DkPolicy {
+  static constexpr int KW = KW_, HS = HS_, R = KW_ / 2;
+  typedef T_ T;
+  typedef float ET;
   typedef Patch<KW, HS> P;
-  constexpr int R = KW / 2;
+  static constexpr bool kStats = true;
+  struct State {
+    LT k[8];          // K * scale * log2e
+    float acc[8];
+  };
+  struct Pre { float k[8]; };
+
+  static __device__ __forceinline__ const T* lds_operand(const TiledParams& p) { return (const T*)p.Q; }
+  static __device__ __forceinline__ const T* own_operand(const TiledParams& p) { return (const T*)p.K; }
+
+  static __device__ __forceinline__ void reset(State& s) {
 #pragma unroll
-  for (int r = 0; r < KW; ++r)
+    for (int c = 0; c < 8; ++c) { s.k[c] = (LT)0; s.acc[c] = 0.f; }
+  }
+  static __device__ __forceinline__ void prefetch(const TiledParams&, const T* own, long long, bool ok, Pre& pre) {
+    load8<T>(own, ok, pre.k);
+  }
+  static __device__ __forceinline__ void refill(State& s, const Pre& pre, const TiledParams& p) {
 #pragma unroll
-    for (int cc = 0; cc < KW; ++cc) {
-      const int idx = lbase + r * P::PC + cc * HS;
-      const float4 lo = qb[idx], hi = qb[P::NPOS + idx];
-      const float4 a4 = sa[idx];     // (-lse*log2e, g_D, g_H, g_W) of that query
-      float tb = sc[idx];            // -g.phi
-      if (R - r != 0) tb = fmaf((float)(R - r), a4.z, tb);
-      if (R - cc != 0) tb = fmaf((float)(R - cc), a4.w, tb);
+    for (int c = 0; c < 8; ++c) { s.k[c] = (LT)pre.k[c] * (LT)p.qscale; s.acc[c] = 0.f; }
+  }
+  template <int PH, bool FULL, class Sh>
+  static __device__ __forceinline__ void step(State (&st)[KW], const Sh& sh, int cur, int lbase, unsigned active) {
+    const typename Lds<ET>::chunk* qb = sh.main[cur];
+    const float4* sa = sh.sa[cur];
+    const float* sc = sh.sc[cur];
 #pragma unroll
-      for (int i = 0; i < KW; ++i)
-        if (active & (1u << i)) {
-          DKState<LT>& s = st[(i + PH) % KW];
-          const float w = exp2_fast((float)dot8<LT>(s.k, lo, hi, (LT)a4.x));
-          const float tt = (i - R != 0) ? fmaf((float)(i - R), a4.y, tb) : tb;
-          axpy8<LT>(s.acc, w * tt, lo, hi);
-        }
-    }
+    for (int r = 0; r < KW; ++r)
+#pragma unroll
+      for (int cc = 0; cc < KW; ++cc) {
+        const int idx = lbase + r * P::PC + cc * HS;
+        float qf[8];
+        Lds<ET>::get8(qb, P::NPOS, idx, qf);
+        LT qv[8];
+        widen8<LT, float>(qf, qv);
+        const float4 a4 = sa[idx];     // (-lse*log2e, g_D, g_H, g_W) of that query
+        float tb = sc[idx];            // -g.phi
+        if (R - r != 0) tb = fmaf((float)(R - r), a4.z, tb);
+        if (R - cc != 0) tb = fmaf((float)(R - cc), a4.w, tb);
+        const LT nlse = (LT)a4.x;
+#pragma unroll
+        for (int i = 0; i < KW; ++i)
+          if (FULL || (active & (1u << i))) {
+            State& s = st[(i + PH) % KW];
+            const float w = exp2_fast((float)dot8<LT>(s.k, qv, nlse));
+            const float tt = (i - R != 0) ? fmaf((float)(i - R), a4.y, tb) : tb;
+            axpy8(s.acc, w * tt, qf);
+          }
+      }
+  }
+  static __device__ __forceinline__ void store(const State& s, const TiledParams& p, long long w) {
+    store8_scaled(p.out + w * 8, s.acc, p.scale);
+  }
+};
+
+// ---- the marching kernel ---------------------------------------------------------------------------
+template <class Pol, bool STATS> struct SharedPlanes;
+template <class Pol> struct SharedPlanes<Pol, false> {
+  typename Lds<typename Pol::ET>::chunk main[2][Lds<typename Pol::ET>::CH * Pol::P::NPOS];
+};
+template <class Pol> struct SharedPlanes<Pol, true> {
+  typename Lds<typename Pol::ET>::chunk main[2][Lds<typename Pol::ET>::CH * Pol::P::NPOS];
+  float4 sa[2][Pol::P::NPOS];
+  float sc[2][Pol::P::NPOS];
+};
+
+template <class Pol, int PH, class Sh, class Stg, class SStg>
+__device__ __forceinline__ void march_body(typename Pol::State (&st)[Pol::KW], const TiledParams& p, const Tile& t,
+                                           Sh& sh, int cur, int lbase, int s, const typename Pol::Pre& pre,
+                                           bool have_next, bool commit_next, const Stg& stg, const SStg& sst) {
+  constexpr int KW = Pol::KW, R = KW / 2;
+  const unsigned active = active_roles<KW>(s, t.z0, t.z1);
+  if (active == (1u << KW) - 1u) Pol::template step<PH, true>(st, sh, cur, lbase, active);
+  else Pol::template step<PH, false>(st, sh, cur, lbase, active);
+  // the staged plane goes to LDS before the results are stored: the wait for its loads would otherwise
+  // also wait for those stores (one counter covers loads and stores on this chip)
+  if (commit_next) {
+    stg.commit(sh.main[cur ^ 1]);
+    if constexpr (Pol::kStats) sst.commit(sh.sa[cur ^ 1], sh.sc[cur ^ 1]);
+  }
+  typename Pol::State& done = st[PH % KW];     // role 0 is complete: it has seen planes z-R .. z+R
+  if ((active & 1u) && t.lane_ok) Pol::store(done, p, t.col + (long long)(s - R) * p.H * p.Wh);
+  if (have_next) Pol::refill(done, pre, p);     // the freed slot takes the plane s + R + 1
 }
 
-template <int KW, int HS, class T, class LT, int PH>
-__device__ __forceinline__ void dk_body(DKState<LT> (&st)[KW], const TiledParams& p, const Tile& t,
-                                        const float4* qb, const float4* sa, const float* sc, int lbase, int s,
-                                        const float (&kn)[8], bool have_next) {
-  constexpr int R = KW / 2;
-  unsigned active = 0;
-#pragma unroll
-  for (int i = 0; i < KW; ++i) {
-    const int zk = s - R + i;
-    if (zk >= t.z0 && zk < t.z1) active |= 1u << i;
-  }
-  dk_step<KW, HS, PH, LT>(st, qb, sa, sc, lbase, active);
-  DKState<LT>& done = st[PH % KW];
-  if ((active & 1u) && t.lane_ok) {
-    store8_scaled<LT>(p.out + (t.col + (long long)(s - R) * p.H * p.Wh) * 8, done.acc, p.scale);
-  }
-  if (have_next) {     // the in-flight copy of K carries the factor scale*log2e (applied in LT precision)
-#pragma unroll
-    for (int c = 0; c < 8; ++c) { done.k[c] = (LT)kn[c] * (LT)p.qscale; done.acc[c] = (LT)0; }
-  }
-}
+struct NoStats {
+  __device__ __forceinline__ void init(int, int, int, int, int) {}
+  __device__ __forceinline__ void fetch(const TiledParams&, long long, bool) {}
+};
 
-template <int KW, int HS, class T, class LT>
-__global__ void __launch_bounds__(NT)
-dk_tiled_kernel(TiledParams p) {
-  typedef Patch<KW, HS> P;
-  constexpr int R = KW / 2;
+template <class Pol, int WAVES>
+__global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(WAVES)))
+march_kernel(TiledParams p) {
+  typedef typename Pol::P P;
+  typedef typename Pol::T T;
+  constexpr int KW = Pol::KW, HS = Pol::HS, R = KW / 2;
   constexpr bool ROT = (KW == 3);
-  __shared__ float4 qbuf[2][P::NV];
-  __shared__ float4 sabuf[2][P::NPOS];
-  __shared__ float scbuf[2][P::NPOS];
+  __shared__ SharedPlanes<Pol, Pol::kStats> sh;
 
   const Tile t = make_tile(p);
-  const T* Qb = (const T*)p.Q + (long long)t.b * p.D * t.plane_elems;
-  const T* Kb = (const T*)p.K + (long long)t.b * p.D * t.plane_elems + ((long long)t.y * p.Wh + t.xs) * 8;
+  const T* Lb = Pol::lds_operand(p) + (long long)t.b * p.D * t.plane_elems;
+  const T* Ob = Pol::own_operand(p) + (long long)t.b * p.D * t.plane_elems + ((long long)t.y * p.Wh + t.xs) * 8;
   const long long pw = (long long)p.H * p.Wh;
   const long long wb = (long long)t.b * p.D * pw;    // window index of (b, 0, 0, 0)
-  const int lbase = t.ty * P::PC + t.tx;
+  const int lbase = t.ty * P::PC + t.tx;             // patch position of the window corner of this lane
 
-  Stager<KW, HS, T> stg;
+  Stager<KW, HS, T, typename Pol::ET> stg;
   stg.init(threadIdx.x, t.y0, t.xs0, p.H, p.Wh);
-  StatStager<KW, HS> sst;
+  typename std::conditional<Pol::kStats, StatStager<KW, HS>, NoStats>::type sst;
   sst.init(threadIdx.x, t.y0, t.xs0, p.H, p.Wh);
 
-  DKState<LT> st[KW];
+  typename Pol::State st[KW];
 #pragma unroll
-  for (int i = 0; i < KW; ++i)
-#pragma unroll
-    for (int c = 0; c < 8; ++c) { st[i].k[c] = (LT)0; st[i].acc[c] = (LT)0; }
+  for (int i = 0; i < KW; ++i) Pol::reset(st[i]);
   {
-    float k0[8];
-    load8<T>(Kb + (long long)t.z0 * t.plane_elems, t.lane_ok, k0);
-#pragma unroll
-    for (int c = 0; c < 8; ++c) st[KW - 1].k[c] = (LT)k0[c] * (LT)p.qscale;
+    typename Pol::Pre pre;
+    Pol::prefetch(p, Ob + (long long)t.z0 * t.plane_elems, t.col + t.z0 * pw, t.lane_ok, pre);
+    Pol::refill(st[KW - 1], pre, p);
   }
   const int s_first = t.z0 - R, s_last = t.z1 - 1 + R;
   {
     const bool ok = s_first >= 0;
-    stg.fetch(ok ? Qb + (long long)s_first * t.plane_elems : nullptr);
+    stg.fetch(ok ? Lb + (long long)s_first * t.plane_elems : nullptr);
     sst.fetch(p, wb + (long long)s_first * pw, ok);
-    stg.commit(qbuf[0]);
-    sst.commit(sabuf[0], scbuf[0]);
+    stg.commit(sh.main[0]);
+    if constexpr (Pol::kStats) sst.commit(sh.sa[0], sh.sc[0]);
   }
   __syncthreads();
 
@@ -626,43 +572,40 @@ dk_tiled_kernel(TiledParams p) {
   for (int s = s_first; s <= s_last; ++s) {
     const int cur = (s - s_first) & 1;
     const int sn = s + 1;
-    if (sn <= s_last) {
+    const bool commit_next = sn <= s_last;
+    if (commit_next) {
       const bool ok = sn >= 0 && sn < p.D;
-      stg.fetch(ok ? Qb + (long long)sn * t.plane_elems : nullptr);
+      stg.fetch(ok ? Lb + (long long)sn * t.plane_elems : nullptr);
       sst.fetch(p, wb + (long long)sn * pw, ok);
     }
     const int zn = s + R + 1;
     const bool have_next = zn < t.z1;
-    float kn[8];
-    load8<T>(Kb + (long long)zn * t.plane_elems, t.lane_ok && have_next, kn);
+    typename Pol::Pre pre;
+    Pol::prefetch(p, Ob + (long long)zn * t.plane_elems, t.col + zn * pw, t.lane_ok && have_next, pre);
 
     if (ROT) {
       switch (ph) {
-        case 0: dk_body<KW, HS, T, LT, 0>(st, p, t, qbuf[cur], sabuf[cur], scbuf[cur], lbase, s, kn, have_next); break;
-        case 1: dk_body<KW, HS, T, LT, 1>(st, p, t, qbuf[cur], sabuf[cur], scbuf[cur], lbase, s, kn, have_next); break;
-        default: dk_body<KW, HS, T, LT, 2 % KW>(st, p, t, qbuf[cur], sabuf[cur], scbuf[cur], lbase, s, kn, have_next); break;
+        case 0: march_body<Pol, 0>(st, p, t, sh, cur, lbase, s, pre, have_next, commit_next, stg, sst); break;
+        case 1: march_body<Pol, 1 % KW>(st, p, t, sh, cur, lbase, s, pre, have_next, commit_next, stg, sst); break;
+        default: march_body<Pol, 2 % KW>(st, p, t, sh, cur, lbase, s, pre, have_next, commit_next, stg, sst); break;
       }
       ph = ph == KW - 1 ? 0 : ph + 1;
     } else {
-      dk_body<KW, HS, T, LT, 0>(st, p, t, qbuf[cur], sabuf[cur], scbuf[cur], lbase, s, kn, have_next);
-      DKState<LT> tmp = st[0];
+      march_body<Pol, 0>(st, p, t, sh, cur, lbase, s, pre, have_next, commit_next, stg, sst);
+      // rotate by moving: role i+1 becomes role i, the refilled slot 0 becomes role KW-1
+      typename Pol::State tmp = st[0];
 #pragma unroll
       for (int i = 0; i + 1 < KW; ++i) st[i] = st[i + 1];
       st[KW - 1] = tmp;
-    }
-    if (sn <= s_last) {
-      stg.commit(qbuf[cur ^ 1]);
-      sst.commit(sabuf[cur ^ 1], scbuf[cur ^ 1]);
     }
     __syncthreads();
   }
 }
 
 // ---- launch ------------------------------------------------------------------------------------------
-#ifndef MODET_LOGIT_T
-#define MODET_LOGIT_T double
+#ifndef MODET_WAVES
+#define MODET_WAVES 2
 #endif
-typedef MODET_LOGIT_T logit_t;    // accumulation type of the logits (see the note at the top of the file)
 
 TiledParams make_params(const Geo& g) {
   TiledParams p = {};
@@ -674,6 +617,9 @@ TiledParams make_params(const Geo& g) {
   const long long tiles = (long long)p.ntx * p.nty * g.B;
   int zc = 16;
   while (zc > 4 && tiles * ((g.D + zc - 1) / zc) < 2048) zc >>= 1;
+#ifdef MODET_TUNING_ENV
+  if (const char* e = getenv("MODET_ZC")) zc = atoi(e);
+#endif
   if (zc > g.D) zc = g.D;
   p.ZC = zc;
   p.nzc = (g.D + zc - 1) / zc;
@@ -684,23 +630,23 @@ TiledParams make_params(const Geo& g) {
 
 inline unsigned nblocks(const TiledParams& p) { return (unsigned)((long long)p.ntx * p.nty * p.B * p.nzc); }
 
-template <int KW, int HS, class T>
+template <int KW, int HS, class T, class LT>
 hipError_t launch_fwd_t(const Geo& g, const void* Q, const void* K, float* phi, float* lse, hipStream_t st) {
   TiledParams p = make_params(g);
   p.Q = Q; p.K = K; p.phi = phi; p.lse = lse;
-  hipLaunchKernelGGL((fwd_tiled_kernel<KW, HS, T, logit_t>), dim3(nblocks(p)), dim3(NT), 0, st, p);
+  hipLaunchKernelGGL((march_kernel<FwdPolicy<KW, HS, T, LT>, MODET_WAVES>), dim3(nblocks(p)), dim3(NT), 0, st, p);
   return hipGetLastError();
 }
 
-template <int KW, int HS, class T>
+template <int KW, int HS, class T, class LT>
 hipError_t launch_bwd_t(const Geo& g, const void* Q, const void* K, const float* dphi, const float* phi,
                         const float* lse, float* dQ, float* dK, hipStream_t st) {
   TiledParams p = make_params(g);
   p.Q = Q; p.K = K; p.dphi = dphi; p.phi_in = phi; p.lse_in = lse;
   p.out = dQ;
-  hipLaunchKernelGGL((dq_tiled_kernel<KW, HS, T, logit_t>), dim3(nblocks(p)), dim3(NT), 0, st, p);
+  hipLaunchKernelGGL((march_kernel<DqPolicy<KW, HS, T, LT>, MODET_WAVES>), dim3(nblocks(p)), dim3(NT), 0, st, p);
   p.out = dK;
-  hipLaunchKernelGGL((dk_tiled_kernel<KW, HS, T, logit_t>), dim3(nblocks(p)), dim3(NT), 0, st, p);
+  hipLaunchKernelGGL((march_kernel<DkPolicy<KW, HS, T, LT>, MODET_WAVES>), dim3(nblocks(p)), dim3(NT), 0, st, p);
   return hipGetLastError();
 }
 
@@ -720,10 +666,10 @@ hipError_t launch_fwd_tiled(const Geo& g, int dtype, const void* Q, const void* 
                             float* phi, float* lse, hipStream_t st) {
   (void)bias; (void)dtype;
   switch (g.heads) {
-    case 1: return launch_fwd_t<3, 1, float>(g, Q, K, phi, lse, st);
-    case 2: return launch_fwd_t<3, 2, float>(g, Q, K, phi, lse, st);
-    case 4: return launch_fwd_t<3, 4, float>(g, Q, K, phi, lse, st);
-    case 8: return launch_fwd_t<3, 8, float>(g, Q, K, phi, lse, st);
+    case 1: return launch_fwd_t<3, 1, float, double>(g, Q, K, phi, lse, st);
+    case 2: return launch_fwd_t<3, 2, float, double>(g, Q, K, phi, lse, st);
+    case 4: return launch_fwd_t<3, 4, float, double>(g, Q, K, phi, lse, st);
+    case 8: return launch_fwd_t<3, 8, float, double>(g, Q, K, phi, lse, st);
     default: return hipErrorNotSupported;
   }
 }
@@ -733,10 +679,10 @@ hipError_t launch_bwd_tiled(const Geo& g, int dtype, const void* Q, const void* 
                             hipStream_t st) {
   (void)bias; (void)dtype;
   switch (g.heads) {
-    case 1: return launch_bwd_t<3, 1, float>(g, Q, K, dphi, phi, lse, dQ, dK, st);
-    case 2: return launch_bwd_t<3, 2, float>(g, Q, K, dphi, phi, lse, dQ, dK, st);
-    case 4: return launch_bwd_t<3, 4, float>(g, Q, K, dphi, phi, lse, dQ, dK, st);
-    case 8: return launch_bwd_t<3, 8, float>(g, Q, K, dphi, phi, lse, dQ, dK, st);
+    case 1: return launch_bwd_t<3, 1, float, double>(g, Q, K, dphi, phi, lse, dQ, dK, st);
+    case 2: return launch_bwd_t<3, 2, float, double>(g, Q, K, dphi, phi, lse, dQ, dK, st);
+    case 4: return launch_bwd_t<3, 4, float, double>(g, Q, K, dphi, phi, lse, dQ, dK, st);
+    case 8: return launch_bwd_t<3, 8, float, double>(g, Q, K, dphi, phi, lse, dQ, dK, st);
     default: return hipErrorNotSupported;
   }
 }
