@@ -36,11 +36,7 @@ namespace {
 constexpr int TX = 32, TY = 8, NT = TX * TY;
 constexpr float kLog2e = 1.4426950408889634f, kLn2 = 0.6931471805599453f;
 
-#ifdef MODET_KO_EXP
-__device__ __forceinline__ float exp2_fast(float x) { return x * 0.5f; }
-#else
 __device__ __forceinline__ float exp2_fast(float x) { return __builtin_amdgcn_exp2f(x); }
-#endif
 __device__ __forceinline__ float log2_fast(float x) { return __builtin_amdgcn_logf(x); }
 
 struct TiledParams {
@@ -118,11 +114,7 @@ template <> struct Lds<double> {
     buf[(2 * hv + 1) * npos + pos] = make_double2((double)v.z, (double)v.w);
   }
   static __device__ __forceinline__ void get8(const chunk* buf, int npos, int pos, double (&v)[8]) {
-#ifdef MODET_KO_LDS
-    const double2 a = make_double2(pos * 0.5, 1.0), b = make_double2(npos * 0.25, 2.0), c = a, d = b;
-#else
     const double2 a = buf[pos], b = buf[npos + pos], c = buf[2 * npos + pos], d = buf[3 * npos + pos];
-#endif
     v[0] = a.x; v[1] = a.y; v[2] = b.x; v[3] = b.y; v[4] = c.x; v[5] = c.y; v[6] = d.x; v[7] = d.y;
   }
 };
@@ -350,7 +342,8 @@ struct FwdPolicy {
     }
   }
   static __device__ __forceinline__ void store(const State& s, const TiledParams& p, long long w) {
-    const LT inv = (LT)1 / s.Z;
+    LT inv = (LT)__builtin_amdgcn_rcpf((float)s.Z);
+    inv = inv * ((LT)2 - s.Z * inv);          // one Newton step: relative error ~1e-14 in fp64
     float* ph = p.phi + w * 3;
     ph[0] = (float)(s.S0 * inv); ph[1] = (float)(s.S1 * inv); ph[2] = (float)(s.S2 * inv);
     if (p.lse) p.lse[w] = (s.m + log2_fast((float)s.Z)) * kLn2;
@@ -630,11 +623,17 @@ TiledParams make_params(const Geo& g) {
 
 inline unsigned nblocks(const TiledParams& p) { return (unsigned)((long long)p.ntx * p.nty * p.B * p.nzc); }
 
+// waves per SIMD the register allocator is asked to make room for: the fp64 state of the fp32-input
+// kernels and the five in-flight planes of k = 5 fit two, the all-fp32 state of k = 3 fits three
+template <class LT, int KW> struct Waves { static constexpr int value = MODET_WAVES; };
+template <> struct Waves<float, 3> { static constexpr int value = 3; };
+
 template <int KW, int HS, class T, class LT>
 hipError_t launch_fwd_t(const Geo& g, const void* Q, const void* K, float* phi, float* lse, hipStream_t st) {
   TiledParams p = make_params(g);
   p.Q = Q; p.K = K; p.phi = phi; p.lse = lse;
-  hipLaunchKernelGGL((march_kernel<FwdPolicy<KW, HS, T, LT>, MODET_WAVES>), dim3(nblocks(p)), dim3(NT), 0, st, p);
+  hipLaunchKernelGGL((march_kernel<FwdPolicy<KW, HS, T, LT>, Waves<LT, KW>::value>), dim3(nblocks(p)), dim3(NT), 0,
+                     st, p);
   return hipGetLastError();
 }
 
@@ -644,17 +643,22 @@ hipError_t launch_bwd_t(const Geo& g, const void* Q, const void* K, const float*
   TiledParams p = make_params(g);
   p.Q = Q; p.K = K; p.dphi = dphi; p.phi_in = phi; p.lse_in = lse;
   p.out = dQ;
-  hipLaunchKernelGGL((march_kernel<DqPolicy<KW, HS, T, LT>, MODET_WAVES>), dim3(nblocks(p)), dim3(NT), 0, st, p);
+  hipLaunchKernelGGL((march_kernel<DqPolicy<KW, HS, T, LT>, Waves<LT, KW>::value>), dim3(nblocks(p)), dim3(NT), 0, st,
+                     p);
   p.out = dK;
-  hipLaunchKernelGGL((march_kernel<DkPolicy<KW, HS, T, LT>, MODET_WAVES>), dim3(nblocks(p)), dim3(NT), 0, st, p);
+  hipLaunchKernelGGL((march_kernel<DkPolicy<KW, HS, T, LT>, Waves<LT, KW>::value>), dim3(nblocks(p)), dim3(NT), 0, st,
+                     p);
   return hipGetLastError();
 }
 
 }  // namespace
 
+// Covered: head size 8, no bias;  k = 3: 1/2/4/8 heads, fp32 inputs (fp64 logits) and bf16 inputs (fp32
+// logits: the bf16 tolerance leaves room);  k = 5: 1/2 heads, bf16 inputs.
 bool tiled_fwd_supported(int d, int heads, int k, int dtype, bool has_bias) {
   if (d != 8 || has_bias) return false;
-  if (k == 3) return dtype == 0 && (heads == 1 || heads == 2 || heads == 4 || heads == 8);
+  if (k == 3) return heads == 1 || heads == 2 || heads == 4 || heads == 8;
+  if (k == 5) return dtype == 1 && (heads == 1 || heads == 2);
   return false;
 }
 
@@ -662,29 +666,44 @@ bool tiled_bwd_supported(int d, int heads, int k, int dtype, bool has_bias) {
   return tiled_fwd_supported(d, heads, k, dtype, has_bias);
 }
 
+#define MODET_DISPATCH(CALL)                                                     \
+  if (g.k == 3 && dtype == 0) {                                                  \
+    switch (g.heads) {                                                           \
+      case 1: return CALL(3, 1, float, double);                                  \
+      case 2: return CALL(3, 2, float, double);                                  \
+      case 4: return CALL(3, 4, float, double);                                  \
+      case 8: return CALL(3, 8, float, double);                                  \
+    }                                                                            \
+  } else if (g.k == 3) {                                                         \
+    switch (g.heads) {                                                           \
+      case 1: return CALL(3, 1, bf16_t, float);                                  \
+      case 2: return CALL(3, 2, bf16_t, float);                                  \
+      case 4: return CALL(3, 4, bf16_t, float);                                  \
+      case 8: return CALL(3, 8, bf16_t, float);                                  \
+    }                                                                            \
+  } else if (g.k == 5 && dtype == 1) {                                           \
+    switch (g.heads) {                                                           \
+      case 1: return CALL(5, 1, bf16_t, float);                                  \
+      case 2: return CALL(5, 2, bf16_t, float);                                  \
+    }                                                                            \
+  }                                                                              \
+  return hipErrorNotSupported;
+
 hipError_t launch_fwd_tiled(const Geo& g, int dtype, const void* Q, const void* K, const float* bias,
                             float* phi, float* lse, hipStream_t st) {
-  (void)bias; (void)dtype;
-  switch (g.heads) {
-    case 1: return launch_fwd_t<3, 1, float, double>(g, Q, K, phi, lse, st);
-    case 2: return launch_fwd_t<3, 2, float, double>(g, Q, K, phi, lse, st);
-    case 4: return launch_fwd_t<3, 4, float, double>(g, Q, K, phi, lse, st);
-    case 8: return launch_fwd_t<3, 8, float, double>(g, Q, K, phi, lse, st);
-    default: return hipErrorNotSupported;
-  }
+  (void)bias;
+#define MODET_FWD(KW, HS, T, LT) launch_fwd_t<KW, HS, T, LT>(g, Q, K, phi, lse, st)
+  MODET_DISPATCH(MODET_FWD)
+#undef MODET_FWD
 }
 
 hipError_t launch_bwd_tiled(const Geo& g, int dtype, const void* Q, const void* K, const float* bias,
                             const float* dphi, const float* phi, const float* lse, float* dQ, float* dK,
                             hipStream_t st) {
-  (void)bias; (void)dtype;
-  switch (g.heads) {
-    case 1: return launch_bwd_t<3, 1, float, double>(g, Q, K, dphi, phi, lse, dQ, dK, st);
-    case 2: return launch_bwd_t<3, 2, float, double>(g, Q, K, dphi, phi, lse, dQ, dK, st);
-    case 4: return launch_bwd_t<3, 4, float, double>(g, Q, K, dphi, phi, lse, dQ, dK, st);
-    case 8: return launch_bwd_t<3, 8, float, double>(g, Q, K, dphi, phi, lse, dQ, dK, st);
-    default: return hipErrorNotSupported;
-  }
+  (void)bias;
+#define MODET_BWD(KW, HS, T, LT) launch_bwd_t<KW, HS, T, LT>(g, Q, K, dphi, phi, lse, dQ, dK, st)
+  MODET_DISPATCH(MODET_BWD)
+#undef MODET_BWD
 }
 
 }  // namespace modet
