@@ -33,7 +33,13 @@
 namespace modet {
 namespace {
 
-constexpr int TX = 32, TY = 8, NT = TX * TY;
+#ifndef MODET_TX
+#define MODET_TX 32
+#endif
+#ifndef MODET_TY
+#define MODET_TY 8
+#endif
+constexpr int TX = MODET_TX, TY = MODET_TY, NT = TX * TY;
 constexpr float kLog2e = 1.4426950408889634f, kLn2 = 0.6931471805599453f;
 
 __device__ __forceinline__ float exp2_fast(float x) { return __builtin_amdgcn_exp2f(x); }
@@ -605,11 +611,11 @@ TiledParams make_params(const Geo& g) {
   p.B = g.B; p.D = g.D; p.H = g.H; p.Wh = g.W * g.heads;
   p.ntx = (p.Wh + TX - 1) / TX;
   p.nty = (g.H + TY - 1) / TY;
-  // enough chunks along D to give every CU several workgroups, but not so short that the
-  // k-1 extra planes per chunk dominate
+  // enough chunks along D to give every CU several workgroups (4 per CU on 256 CUs), but not so short
+  // that the k-1 extra planes per chunk dominate
   const long long tiles = (long long)p.ntx * p.nty * g.B;
   int zc = 16;
-  while (zc > 4 && tiles * ((g.D + zc - 1) / zc) < 2048) zc >>= 1;
+  while (zc > 4 && tiles * ((g.D + zc - 1) / zc) < 1024) zc >>= 1;
 #ifdef MODET_TUNING_ENV
   if (const char* e = getenv("MODET_ZC")) zc = atoi(e);
 #endif

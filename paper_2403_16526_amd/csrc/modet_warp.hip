@@ -65,19 +65,41 @@ __device__ __forceinline__ void upsampled_disp(const float* __restrict__ fc, int
   u[0] *= 2.0; u[1] *= 2.0; u[2] *= 2.0;
 }
 
+// Work mapping: a workgroup handles a brick of BX x BY x BZ voxels (x fastest, then the channel chunk
+// inside a voxel), so the 8 corners of neighbouring voxels are found in the CU's own L1 instead of being
+// re-fetched from L2 by another workgroup, and bricks are numbered so that every XCD (own L2) gets one
+// contiguous slab of the volume.
+struct Brick { int bx, by, bz, nbx, nby, nbz, sc, sx, sy; };   // sc, sx, sy: log2 of nchunk, bx, by (or -1)
+
 template <class T, int VEC, bool HALF>
 __global__ void __launch_bounds__(kThreads)
 warp_kernel(const T* __restrict__ src, const float* __restrict__ field, T* __restrict__ out, int B, int D, int H,
-            int W, int C, long long total) {
-  long long idx = (long long)blockIdx.x * kThreads + threadIdx.x;
-  if (idx >= total) return;
-  const int nchunk = C / VEC;
-  const int chunk = (int)(idx % nchunk);
-  long long v = idx / nchunk, t = v;
-  const int x = (int)(t % W); t /= W;
-  const int y = (int)(t % H); t /= H;
-  const int z = (int)(t % D);
-  const int b = (int)(t / D);
+            int W, int C, Brick bk) {
+  const unsigned nb = gridDim.x, xcd = blockIdx.x & 7u, q = nb >> 3, rem = nb & 7u;
+  unsigned blk = xcd * q + (xcd < rem ? xcd : rem) + (blockIdx.x >> 3);
+  // per-lane index split with shifts when the channel-chunk count is a power of two (no integer division)
+  int chunk, lx, ly, lz;
+  if (bk.sc >= 0) {
+    int t = threadIdx.x;
+    chunk = t & ((1 << bk.sc) - 1); t >>= bk.sc;
+    lx = t & (bk.bx - 1); t >>= bk.sx;
+    ly = t & (bk.by - 1);
+    lz = t >> bk.sy;
+  } else {
+    const int nchunk = C / VEC;
+    chunk = threadIdx.x % nchunk;
+    int t = threadIdx.x / nchunk;
+    lx = t % bk.bx; t /= bk.bx;
+    ly = t % bk.by;
+    lz = t / bk.by;
+  }
+  const int ibx = blk % bk.nbx; blk /= bk.nbx;
+  const int iby = blk % bk.nby; blk /= bk.nby;
+  const int ibz = blk % bk.nbz;
+  const int b = blk / bk.nbz;
+  const int x = ibx * bk.bx + lx, y = iby * bk.by + ly, z = ibz * bk.bz + lz;
+  if (lz >= bk.bz || x >= W || y >= H || z >= D) return;
+  const long long v = (((long long)b * D + z) * H + y) * W + x;
   double u[3];
   if (HALF) {
     const int Dc = D / 2, Hc = H / 2, Wc = W / 2;
@@ -93,19 +115,25 @@ warp_kernel(const T* __restrict__ src, const float* __restrict__ field, T* __res
   const int y0 = y + (int)fmin(fmax(fy, -1.0e6), 1.0e6);
   const int x0 = x + (int)fmin(fmax(fx, -1.0e6), 1.0e6);
   const T* sb = src + (long long)b * D * H * W * C + chunk * VEC;
+  // all 8 corner loads are issued before any is consumed (addresses clamped into the volume, values of
+  // corners outside it replaced by zero afterwards): one memory round trip per lane instead of eight
+  float val[8][VEC];
+  bool in[8];
+#pragma unroll
+  for (int c = 0; c < 8; ++c) {
+    const int zi = z0 + ((c >> 2) & 1), yi = y0 + ((c >> 1) & 1), xi = x0 + (c & 1);
+    in[c] = (unsigned)zi < (unsigned)D && (unsigned)yi < (unsigned)H && (unsigned)xi < (unsigned)W;
+    const int zc = min(max(zi, 0), D - 1), yc = min(max(yi, 0), H - 1), xc = min(max(xi, 0), W - 1);
+    Vec<T, VEC>::load(sb + (((long long)zc * H + yc) * W + xc) * C, val[c]);
+  }
   float acc[VEC];
 #pragma unroll
   for (int i = 0; i < VEC; ++i) acc[i] = 0.f;
 #pragma unroll
   for (int c = 0; c < 8; ++c) {
-    const int zi = z0 + ((c >> 2) & 1), yi = y0 + ((c >> 1) & 1), xi = x0 + (c & 1);
-    if ((unsigned)zi < (unsigned)D && (unsigned)yi < (unsigned)H && (unsigned)xi < (unsigned)W) {
-      const float w = ((c & 4) ? tz : 1.f - tz) * ((c & 2) ? ty : 1.f - ty) * ((c & 1) ? tx : 1.f - tx);
-      float val[VEC];
-      Vec<T, VEC>::load(sb + (((long long)zi * H + yi) * W + xi) * C, val);
+    const float w = ((c & 4) ? tz : 1.f - tz) * ((c & 2) ? ty : 1.f - ty) * ((c & 1) ? tx : 1.f - tx);
 #pragma unroll
-      for (int i = 0; i < VEC; ++i) acc[i] = fmaf(w, val[i], acc[i]);
-    }
+    for (int i = 0; i < VEC; ++i) acc[i] = fmaf(w, in[c] ? val[c][i] : 0.f, acc[i]);
   }
   Vec<T, VEC>::store(out + v * C + chunk * VEC, acc);
 }
@@ -113,14 +141,26 @@ warp_kernel(const T* __restrict__ src, const float* __restrict__ field, T* __res
 template <class T, int VEC>
 hipError_t launch_t(const void* src, const float* field, void* out, int B, int D, int H, int W, int C, int half,
                     hipStream_t st) {
-  const long long total = (long long)B * D * H * W * (C / VEC);
-  dim3 grid((unsigned)((total + kThreads - 1) / kThreads)), block(kThreads);
+  const int nchunk = C / VEC;
+  const int vpb = kThreads / nchunk;            // voxels per workgroup (a few lanes idle if it does not divide)
+  Brick bk;
+  bk.bx = vpb >= 16 ? 16 : vpb;
+  bk.by = vpb / bk.bx >= 4 ? 4 : (vpb / bk.bx >= 2 ? 2 : 1);
+  bk.bz = vpb / (bk.bx * bk.by);
+  if (bk.bz < 1) bk.bz = 1;
+  bk.nbx = (W + bk.bx - 1) / bk.bx;
+  bk.nby = (H + bk.by - 1) / bk.by;
+  bk.nbz = (D + bk.bz - 1) / bk.bz;
+  auto lg = [](int n) { int s = 0; while ((1 << s) < n) ++s; return (1 << s) == n ? s : -1; };
+  bk.sc = lg(nchunk); bk.sx = lg(bk.bx); bk.sy = lg(bk.by);
+  if (bk.sx < 0 || bk.sy < 0) bk.sc = -1;
+  dim3 grid((unsigned)((long long)bk.nbx * bk.nby * bk.nbz * B)), block(kThreads);
   if (half)
     hipLaunchKernelGGL((warp_kernel<T, VEC, true>), grid, block, 0, st, (const T*)src, field, (T*)out, B, D, H, W,
-                       C, total);
+                       C, bk);
   else
     hipLaunchKernelGGL((warp_kernel<T, VEC, false>), grid, block, 0, st, (const T*)src, field, (T*)out, B, D, H, W,
-                       C, total);
+                       C, bk);
   return hipGetLastError();
 }
 
