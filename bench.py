@@ -22,9 +22,10 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 
-# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
-# command (see profiles/), scaled by the copy-kernel calibration; None until measured.
-MEASURED_TRAFFIC_BYTES = {3: None}
+# HBM bytes per modet_bwd call (its dQ kernel + its dK kernel) from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# runs of this command, scaled by what the same counters read for the device copy below
+# (profiles/config3_fwd_bwd_warp_kernels.txt); None where not measured.
+MEASURED_TRAFFIC_BYTES = {3: 1813392353}
 
 
 def main():
@@ -108,11 +109,12 @@ def main():
     # algorithmic bytes (each tensor moved once, no stored attention)
     fwd_bytes = nvox * (2 * C * esz + 12 * heads)
     bwd_bytes = nvox * (2 * C * esz + 12 * heads + 8 * C)
-    dom_bytes, dom_ms, dom_name = (bwd_bytes, t_bwd, "modet_bwd") if t_bwd >= t_fwd else (fwd_bytes, t_fwd, "modet_fwd")
+    dom_bytes, dom_ms, dom_name = ((bwd_bytes, t_bwd, "modet_bwd (dQ kernel + dK kernel)") if t_bwd >= t_fwd
+                                  else (fwd_bytes, t_fwd, "modet_fwd"))
     achieved = dom_bytes / (dom_ms * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": dom_name, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": MEASURED_TRAFFIC_BYTES.get(args.config),
+                "traffic": MEASURED_TRAFFIC_BYTES.get(args.config) if (t_bwd >= t_fwd and not args.generic) else None,
                 "algorithmic_bytes": dom_bytes, "avg_launch_ms": round(dom_ms, 4)}
 
     # a plain device copy of the same byte count: the attainable ceiling on this machine
