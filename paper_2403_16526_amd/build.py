@@ -11,7 +11,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libmodet.so")
 SOURCES = ["modet_api.hip", "modet_generic.hip", "modet_tiled.hip", "modet_warp.hip"]
-# packed fp32 instructions are switched off on purpose ("compiler flags")
+# packed fp32 instructions are switched off on purpose: some of their forms have given wrong results on this hardware
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
 
