@@ -36,6 +36,8 @@ def main():
     ap.add_argument("--config", type=int, default=3, choices=[1, 2, 3, 5])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--generic", action="store_true", help="force the generic kernels")
+    ap.add_argument("--fast-logits", action="store_true",
+                    help="fp32 instead of fp64 logits (does not meet the parity tolerance; for information)")
     ap.add_argument("--recompute-stats", action="store_true", help="do not hand phi/lse of the forward to the backward")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -75,6 +77,8 @@ def main():
     ws = torch.empty(max(wsb, 16), device="cuda", dtype=torch.uint8)
     if args.generic:
         modet.modet_set_kernel_path(1)
+    if args.fast_logits:
+        modet.modet_set_math_mode(1)
 
     def fwd():
         modet.modet_fwd(Q, K, heads, k, out=(phi, lse))
@@ -172,7 +176,9 @@ def main():
         "config": {"workload": f"config {args.config}: {cfg['name']} B={B} {D}x{H}x{W} C={C} heads={heads} k={k} "
                                f"{dtype}, fwd(phi,lse)+bwd(dQ,dK)",
                    "kernel_path": "generic" if args.generic else "auto",
-                   "stats_from_forward": have_stats},
+                   "stats_from_forward": have_stats,
+                   "logits": ("fp32" if dtype == "bf16" else
+                              "fp32 (outside the parity tolerance)" if args.fast_logits else "fp64")},
         "roofline": roofline,
         "cpu_baseline": cpu,
         "fwd_ms": round(t_fwd, 4), "bwd_ms": round(t_bwd, 4),

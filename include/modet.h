@@ -108,6 +108,13 @@ int modet_warp(const void* src, const float* field, void* out,
  * previous value.  Process-wide, not thread safe. */
 int modet_set_kernel_path(int path);
 
+/* Arithmetic of the LDS-tiled kernels for fp32 inputs.  0 (default) = logits accumulated in fp64: meets
+ * 1e-5 relative / 1e-6 absolute against an fp64 evaluation of Eq. 3-4.  1 = logits accumulated in fp32:
+ * about twice as fast, but a logit of magnitude ~10 then carries ~1e-6 of rounding and gradients can miss
+ * that tolerance by a small factor.  bf16 inputs always use fp32.  Returns the previous value.
+ * Process-wide, not thread safe. */
+int modet_set_math_mode(int mode);
+
 /* Bit 0: modet_fwd, bit 1: modet_bwd run on the LDS-tiled kernels for this (head size, heads, k,
  * dtype) under path 0 (without bias and attention output). */
 int modet_has_tiled_kernels(int C, int heads, int k, modet_dtype in_dtype);

@@ -10,6 +10,7 @@ using namespace modet;
 namespace {
 
 int g_kernel_path = 0;   // 0 = automatic, 1 = generic kernels only
+int g_math_mode = 0;     // 0 = fp64 logits for fp32 inputs, 1 = fp32 logits
 
 inline bool misaligned(const void* p) { return p && (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 
@@ -53,7 +54,7 @@ int modet_fwd(const void* Q, const void* K, const float* bias, float* phi, float
   hipStream_t st = (hipStream_t)stream;
   hipError_t e;
   if (g_kernel_path == 0 && !attn && tiled_fwd_supported(g.d, heads, k, (int)in_dtype, bias != nullptr))
-    e = launch_fwd_tiled(g, (int)in_dtype, Q, K, bias, phi, lse, st);
+    e = launch_fwd_tiled(g, (int)in_dtype, g_math_mode == 1, Q, K, bias, phi, lse, st);
   else
     e = launch_fwd_generic(g, (int)in_dtype, Q, K, bias, phi, attn, lse, st);
   return e == hipSuccess ? MODET_OK : MODET_ERR_LAUNCH;
@@ -88,13 +89,13 @@ int modet_bwd(const void* Q, const void* K, const float* bias, const float* dphi
   if (!phi) {   // statistics pass: the forward kernel writes phi and lse into the workspace
     float* wphi = (float*)workspace;
     float* wlse = (float*)((char*)workspace + round16((size_t)g.nvn * 3 * sizeof(float)));
-    e = tiled_f ? launch_fwd_tiled(g, (int)in_dtype, Q, K, bias, wphi, wlse, st)
+    e = tiled_f ? launch_fwd_tiled(g, (int)in_dtype, g_math_mode == 1, Q, K, bias, wphi, wlse, st)
               : launch_fwd_generic(g, (int)in_dtype, Q, K, bias, wphi, nullptr, wlse, st);
     if (e != hipSuccess) return MODET_ERR_LAUNCH;
     phi = wphi;
     lse = wlse;
   }
-  e = tiled_b ? launch_bwd_tiled(g, (int)in_dtype, Q, K, bias, dphi, phi, lse, dQ, dK, st)
+  e = tiled_b ? launch_bwd_tiled(g, (int)in_dtype, g_math_mode == 1, Q, K, bias, dphi, phi, lse, dQ, dK, st)
             : launch_bwd_generic(g, (int)in_dtype, Q, K, bias, dphi, phi, lse, dQ, dK, st);
   if (e != hipSuccess) return MODET_ERR_LAUNCH;
   if (dbias) {
@@ -122,6 +123,12 @@ int modet_warp(const void* src, const float* field, void* out,
 int modet_set_kernel_path(int path) {
   int old = g_kernel_path;
   g_kernel_path = path == 1 ? 1 : 0;
+  return old;
+}
+
+int modet_set_math_mode(int mode) {
+  int old = g_math_mode;
+  g_math_mode = mode == 1 ? 1 : 0;
   return old;
 }
 

@@ -534,7 +534,11 @@ march_kernel(TiledParams p) {
   typedef typename Pol::P P;
   typedef typename Pol::T T;
   constexpr int KW = Pol::KW, HS = Pol::HS, R = KW / 2;
+#ifdef MODET_NOROT
+  constexpr bool ROT = false;
+#else
   constexpr bool ROT = (KW == 3);
+#endif
   __shared__ SharedPlanes<Pol, Pol::kStats> sh;
 
   const Tile t = make_tile(p);
@@ -673,7 +677,14 @@ bool tiled_bwd_supported(int d, int heads, int k, int dtype, bool has_bias) {
 }
 
 #define MODET_DISPATCH(CALL)                                                     \
-  if (g.k == 3 && dtype == 0) {                                                  \
+  if (g.k == 3 && dtype == 0 && fast_logits) {                                   \
+    switch (g.heads) {                                                           \
+      case 1: return CALL(3, 1, float, float);                                   \
+      case 2: return CALL(3, 2, float, float);                                   \
+      case 4: return CALL(3, 4, float, float);                                   \
+      case 8: return CALL(3, 8, float, float);                                   \
+    }                                                                            \
+  } else if (g.k == 3 && dtype == 0) {                                           \
     switch (g.heads) {                                                           \
       case 1: return CALL(3, 1, float, double);                                  \
       case 2: return CALL(3, 2, float, double);                                  \
@@ -695,17 +706,17 @@ bool tiled_bwd_supported(int d, int heads, int k, int dtype, bool has_bias) {
   }                                                                              \
   return hipErrorNotSupported;
 
-hipError_t launch_fwd_tiled(const Geo& g, int dtype, const void* Q, const void* K, const float* bias,
-                            float* phi, float* lse, hipStream_t st) {
+hipError_t launch_fwd_tiled(const Geo& g, int dtype, bool fast_logits, const void* Q, const void* K,
+                            const float* bias, float* phi, float* lse, hipStream_t st) {
   (void)bias;
 #define MODET_FWD(KW, HS, T, LT) launch_fwd_t<KW, HS, T, LT>(g, Q, K, phi, lse, st)
   MODET_DISPATCH(MODET_FWD)
 #undef MODET_FWD
 }
 
-hipError_t launch_bwd_tiled(const Geo& g, int dtype, const void* Q, const void* K, const float* bias,
-                            const float* dphi, const float* phi, const float* lse, float* dQ, float* dK,
-                            hipStream_t st) {
+hipError_t launch_bwd_tiled(const Geo& g, int dtype, bool fast_logits, const void* Q, const void* K,
+                            const float* bias, const float* dphi, const float* phi, const float* lse, float* dQ,
+                            float* dK, hipStream_t st) {
   (void)bias;
 #define MODET_BWD(KW, HS, T, LT) launch_bwd_t<KW, HS, T, LT>(g, Q, K, dphi, phi, lse, dQ, dK, st)
   MODET_DISPATCH(MODET_BWD)

@@ -18,7 +18,7 @@ LIB_PATH = os.environ.get("MODET_LIBRARY") or os.path.join(_HERE, "libmodet.so")
 MODET_F32, MODET_BF16 = 0, 1
 MODET_OK = 0
 
-EXPORTS = ("modet_fwd", "modet_bwd", "modet_bwd_workspace_bytes", "modet_warp", "modet_set_kernel_path",
+EXPORTS = ("modet_fwd", "modet_bwd", "modet_bwd_workspace_bytes", "modet_warp", "modet_set_kernel_path", "modet_set_math_mode",
            "modet_has_tiled_kernels", "modet_status_string", "modet_version")
 
 if not os.path.exists(LIB_PATH):
@@ -37,6 +37,8 @@ _lib.modet_warp.argtypes = [_vp] * 3 + [_ci] * 5 + [_ci, _ci, _vp]
 _lib.modet_warp.restype = _ci
 _lib.modet_set_kernel_path.argtypes = [_ci]
 _lib.modet_set_kernel_path.restype = _ci
+_lib.modet_set_math_mode.argtypes = [_ci]
+_lib.modet_set_math_mode.restype = _ci
 _lib.modet_has_tiled_kernels.argtypes = [_ci] * 4
 _lib.modet_has_tiled_kernels.restype = _ci
 _lib.modet_status_string.argtypes = [_ci]
@@ -60,6 +62,11 @@ def modet_version() -> int:
 
 def modet_set_kernel_path(path: int) -> int:
     return int(_lib.modet_set_kernel_path(int(path)))
+
+
+def modet_set_math_mode(mode: int) -> int:
+    """0 = fp64 logits for fp32 inputs (default), 1 = fp32 logits (faster, ~1e-6 logit rounding)."""
+    return int(_lib.modet_set_math_mode(int(mode)))
 
 
 def modet_has_tiled_kernels(C: int, heads: int, k: int, dtype: int = MODET_F32) -> int:

@@ -105,6 +105,25 @@ def test_explicit_scale_and_peaked_attention(modet):
         assert np.abs(phi - ref).max() < 5e-2
 
 
+def test_fp32_logit_mode_is_close_but_outside_the_bar(modet):
+    """the optional fp32-logit arithmetic: same answers to a few 1e-6, which is why it is not the default."""
+    c = synth.make_case(1, 24, 40, 70, 8, 1, 3, keys="displaced", m=1, seed=21)
+    Q, K, g = up(c["Q"]), up(c["K"]), up(c["dphi"])
+    ref_phi = oracle.modet_fwd(c["Q"], c["K"], 1, 3)
+    ref_dQ, ref_dK = oracle.modet_bwd(c["Q"], c["K"], c["dphi"], 1, 3)
+    old = modet.modet_set_math_mode(1)
+    try:
+        phi, lse = modet.modet_fwd(Q, K, 1, 3, want_lse=True)
+        dQ, dK = modet.modet_bwd(Q, K, g, 1, 3, phi=phi, lse=lse)
+    finally:
+        assert modet.modet_set_math_mode(old) == 1
+    from parity_util import worst
+    for name, got, ref in (("phi", phi, ref_phi), ("dQ", dQ, ref_dQ), ("dK", dK, ref_dK)):
+        w = worst(got.cpu().numpy(), ref, 1e-5, 1e-6)
+        print(f"fp32-logit mode {name}: worst error {w:.2f} x tolerance")
+        assert w < 10.0
+
+
 def test_zero_query_is_uniform_everywhere(modet):
     K = up(synth.normal(6, 0, (1, 6, 7, 66, 8)))
     for path in (0, 1):
