@@ -63,6 +63,18 @@ __device__ __forceinline__ unsigned xcd_remap(unsigned id, unsigned n) {
   return xcd * q + (xcd < rem ? xcd : rem) + k;
 }
 
+#ifdef MODET_PROFILE
+// debugging aid: per-wave time stamps of the first workgroups (not built by default)
+__device__ long long g_dbg[64 * 4 * 32 * 8];
+__device__ __forceinline__ void stamp(int step, int slot) {
+  if (blockIdx.x < 64 && (threadIdx.x & 63) == 0 && step < 32)
+    g_dbg[((blockIdx.x * 4 + threadIdx.x / 64) * 32 + step) * 8 + slot] = clock64();
+}
+#define MODET_STAMP(step, slot) stamp(step, slot)
+#else
+#define MODET_STAMP(step, slot) do { } while (0)
+#endif
+
 struct Tile {
   int b, z0, z1, y0, xs0, tx, ty, xs, y;
   bool lane_ok;
@@ -128,6 +140,7 @@ template <> struct Lds<double> {
 template <class T> struct Ld;
 template <> struct Ld<float> {
   static __device__ __forceinline__ float4 vec4(const float* p) { return *reinterpret_cast<const float4*>(p); }
+  static __device__ __forceinline__ float one(const float* p) { return *p; }
 };
 template <> struct Ld<bf16_t> {
   static __device__ __forceinline__ float4 vec4(const bf16_t* p) {
@@ -135,15 +148,20 @@ template <> struct Ld<bf16_t> {
     return make_float4(__uint_as_float(t.x << 16), __uint_as_float(t.x & 0xFFFF0000u),
                        __uint_as_float(t.y << 16), __uint_as_float(t.y & 0xFFFF0000u));
   }
+  static __device__ __forceinline__ float one(const bf16_t* p) { return __uint_as_float(((uint32_t)*p) << 16); }
 };
 
-// stages one haloed plane of an [.., H, Wh, 8] tensor: global -> registers (fetch), registers -> LDS (commit)
+// stages one haloed plane of an [.., H, Wh, 8] tensor: global -> registers (fetch), registers -> LDS (commit).
+// The loads are unconditional (slots outside the volume read a clamped, valid address and are zeroed when
+// committed): a load under a branch makes the compiler wait for it at the end of the branch, which would
+// expose the whole memory latency in every step.
 template <int KW, int HS, class T, class ET>
 struct Stager {
   typedef Patch<KW, HS> P;
-  int goff[P::NL];      // element offset inside a plane, or -1: outside the volume / unused slot
-  int loff[P::NL];      // (position << 1 | half) inside the patch, or -1 when unused
+  int goff[P::NL];      // element offset inside a plane (clamped into the plane)
+  int loff[P::NL];      // (position << 2 | half << 1 | inside-the-volume) inside the patch, or -1 when unused
   float4 v[P::NL];
+  bool plane_ok;
 
   __device__ __forceinline__ void init(int tid, int y0, int xs0, int H, int Wh) {
 #pragma unroll
@@ -154,31 +172,40 @@ struct Stager {
       const int gy = y0 - P::R + pr, gx = xs0 - P::R * HS + pc;
       const bool used = e < P::NV;
       const bool in = used && gy >= 0 && gy < H && gx >= 0 && gx < Wh;
-      goff[i] = in ? (gy * Wh + gx) * 8 + hv * 4 : -1;
-      loff[i] = used ? (pos << 1 | hv) : -1;
+      const int cy = min(max(gy, 0), H - 1), cx = min(max(gx, 0), Wh - 1);
+      goff[i] = (cy * Wh + cx) * 8 + hv * 4;
+      loff[i] = used ? (pos << 2 | hv << 1 | (in ? 1 : 0)) : -1;
     }
+    plane_ok = false;
   }
-  // plane == nullptr: the plane lies outside the volume (zero padding)
-  __device__ __forceinline__ void fetch(const T* plane) {
+  // `plane` must point at a plane inside the tensor; ok = false: the wanted plane lies outside the volume
+  // (zero padding) and the loaded values are discarded
+  __device__ __forceinline__ void fetch(const T* plane, bool ok) {
 #pragma unroll
-    for (int i = 0; i < P::NL; ++i)
-      v[i] = (plane && goff[i] >= 0) ? Ld<T>::vec4(plane + goff[i]) : make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int i = 0; i < P::NL; ++i) v[i] = Ld<T>::vec4(plane + goff[i]);
+    plane_ok = ok;
   }
   __device__ __forceinline__ void commit(typename Lds<ET>::chunk* buf) const {
 #pragma unroll
     for (int i = 0; i < P::NL; ++i)
-      if (loff[i] >= 0) Lds<ET>::put4(buf, P::NPOS, loff[i] >> 1, loff[i] & 1, v[i]);
+      if (loff[i] >= 0) {
+        const bool keep = plane_ok && (loff[i] & 1);
+        const float4 w = make_float4(keep ? v[i].x : 0.f, keep ? v[i].y : 0.f, keep ? v[i].z : 0.f,
+                                     keep ? v[i].w : 0.f);
+        Lds<ET>::put4(buf, P::NPOS, loff[i] >> 2, (loff[i] >> 1) & 1, w);
+      }
   }
 };
 
-// per-query statistics of a haloed patch: (-lse*log2e, g_D, g_H, g_W) and -g.phi; zeros outside the volume
+// per-query statistics of a haloed patch: (-lse*log2e, g_D, g_H, g_W) and -g.phi; zeros outside the volume.
+// Loads are unconditional from clamped addresses, like the Stager's.
 template <int KW, int HS>
 struct StatStager {
   typedef Patch<KW, HS> P;
-  int goff[P::NS];   // window index inside a plane, or -1
-  int loff[P::NS];
-  float4 a[P::NS];
-  float c[P::NS];
+  int goff[P::NS];   // window index inside a plane (clamped)
+  int loff[P::NS];   // (position << 1 | inside-the-volume), or -1
+  float lse[P::NS], g[P::NS][3], f[P::NS][3];
+  bool plane_ok;
 
   __device__ __forceinline__ void init(int tid, int y0, int xs0, int H, int Wh) {
 #pragma unroll
@@ -188,43 +215,50 @@ struct StatStager {
       const int gy = y0 - P::R + pr, gx = xs0 - P::R * HS + pc;
       const bool used = pos < P::NPOS;
       const bool in = used && gy >= 0 && gy < H && gx >= 0 && gx < Wh;
-      goff[i] = in ? gy * Wh + gx : -1;
-      loff[i] = used ? pos : -1;
+      const int cy = min(max(gy, 0), H - 1), cx = min(max(gx, 0), Wh - 1);
+      goff[i] = cy * Wh + cx;
+      loff[i] = used ? (pos << 1 | (in ? 1 : 0)) : -1;
     }
+    plane_ok = false;
   }
-  // base = window index of (b, z, 0, 0); pass ok = false for planes outside the volume
+  // base = window index of (b, z, 0, 0) of a plane inside the volume; ok as in Stager::fetch
   __device__ __forceinline__ void fetch(const TiledParams& p, long long base, bool ok) {
 #pragma unroll
     for (int i = 0; i < P::NS; ++i) {
-      if (ok && goff[i] >= 0) {
-        const long long w = base + goff[i];
-        const float* g = p.dphi + w * 3;
-        const float* f = p.phi_in + w * 3;
-        const float g0 = g[0], g1 = g[1], g2 = g[2];
-        a[i] = make_float4(-p.lse_in[w] * kLog2e, g0, g1, g2);
-        c[i] = -(g0 * f[0] + g1 * f[1] + g2 * f[2]);
-      } else {
-        a[i] = make_float4(0.f, 0.f, 0.f, 0.f);
-        c[i] = 0.f;
-      }
+      const long long w = base + goff[i];
+      const float* gp = p.dphi + w * 3;
+      const float* fp = p.phi_in + w * 3;
+      lse[i] = p.lse_in[w];
+      g[i][0] = gp[0]; g[i][1] = gp[1]; g[i][2] = gp[2];
+      f[i][0] = fp[0]; f[i][1] = fp[1]; f[i][2] = fp[2];
     }
+    plane_ok = ok;
   }
   __device__ __forceinline__ void commit(float4* sa, float* sc) const {
 #pragma unroll
     for (int i = 0; i < P::NS; ++i)
-      if (loff[i] >= 0) { sa[loff[i]] = a[i]; sc[loff[i]] = c[i]; }
+      if (loff[i] >= 0) {
+        const bool keep = plane_ok && (loff[i] & 1);
+        const float g0 = keep ? g[i][0] : 0.f, g1 = keep ? g[i][1] : 0.f, g2 = keep ? g[i][2] : 0.f;
+        sa[loff[i] >> 1] = make_float4(keep ? -lse[i] * kLog2e : 0.f, g0, g1, g2);
+        sc[loff[i] >> 1] = -(g0 * f[i][0] + g1 * f[i][1] + g2 * f[i][2]);
+      }
   }
 };
 
-template <class T>
-__device__ __forceinline__ void load8(const T* p, bool ok, float (&q)[8]) {
-  if (ok) {
-    float4 a = Ld<T>::vec4(p), b = Ld<T>::vec4(p + 4);
-    q[0] = a.x; q[1] = a.y; q[2] = a.z; q[3] = a.w; q[4] = b.x; q[5] = b.y; q[6] = b.z; q[7] = b.w;
-  } else {
+// Makes the compiler treat x as read and rewritten here, so a load into x is waited for at this point of the
+// program and nowhere later.
+__device__ __forceinline__ void pin(float& x) { asm volatile("" : "+v"(x)); }
+__device__ __forceinline__ void pin(float (&x)[8]) {
 #pragma unroll
-    for (int c = 0; c < 8; ++c) q[c] = 0.f;
-  }
+  for (int i = 0; i < 8; ++i) pin(x[i]);
+}
+
+// unconditional (see Stager): p must be a valid address; the caller discards the values where they are not wanted
+template <class T>
+__device__ __forceinline__ void load8(const T* p, float (&q)[8]) {
+  const float4 a = Ld<T>::vec4(p), b = Ld<T>::vec4(p + 4);
+  q[0] = a.x; q[1] = a.y; q[2] = a.z; q[3] = a.w; q[4] = b.x; q[5] = b.y; q[6] = b.z; q[7] = b.w;
 }
 
 // sum_c q[c] * v[c] (+ init), accumulated in LT
@@ -277,7 +311,48 @@ __device__ __forceinline__ unsigned active_roles(int s, int z0, int z1) {
 // z = s - R + i while LDS plane s is current; it is complete after step z + R.
 // =================================================================================================
 
-// ---- forward: lane owns a query column; K planes in LDS (in LT); online softmax per window row --------
+// ---- forward: lane owns a query column; K planes in LDS (in LT); softmax sums against a fixed reference ----
+// The weights of a query are exp2(l - ref) with ONE reference per query, the largest logit of the first
+// window row it meets: no running maximum is maintained, nothing is rescaled from row to row, and the inner
+// loop has no branches.  phi = S / Z does not depend on the reference.  A logit more than ~2^7 above the
+// reference (far outside what normalised features produce) overflows fp32 and makes Z non-finite; such a
+// query is recomputed on its own with a two-pass softmax when it is stored.
+
+// Eq. 3-4 for one query straight from global memory, all in fp64 (the rare path of the above).
+template <int KW, int HS, class T>
+__device__ void fwd_query_two_pass(const TiledParams& p, long long w) {
+  constexpr int R = KW / 2;
+  long long r = w;
+  const int xs = (int)(r % p.Wh); r /= p.Wh;
+  const int y = (int)(r % p.H); r /= p.H;
+  const int z = (int)(r % p.D);
+  const T* Qp = (const T*)p.Q + w * 8;     // re-read per offset: this path is rare, keep it small in registers
+  double mx = -INFINITY, Z = 0.0, S0 = 0.0, S1 = 0.0, S2 = 0.0;
+#pragma unroll 1
+  for (int pass = 0; pass < 2; ++pass)
+#pragma unroll 1
+    for (int j = 0; j < KW * KW * KW; ++j) {
+      const int a = j / (KW * KW) - R, bb = (j / KW) % KW - R, cc = j % KW - R;
+      const int zz = z + a, yy = y + bb, xx = xs + cc * HS;
+      double l = 0.0;      // a neighbour outside the volume is a zero key
+      if (zz >= 0 && zz < p.D && yy >= 0 && yy < p.H && xx >= 0 && xx < p.Wh) {
+        const T* Kp = (const T*)p.K + (w + ((long long)a * p.H + bb) * p.Wh + cc * HS) * 8;
+#pragma unroll 1
+        for (int c = 0; c < 8; ++c) l = fma((double)Ld<T>::one(Qp + c), (double)Ld<T>::one(Kp + c), l);
+        l *= (double)p.qscale;
+      }
+      if (pass == 0) {
+        mx = fmax(mx, l);
+      } else {
+        const double e = (double)exp2_fast((float)(l - mx));
+        Z += e; S0 += a * e; S1 += bb * e; S2 += cc * e;
+      }
+    }
+  float* ph = p.phi + w * 3;
+  ph[0] = (float)(S0 / Z); ph[1] = (float)(S1 / Z); ph[2] = (float)(S2 / Z);
+  if (p.lse) p.lse[w] = (float)((mx + (double)log2_fast((float)Z)) * (double)kLn2);
+}
+
 template <int KW_, int HS_, class T_, class LT>
 struct FwdPolicy {
   static constexpr int KW = KW_, HS = HS_, R = KW_ / 2;
@@ -287,10 +362,11 @@ struct FwdPolicy {
   static constexpr bool kStats = false;
   struct State {
     LT q[8];            // Q * scale * log2e
-    float m;            // running maximum (log2 units)
-    LT Z, S0, S1, S2;   // sum of weights and of weight*offset, relative to m.  Kept in LT: phi feeds the
-  };                    // backward, where its error is multiplied by the upstream gradient
+    LT nref;            // minus the reference (log2 units); the dot products start from it
+    LT Z, S0, S1, S2;   // sum of weights and of weight*offset, relative to the reference.  Kept in LT: phi
+  };                    // feeds the backward, where its error is multiplied by the upstream gradient
   struct Pre { float q[8]; };
+  static __device__ __forceinline__ void arrived(Pre& a) { pin(a.q); }
 
   static __device__ __forceinline__ const T* lds_operand(const TiledParams& p) { return (const T*)p.K; }
   static __device__ __forceinline__ const T* own_operand(const TiledParams& p) { return (const T*)p.Q; }
@@ -298,39 +374,50 @@ struct FwdPolicy {
   static __device__ __forceinline__ void reset(State& s) {
 #pragma unroll
     for (int c = 0; c < 8; ++c) s.q[c] = (LT)0;
-    s.m = -INFINITY; s.Z = (LT)0; s.S0 = (LT)0; s.S1 = (LT)0; s.S2 = (LT)0;
+    s.nref = (LT)0; s.Z = (LT)0; s.S0 = (LT)0; s.S1 = (LT)0; s.S2 = (LT)0;
   }
-  static __device__ __forceinline__ void prefetch(const TiledParams&, const T* own, long long, bool ok, Pre& pre) {
-    load8<T>(own, ok, pre.q);
+  static __device__ __forceinline__ void prefetch(const TiledParams&, const T* own, long long, Pre& pre) {
+    load8<T>(own, pre.q);
   }
   static __device__ __forceinline__ void refill(State& s, const Pre& pre, const TiledParams& p) {
 #pragma unroll
     for (int c = 0; c < 8; ++c) s.q[c] = (LT)pre.q[c] * (LT)p.qscale;
-    s.m = -INFINITY; s.Z = (LT)0; s.S0 = (LT)0; s.S1 = (LT)0; s.S2 = (LT)0;
+    s.nref = (LT)0; s.Z = (LT)0; s.S0 = (LT)0; s.S1 = (LT)0; s.S2 = (LT)0;
   }
-  // fold one window row (in-plane offsets (b, -R..R), plane offset a) into the running softmax
-  static __device__ __forceinline__ void fold_row(State& s, const LT (&l)[KW], int a, int b) {
-    float mx = s.m;
+  // Fold one window row (in-plane row offset b) into the sums.  l holds the logits MINUS the reference (the dot
+  // products started from nref); FIRST: the first row this query meets, whose l is relative to zero and which
+  // fixes the reference.  The row sum goes to `plane` (the caller adds the plane's total to Z and S0 once).
+  template <bool FIRST>
+  static __device__ __forceinline__ void fold_row(State& s, LT (&l)[KW], LT& plane, int b) {
+    if (FIRST) {
+      float mx = (float)l[0];
 #pragma unroll
-    for (int c = 0; c < KW; ++c) mx = fmaxf(mx, (float)l[c]);
-    const float alpha = exp2_fast(s.m - mx);
+      for (int c = 1; c < KW; ++c) mx = fmaxf(mx, (float)l[c]);
+      s.nref = -(LT)mx;
+#pragma unroll
+      for (int c = 0; c < KW; ++c) l[c] -= (LT)mx;
+    }
     float rs = 0.f, ws = 0.f;
 #pragma unroll
     for (int c = 0; c < KW; ++c) {
-      const float e = exp2_fast((float)(l[c] - (LT)mx));
+      const float e = exp2_fast((float)l[c]);
       rs += e;
       if (c != R) ws = fmaf((float)(c - R), e, ws);
     }
-    const LT al = (LT)alpha, rr = (LT)rs;
-    s.Z = fma(s.Z, al, rr);
-    s.S0 = a == 0 ? s.S0 * al : fma(s.S0, al, (LT)a * rr);
-    s.S1 = b == 0 ? s.S1 * al : fma(s.S1, al, (LT)b * rr);
-    s.S2 = fma(s.S2, al, (LT)ws);
-    s.m = mx;
+    const LT rr = (LT)rs;
+    plane += rr;
+    if (b != 0) s.S1 = fma((LT)b, rr, s.S1);
+    s.S2 += (LT)ws;
   }
   template <int PH, bool FULL, class Sh>
   static __device__ __forceinline__ void step(State (&st)[KW], const Sh& sh, int cur, int lbase, unsigned active) {
     const typename Lds<ET>::chunk* kb = sh.main[cur];
+#ifdef MODET_PROFILE
+    const int g_dbg_step = sh.dbg_step;
+#endif
+    LT plane[KW];      // per role: sum of the weights of this plane of its window
+#pragma unroll
+    for (int i = 0; i < KW; ++i) plane[i] = (LT)0;
 #pragma unroll
     for (int b = 0; b < KW; ++b) {
       LT l[KW][KW];   // [role][col] of this window row
@@ -340,19 +427,38 @@ struct FwdPolicy {
         Lds<ET>::get8(kb, P::NPOS, lbase + b * P::PC + c * HS, kv);
 #pragma unroll
         for (int i = 0; i < KW; ++i)
-          if (FULL || (active & (1u << i))) l[i][c] = dot8<LT>(st[(i + PH) % KW].q, kv);
+          if (FULL || (active & (1u << i))) l[i][c] = dot8<LT>(st[(i + PH) % KW].q, kv, st[(i + PH) % KW].nref);
       }
+      // role KW-1 is the plane that entered last: this step shows it the first plane of its window
 #pragma unroll
       for (int i = 0; i < KW; ++i)
-        if (FULL || (active & (1u << i))) fold_row(st[(i + PH) % KW], l[i], R - i, b - R);
+        if (FULL || (active & (1u << i))) {
+          if (i == KW - 1 && b == 0) fold_row<true>(st[(i + PH) % KW], l[i], plane[i], b - R);
+          else fold_row<false>(st[(i + PH) % KW], l[i], plane[i], b - R);
+        }
+#ifdef MODET_PROFILE
+      if (b < 3) MODET_STAMP(g_dbg_step, 1 + b);
+#endif
     }
+#pragma unroll
+    for (int i = 0; i < KW; ++i)
+      if (FULL || (active & (1u << i))) {
+        State& s = st[(i + PH) % KW];
+        s.Z += plane[i];
+        if (R - i != 0) s.S0 = fma((LT)(R - i), plane[i], s.S0);
+      }
   }
   static __device__ __forceinline__ void store(const State& s, const TiledParams& p, long long w) {
-    LT inv = (LT)__builtin_amdgcn_rcpf((float)s.Z);
+    const float zf = (float)s.Z;
+    if (!(zf >= 1e-30f && zf <= 1e30f)) {     // overflowed, all underflowed, or NaN: this query alone, safely
+      fwd_query_two_pass<KW, HS, T>(p, w);
+      return;
+    }
+    LT inv = (LT)__builtin_amdgcn_rcpf(zf);
     inv = inv * ((LT)2 - s.Z * inv);          // one Newton step: relative error ~1e-14 in fp64
     float* ph = p.phi + w * 3;
     ph[0] = (float)(s.S0 * inv); ph[1] = (float)(s.S1 * inv); ph[2] = (float)(s.S2 * inv);
-    if (p.lse) p.lse[w] = (s.m + log2_fast((float)s.Z)) * kLn2;
+    if (p.lse) p.lse[w] = (float)(((LT)log2_fast(zf) - s.nref) * (LT)kLn2);
   }
 };
 
@@ -371,6 +477,10 @@ struct DqPolicy {
     float acc[8];
   };
   struct Pre { float q[8]; float lse, g0, g1, g2, f0, f1, f2; };
+  static __device__ __forceinline__ void arrived(Pre& a) {
+    pin(a.q);
+    pin(a.lse); pin(a.g0); pin(a.g1); pin(a.g2); pin(a.f0); pin(a.f1); pin(a.f2);
+  }
 
   static __device__ __forceinline__ const T* lds_operand(const TiledParams& p) { return (const T*)p.K; }
   static __device__ __forceinline__ const T* own_operand(const TiledParams& p) { return (const T*)p.Q; }
@@ -380,17 +490,12 @@ struct DqPolicy {
     for (int c = 0; c < 8; ++c) { s.q[c] = (LT)0; s.acc[c] = 0.f; }
     s.nlse = (LT)0; s.g0 = s.g1 = s.g2 = s.ngphi = 0.f;
   }
-  static __device__ __forceinline__ void prefetch(const TiledParams& p, const T* own, long long w, bool ok,
-                                                  Pre& a) {
-    load8<T>(own, ok, a.q);
-    if (ok) {
-      a.lse = p.lse_in[w];
-      const float* g = p.dphi + w * 3;
-      const float* f = p.phi_in + w * 3;
-      a.g0 = g[0]; a.g1 = g[1]; a.g2 = g[2]; a.f0 = f[0]; a.f1 = f[1]; a.f2 = f[2];
-    } else {
-      a.lse = a.g0 = a.g1 = a.g2 = a.f0 = a.f1 = a.f2 = 0.f;
-    }
+  static __device__ __forceinline__ void prefetch(const TiledParams& p, const T* own, long long w, Pre& a) {
+    load8<T>(own, a.q);
+    a.lse = p.lse_in[w];
+    const float* g = p.dphi + w * 3;
+    const float* f = p.phi_in + w * 3;
+    a.g0 = g[0]; a.g1 = g[1]; a.g2 = g[2]; a.f0 = f[0]; a.f1 = f[1]; a.f2 = f[2];
   }
   static __device__ __forceinline__ void refill(State& s, const Pre& a, const TiledParams& p) {
 #pragma unroll
@@ -444,6 +549,7 @@ struct DkPolicy {
     float acc[8];
   };
   struct Pre { float k[8]; };
+  static __device__ __forceinline__ void arrived(Pre& a) { pin(a.k); }
 
   static __device__ __forceinline__ const T* lds_operand(const TiledParams& p) { return (const T*)p.Q; }
   static __device__ __forceinline__ const T* own_operand(const TiledParams& p) { return (const T*)p.K; }
@@ -452,8 +558,8 @@ struct DkPolicy {
 #pragma unroll
     for (int c = 0; c < 8; ++c) { s.k[c] = (LT)0; s.acc[c] = 0.f; }
   }
-  static __device__ __forceinline__ void prefetch(const TiledParams&, const T* own, long long, bool ok, Pre& pre) {
-    load8<T>(own, ok, pre.k);
+  static __device__ __forceinline__ void prefetch(const TiledParams&, const T* own, long long, Pre& pre) {
+    load8<T>(own, pre.k);
   }
   static __device__ __forceinline__ void refill(State& s, const Pre& pre, const TiledParams& p) {
 #pragma unroll
@@ -497,6 +603,9 @@ struct DkPolicy {
 template <class Pol, bool STATS> struct SharedPlanes;
 template <class Pol> struct SharedPlanes<Pol, false> {
   typename Lds<typename Pol::ET>::chunk main[2][Lds<typename Pol::ET>::CH * Pol::P::NPOS];
+#ifdef MODET_PROFILE
+  int dbg_step;
+#endif
 };
 template <class Pol> struct SharedPlanes<Pol, true> {
   typename Lds<typename Pol::ET>::chunk main[2][Lds<typename Pol::ET>::CH * Pol::P::NPOS];
@@ -506,18 +615,24 @@ template <class Pol> struct SharedPlanes<Pol, true> {
 
 template <class Pol, int PH, class Sh, class Stg, class SStg>
 __device__ __forceinline__ void march_body(typename Pol::State (&st)[Pol::KW], const TiledParams& p, const Tile& t,
-                                           Sh& sh, int cur, int lbase, int s, const typename Pol::Pre& pre,
+                                           Sh& sh, int cur, int lbase, int s, typename Pol::Pre& pre,
                                            bool have_next, bool commit_next, const Stg& stg, const SStg& sst) {
   constexpr int KW = Pol::KW, R = KW / 2;
   const unsigned active = active_roles<KW>(s, t.z0, t.z1);
+  MODET_STAMP(s - (t.z0 - R), 0);
   if (active == (1u << KW) - 1u) Pol::template step<PH, true>(st, sh, cur, lbase, active);
   else Pol::template step<PH, false>(st, sh, cur, lbase, active);
+  MODET_STAMP(s - (t.z0 - R), 4);
   // the staged plane goes to LDS before the results are stored: the wait for its loads would otherwise
   // also wait for those stores (one counter covers loads and stores on this chip)
   if (commit_next) {
     stg.commit(sh.main[cur ^ 1]);
     if constexpr (Pol::kStats) sst.commit(sh.sa[cur ^ 1], sh.sc[cur ^ 1]);
   }
+  MODET_STAMP(s - (t.z0 - R), 5);
+  // All loads of this step end here, before the stores are issued: a wait placed after the stores (or at the
+  // top of the next step, when the refill below is skipped) would wait for the stores as well.
+  Pol::arrived(pre);
   typename Pol::State& done = st[PH % KW];     // role 0 is complete: it has seen planes z-R .. z+R
   if ((active & 1u) && t.lane_ok) Pol::store(done, p, t.col + (long long)(s - R) * p.H * p.Wh);
   if (have_next) Pol::refill(done, pre, p);     // the freed slot takes the plane s + R + 1
@@ -527,6 +642,8 @@ struct NoStats {
   __device__ __forceinline__ void init(int, int, int, int, int) {}
   __device__ __forceinline__ void fetch(const TiledParams&, long long, bool) {}
 };
+
+__device__ __forceinline__ int clampi(int v, int lo, int hi) { return min(max(v, lo), hi); }
 
 template <class Pol, int WAVES>
 __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(WAVES)))
@@ -543,7 +660,10 @@ march_kernel(TiledParams p) {
 
   const Tile t = make_tile(p);
   const T* Lb = Pol::lds_operand(p) + (long long)t.b * p.D * t.plane_elems;
-  const T* Ob = Pol::own_operand(p) + (long long)t.b * p.D * t.plane_elems + ((long long)t.y * p.Wh + t.xs) * 8;
+  // lanes outside the volume compute on a clamped (valid) column and never store
+  const int cy = min(t.y, p.H - 1), cxs = min(t.xs, p.Wh - 1);
+  const T* Ob = Pol::own_operand(p) + (long long)t.b * p.D * t.plane_elems + ((long long)cy * p.Wh + cxs) * 8;
+  const long long ccol = (long long)t.b * p.D * p.H * p.Wh + (long long)cy * p.Wh + cxs;
   const long long pw = (long long)p.H * p.Wh;
   const long long wb = (long long)t.b * p.D * pw;    // window index of (b, 0, 0, 0)
   const int lbase = t.ty * P::PC + t.tx;             // patch position of the window corner of this lane
@@ -558,33 +678,42 @@ march_kernel(TiledParams p) {
   for (int i = 0; i < KW; ++i) Pol::reset(st[i]);
   {
     typename Pol::Pre pre;
-    Pol::prefetch(p, Ob + (long long)t.z0 * t.plane_elems, t.col + t.z0 * pw, t.lane_ok, pre);
+    Pol::prefetch(p, Ob + (long long)t.z0 * t.plane_elems, ccol + t.z0 * pw, pre);
     Pol::refill(st[KW - 1], pre, p);
   }
   const int s_first = t.z0 - R, s_last = t.z1 - 1 + R;
+  // Loads run one step ahead of their use and are issued at the END of a step, right after the registers
+  // they land in were consumed: they are in flight across the barrier and the whole next step.  All of them
+  // are unconditional and read clamped (valid) planes; what lies outside the volume or is not wanted is
+  // discarded where it is consumed.
+  typename Pol::Pre pre;
+  auto issue_loads = [&](int s) {    // for step s: the plane s + 1 to stage and the plane s + R + 1 to refill
+    const int sn = s + 1;
+    const int zs = clampi(sn, 0, p.D - 1);
+    stg.fetch(Lb + (long long)zs * t.plane_elems, sn >= 0 && sn < p.D);
+    sst.fetch(p, wb + (long long)zs * pw, sn >= 0 && sn < p.D);
+    const int zo = min(s + R + 1, p.D - 1);
+    Pol::prefetch(p, Ob + (long long)zo * t.plane_elems, ccol + zo * pw, pre);
+  };
   {
     const bool ok = s_first >= 0;
-    stg.fetch(ok ? Lb + (long long)s_first * t.plane_elems : nullptr);
-    sst.fetch(p, wb + (long long)s_first * pw, ok);
+    const int zc = clampi(s_first, 0, p.D - 1);
+    stg.fetch(Lb + (long long)zc * t.plane_elems, ok);
+    sst.fetch(p, wb + (long long)zc * pw, ok);
     stg.commit(sh.main[0]);
     if constexpr (Pol::kStats) sst.commit(sh.sa[0], sh.sc[0]);
   }
+  issue_loads(s_first);
   __syncthreads();
 
   int ph = 0;
   for (int s = s_first; s <= s_last; ++s) {
     const int cur = (s - s_first) & 1;
-    const int sn = s + 1;
-    const bool commit_next = sn <= s_last;
-    if (commit_next) {
-      const bool ok = sn >= 0 && sn < p.D;
-      stg.fetch(ok ? Lb + (long long)sn * t.plane_elems : nullptr);
-      sst.fetch(p, wb + (long long)sn * pw, ok);
-    }
-    const int zn = s + R + 1;
-    const bool have_next = zn < t.z1;
-    typename Pol::Pre pre;
-    Pol::prefetch(p, Ob + (long long)zn * t.plane_elems, t.col + zn * pw, t.lane_ok && have_next, pre);
+    const bool commit_next = s + 1 <= s_last;
+    const bool have_next = s + R + 1 < t.z1;
+#ifdef MODET_PROFILE
+    if constexpr (!Pol::kStats) { if (threadIdx.x == 0) sh.dbg_step = s - s_first; }
+#endif
 
     if (ROT) {
       switch (ph) {
@@ -601,7 +730,10 @@ march_kernel(TiledParams p) {
       for (int i = 0; i + 1 < KW; ++i) st[i] = st[i + 1];
       st[KW - 1] = tmp;
     }
+    issue_loads(s + 1);
+    MODET_STAMP(s - s_first, 6);
     __syncthreads();
+    MODET_STAMP(s - s_first, 7);
   }
 }
 
@@ -610,20 +742,53 @@ march_kernel(TiledParams p) {
 #define MODET_WAVES 2
 #endif
 
-TiledParams make_params(const Geo& g) {
+int compute_units() {
+  static int n = 0;
+  if (n == 0) {
+    int dev = 0, v = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
+      n = v;
+    else
+      n = 256;
+  }
+  return n;
+}
+
+// Chunk length along D.  A workgroup marches through zc + k - 1 planes, and `slots` workgroups are resident at
+// a time (compute units x the workgroups of this kernel that fit one CU).  The cost of a
+// split is the number of plane steps the busiest slot runs: full rounds of resident workgroups, plus a last,
+// partly filled round that counts half when it leaves at least half of the slots empty (a workgroup alone on
+// its CU steps faster).  Short chunks are avoided because each re-reads k - 1 planes.
+int chunk_length(long long tiles, int D, int k, int wgs_per_cu) {
+  const long long slots = (long long)compute_units() * wgs_per_cu;
+  const int min_zc = D < 8 ? D : 8;
+  int best_zc = D;
+  double best = 1e30;
+  for (int nz = 1; nz <= D; ++nz) {
+    const int zc = (D + nz - 1) / nz;
+    if (zc < min_zc) break;
+    if ((D + zc - 1) / zc != nz) continue;      // the same split as a smaller nz
+    const long long wgs = tiles * nz, full = wgs / slots, rem = wgs % slots;
+    const int steps = zc + k - 1;
+    double cost = (double)full * steps + (rem == 0 ? 0.0 : (2 * rem <= slots ? 0.5 : 1.0) * steps);
+    if (wgs < slots) cost = (wgs * 2 <= slots ? 0.5 : 1.0) * steps;
+    if (cost < best - 1e-9) { best = cost; best_zc = zc; }
+  }
+  return best_zc;
+}
+
+TiledParams make_params(const Geo& g, int wgs_per_cu) {
   TiledParams p = {};
   p.B = g.B; p.D = g.D; p.H = g.H; p.Wh = g.W * g.heads;
   p.ntx = (p.Wh + TX - 1) / TX;
   p.nty = (g.H + TY - 1) / TY;
-  // enough chunks along D to give every CU several workgroups (4 per CU on 256 CUs), but not so short
-  // that the k-1 extra planes per chunk dominate
-  const long long tiles = (long long)p.ntx * p.nty * g.B;
-  int zc = 16;
-  while (zc > 4 && tiles * ((g.D + zc - 1) / zc) < 1024) zc >>= 1;
+  int zc = chunk_length((long long)p.ntx * p.nty * g.B, g.D, g.k, wgs_per_cu);
 #ifdef MODET_TUNING_ENV
   if (const char* e = getenv("MODET_ZC")) zc = atoi(e);
 #endif
   if (zc > g.D) zc = g.D;
+  if (zc < 1) zc = 1;
   p.ZC = zc;
   p.nzc = (g.D + zc - 1) / zc;
   p.scale = g.scale;
@@ -638,30 +803,54 @@ inline unsigned nblocks(const TiledParams& p) { return (unsigned)((long long)p.n
 template <class LT, int KW> struct Waves { static constexpr int value = MODET_WAVES; };
 template <> struct Waves<float, 3> { static constexpr int value = 3; };
 
+// workgroups of one kernel instantiation that are resident on a CU (registers and LDS decide)
+template <class Pol, int WAVES>
+int resident_workgroups() {
+  static int n = 0;
+  if (n == 0) {
+    int v = 0;
+    n = (hipOccupancyMaxActiveBlocksPerMultiprocessor(&v, march_kernel<Pol, WAVES>, NT, 0) == hipSuccess && v > 0)
+            ? v : WAVES;
+  }
+  return n;
+}
+
+template <class Pol, int WAVES>
+void launch_march(const Geo& g, TiledParams io, hipStream_t st) {
+  TiledParams p = make_params(g, resident_workgroups<Pol, WAVES>());
+  p.Q = io.Q; p.K = io.K; p.phi = io.phi; p.lse = io.lse;
+  p.dphi = io.dphi; p.phi_in = io.phi_in; p.lse_in = io.lse_in; p.out = io.out;
+  hipLaunchKernelGGL((march_kernel<Pol, WAVES>), dim3(nblocks(p)), dim3(NT), 0, st, p);
+}
+
 template <int KW, int HS, class T, class LT>
 hipError_t launch_fwd_t(const Geo& g, const void* Q, const void* K, float* phi, float* lse, hipStream_t st) {
-  TiledParams p = make_params(g);
-  p.Q = Q; p.K = K; p.phi = phi; p.lse = lse;
-  hipLaunchKernelGGL((march_kernel<FwdPolicy<KW, HS, T, LT>, Waves<LT, KW>::value>), dim3(nblocks(p)), dim3(NT), 0,
-                     st, p);
+  TiledParams io = {};
+  io.Q = Q; io.K = K; io.phi = phi; io.lse = lse;
+  launch_march<FwdPolicy<KW, HS, T, LT>, Waves<LT, KW>::value>(g, io, st);
   return hipGetLastError();
 }
 
 template <int KW, int HS, class T, class LT>
 hipError_t launch_bwd_t(const Geo& g, const void* Q, const void* K, const float* dphi, const float* phi,
                         const float* lse, float* dQ, float* dK, hipStream_t st) {
-  TiledParams p = make_params(g);
-  p.Q = Q; p.K = K; p.dphi = dphi; p.phi_in = phi; p.lse_in = lse;
-  p.out = dQ;
-  hipLaunchKernelGGL((march_kernel<DqPolicy<KW, HS, T, LT>, Waves<LT, KW>::value>), dim3(nblocks(p)), dim3(NT), 0, st,
-                     p);
-  p.out = dK;
-  hipLaunchKernelGGL((march_kernel<DkPolicy<KW, HS, T, LT>, Waves<LT, KW>::value>), dim3(nblocks(p)), dim3(NT), 0, st,
-                     p);
+  TiledParams io = {};
+  io.Q = Q; io.K = K; io.dphi = dphi; io.phi_in = phi; io.lse_in = lse;
+  io.out = dQ;
+  launch_march<DqPolicy<KW, HS, T, LT>, Waves<LT, KW>::value>(g, io, st);
+  io.out = dK;
+  launch_march<DkPolicy<KW, HS, T, LT>, Waves<LT, KW>::value>(g, io, st);
   return hipGetLastError();
 }
 
 }  // namespace
+
+#ifdef MODET_PROFILE
+extern "C" void modet_debug_read(long long* host) {
+  (void)hipDeviceSynchronize();
+  (void)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_dbg), sizeof(long long) * 64 * 4 * 32 * 8);
+}
+#endif
 
 // Covered: head size 8, no bias;  k = 3: 1/2/4/8 heads, fp32 inputs (fp64 logits) and bf16 inputs (fp32
 // logits: the bf16 tolerance leaves room);  k = 5: 1/2 heads, bf16 inputs.

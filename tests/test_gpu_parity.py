@@ -105,6 +105,33 @@ def test_explicit_scale_and_peaked_attention(modet):
         assert np.abs(phi - ref).max() < 5e-2
 
 
+@pytest.mark.parametrize("dtype,heads,k", [("f32", 1, 3), ("f32", 2, 3), ("bf16", 2, 3), ("bf16", 1, 5)])
+def test_forward_survives_logits_far_above_the_first_window_row(modet, dtype, heads, k):
+    """The tiled forward measures every logit of a query against the largest one of the first window row it
+    meets.  Here half of the queries have their match in the LAST plane of the window with a logit ~400 (log2
+    units) above everything else, which overflows fp32 exponentials: those queries take the two-pass path and
+    must still agree with the oracle, the other half must be untouched by it."""
+    B, D, H, W, d = 1, 9, 12, 70, 8
+    r = k // 2
+    Q = synth.normal(31, 0, (B, D, H, W, heads, d), dtype=np.float64)
+    Q = (Q / np.linalg.norm(Q, axis=-1, keepdims=True)).reshape(B, D, H, W, heads * d).astype(np.float32)
+    K = (0.05 * synth.normal(31, 1, Q.shape)).astype(np.float32)
+    K[:, r:, :, : W // 2] = Q[:, :-r, :, : W // 2]          # K[p + (r, 0, 0)] = Q[p] for the left half
+    if dtype == "bf16":
+        Q, K = synth.to_bf16_bits(Q), synth.to_bf16_bits(K)
+    scale = 300.0
+    ref_phi, _, ref_lse = oracle.modet_fwd(Q, K, heads, k, scale=scale, dtype=dtype, want_attn=True, want_lse=True)
+    for path in (0, 1):
+        old = modet.modet_set_kernel_path(path)
+        phi, lse = modet.modet_fwd(up(Q, dtype), up(K, dtype), heads, k, scale=scale, want_lse=True)
+        modet.modet_set_kernel_path(old)
+        assert_close(phi.cpu().numpy(), ref_phi, dtype, f"phi path {path}")
+        np.testing.assert_allclose(lse.cpu().numpy(), ref_lse, rtol=2e-2 if dtype == "bf16" else 2e-6, atol=1e-5)
+    # the planted half really is (nearly always) one-hot on (r, 0, 0), the other half is not
+    assert np.median(np.abs(ref_phi[:, : D - r, :, : W // 2, :, 0] - r)) < 1e-9
+    assert np.median(np.abs(ref_phi[:, :, :, W // 2 + r:, :, 0] - r)) > 0.1
+
+
 def test_fp32_logit_mode_is_close_but_outside_the_bar(modet):
     """the optional fp32-logit arithmetic: same answers to a few 1e-6, which is why it is not the default."""
     c = synth.make_case(1, 24, 40, 70, 8, 1, 3, keys="displaced", m=1, seed=21)
