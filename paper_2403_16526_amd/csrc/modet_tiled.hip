@@ -63,18 +63,6 @@ __device__ __forceinline__ unsigned xcd_remap(unsigned id, unsigned n) {
   return xcd * q + (xcd < rem ? xcd : rem) + k;
 }
 
-#ifdef MODET_PROFILE
-// debugging aid: per-wave time stamps of the first workgroups (not built by default)
-__device__ long long g_dbg[64 * 4 * 32 * 8];
-__device__ __forceinline__ void stamp(int step, int slot) {
-  if (blockIdx.x < 64 && (threadIdx.x & 63) == 0 && step < 32)
-    g_dbg[((blockIdx.x * 4 + threadIdx.x / 64) * 32 + step) * 8 + slot] = clock64();
-}
-#define MODET_STAMP(step, slot) stamp(step, slot)
-#else
-#define MODET_STAMP(step, slot) do { } while (0)
-#endif
-
 struct Tile {
   int b, z0, z1, y0, xs0, tx, ty, xs, y;
   bool lane_ok;
@@ -82,9 +70,8 @@ struct Tile {
   long long col;           // window index of (b, z=0, y, xs): + z*H*Wh
 };
 
-__device__ __forceinline__ Tile make_tile(const TiledParams& p) {
+__device__ __forceinline__ Tile make_tile(const TiledParams& p, unsigned id) {
   Tile t;
-  unsigned id = xcd_remap(blockIdx.x, gridDim.x);
   const int txi = id % p.ntx; id /= p.ntx;
   const int tyi = id % p.nty; id /= p.nty;
   const int zc = id % p.nzc;
@@ -412,9 +399,6 @@ struct FwdPolicy {
   template <int PH, bool FULL, class Sh>
   static __device__ __forceinline__ void step(State (&st)[KW], const Sh& sh, int cur, int lbase, unsigned active) {
     const typename Lds<ET>::chunk* kb = sh.main[cur];
-#ifdef MODET_PROFILE
-    const int g_dbg_step = sh.dbg_step;
-#endif
     LT plane[KW];      // per role: sum of the weights of this plane of its window
 #pragma unroll
     for (int i = 0; i < KW; ++i) plane[i] = (LT)0;
@@ -436,9 +420,6 @@ struct FwdPolicy {
           if (i == KW - 1 && b == 0) fold_row<true>(st[(i + PH) % KW], l[i], plane[i], b - R);
           else fold_row<false>(st[(i + PH) % KW], l[i], plane[i], b - R);
         }
-#ifdef MODET_PROFILE
-      if (b < 3) MODET_STAMP(g_dbg_step, 1 + b);
-#endif
     }
 #pragma unroll
     for (int i = 0; i < KW; ++i)
@@ -603,9 +584,6 @@ struct DkPolicy {
 template <class Pol, bool STATS> struct SharedPlanes;
 template <class Pol> struct SharedPlanes<Pol, false> {
   typename Lds<typename Pol::ET>::chunk main[2][Lds<typename Pol::ET>::CH * Pol::P::NPOS];
-#ifdef MODET_PROFILE
-  int dbg_step;
-#endif
 };
 template <class Pol> struct SharedPlanes<Pol, true> {
   typename Lds<typename Pol::ET>::chunk main[2][Lds<typename Pol::ET>::CH * Pol::P::NPOS];
@@ -619,17 +597,14 @@ __device__ __forceinline__ void march_body(typename Pol::State (&st)[Pol::KW], c
                                            bool have_next, bool commit_next, const Stg& stg, const SStg& sst) {
   constexpr int KW = Pol::KW, R = KW / 2;
   const unsigned active = active_roles<KW>(s, t.z0, t.z1);
-  MODET_STAMP(s - (t.z0 - R), 0);
   if (active == (1u << KW) - 1u) Pol::template step<PH, true>(st, sh, cur, lbase, active);
   else Pol::template step<PH, false>(st, sh, cur, lbase, active);
-  MODET_STAMP(s - (t.z0 - R), 4);
   // the staged plane goes to LDS before the results are stored: the wait for its loads would otherwise
   // also wait for those stores (one counter covers loads and stores on this chip)
   if (commit_next) {
     stg.commit(sh.main[cur ^ 1]);
     if constexpr (Pol::kStats) sst.commit(sh.sa[cur ^ 1], sh.sc[cur ^ 1]);
   }
-  MODET_STAMP(s - (t.z0 - R), 5);
   // All loads of this step end here, before the stores are issued: a wait placed after the stores (or at the
   // top of the next step, when the refill below is skipped) would wait for the stores as well.
   Pol::arrived(pre);
@@ -645,9 +620,9 @@ struct NoStats {
 
 __device__ __forceinline__ int clampi(int v, int lo, int hi) { return min(max(v, lo), hi); }
 
-template <class Pol, int WAVES>
-__global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(WAVES)))
-march_kernel(TiledParams p) {
+// One workgroup's march over its chunk.  id: logical tile index (after the XCD remap); smem: the workgroup's LDS.
+template <class Pol>
+__device__ __forceinline__ void march(const TiledParams& p, unsigned id, void* smem) {
   typedef typename Pol::P P;
   typedef typename Pol::T T;
   constexpr int KW = Pol::KW, HS = Pol::HS, R = KW / 2;
@@ -656,9 +631,9 @@ march_kernel(TiledParams p) {
 #else
   constexpr bool ROT = (KW == 3);
 #endif
-  __shared__ SharedPlanes<Pol, Pol::kStats> sh;
+  SharedPlanes<Pol, Pol::kStats>& sh = *reinterpret_cast<SharedPlanes<Pol, Pol::kStats>*>(smem);
 
-  const Tile t = make_tile(p);
+  const Tile t = make_tile(p, id);
   const T* Lb = Pol::lds_operand(p) + (long long)t.b * p.D * t.plane_elems;
   // lanes outside the volume compute on a clamped (valid) column and never store
   const int cy = min(t.y, p.H - 1), cxs = min(t.xs, p.Wh - 1);
@@ -711,9 +686,6 @@ march_kernel(TiledParams p) {
     const int cur = (s - s_first) & 1;
     const bool commit_next = s + 1 <= s_last;
     const bool have_next = s + R + 1 < t.z1;
-#ifdef MODET_PROFILE
-    if constexpr (!Pol::kStats) { if (threadIdx.x == 0) sh.dbg_step = s - s_first; }
-#endif
 
     if (ROT) {
       switch (ph) {
@@ -731,9 +703,33 @@ march_kernel(TiledParams p) {
       st[KW - 1] = tmp;
     }
     issue_loads(s + 1);
-    MODET_STAMP(s - s_first, 6);
     __syncthreads();
-    MODET_STAMP(s - s_first, 7);
+  }
+}
+
+template <class Pol, int WAVES>
+__global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(WAVES)))
+march_kernel(TiledParams p) {
+  __shared__ __align__(16) unsigned char smem[sizeof(SharedPlanes<Pol, Pol::kStats>)];
+  march<Pol>(p, xcd_remap(blockIdx.x, gridDim.x), smem);
+}
+
+// Two marches over the same tiles in one grid: even logical ids run PolA, odd ones PolB, writing outA / outB.
+// The two workgroups of a tile are neighbours in dispatch order and land on the same XCD, so what one of
+// them has just read from HBM (Q, K and the per-query statistics are inputs of both) is still in the caches
+// in front of HBM when the other asks for it; run one after the other, each pass re-reads everything.
+template <class PolA, class PolB, int WAVES>
+__global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(WAVES)))
+march_pair_kernel(TiledParams p, float* outA, float* outB) {
+  constexpr size_t kA = sizeof(SharedPlanes<PolA, PolA::kStats>), kB = sizeof(SharedPlanes<PolB, PolB::kStats>);
+  __shared__ __align__(16) unsigned char smem[kA > kB ? kA : kB];
+  const unsigned id = xcd_remap(blockIdx.x, gridDim.x);
+  if (id & 1u) {
+    p.out = outB;
+    march<PolB>(p, id >> 1, smem);
+  } else {
+    p.out = outA;
+    march<PolA>(p, id >> 1, smem);
   }
 }
 
@@ -778,12 +774,12 @@ int chunk_length(long long tiles, int D, int k, int wgs_per_cu) {
   return best_zc;
 }
 
-TiledParams make_params(const Geo& g, int wgs_per_cu) {
+TiledParams make_params(const Geo& g, int wgs_per_cu, int wgs_per_tile = 1) {
   TiledParams p = {};
   p.B = g.B; p.D = g.D; p.H = g.H; p.Wh = g.W * g.heads;
   p.ntx = (p.Wh + TX - 1) / TX;
   p.nty = (g.H + TY - 1) / TY;
-  int zc = chunk_length((long long)p.ntx * p.nty * g.B, g.D, g.k, wgs_per_cu);
+  int zc = chunk_length((long long)p.ntx * p.nty * g.B * wgs_per_tile, g.D, g.k, wgs_per_cu);
 #ifdef MODET_TUNING_ENV
   if (const char* e = getenv("MODET_ZC")) zc = atoi(e);
 #endif
@@ -831,26 +827,32 @@ hipError_t launch_fwd_t(const Geo& g, const void* Q, const void* K, float* phi, 
   return hipGetLastError();
 }
 
+template <class PolA, class PolB, int WAVES>
+int resident_pair_workgroups() {
+  static int n = 0;
+  if (n == 0) {
+    int v = 0;
+    n = (hipOccupancyMaxActiveBlocksPerMultiprocessor(&v, march_pair_kernel<PolA, PolB, WAVES>, NT, 0) ==
+             hipSuccess && v > 0) ? v : WAVES;
+  }
+  return n;
+}
+
 template <int KW, int HS, class T, class LT>
 hipError_t launch_bwd_t(const Geo& g, const void* Q, const void* K, const float* dphi, const float* phi,
                         const float* lse, float* dQ, float* dK, hipStream_t st) {
-  TiledParams io = {};
-  io.Q = Q; io.K = K; io.dphi = dphi; io.phi_in = phi; io.lse_in = lse;
-  io.out = dQ;
-  launch_march<DqPolicy<KW, HS, T, LT>, Waves<LT, KW>::value>(g, io, st);
-  io.out = dK;
-  launch_march<DkPolicy<KW, HS, T, LT>, Waves<LT, KW>::value>(g, io, st);
+  typedef DqPolicy<KW, HS, T, LT> A;
+  typedef DkPolicy<KW, HS, T, LT> B;
+  constexpr int W = Waves<LT, KW>::value;
+  // two workgroups per tile: the chunk length is chosen for twice the tile count
+  TiledParams p = make_params(g, resident_pair_workgroups<A, B, W>(), 2);
+  p.Q = Q; p.K = K; p.dphi = dphi; p.phi_in = phi; p.lse_in = lse;
+  hipLaunchKernelGGL((march_pair_kernel<A, B, W>), dim3(2 * nblocks(p)), dim3(NT), 0, st, p, dQ, dK);
   return hipGetLastError();
 }
 
 }  // namespace
 
-#ifdef MODET_PROFILE
-extern "C" void modet_debug_read(long long* host) {
-  (void)hipDeviceSynchronize();
-  (void)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_dbg), sizeof(long long) * 64 * 4 * 32 * 8);
-}
-#endif
 
 // Covered: head size 8, no bias;  k = 3: 1/2/4/8 heads, fp32 inputs (fp64 logits) and bf16 inputs (fp32
 // logits: the bf16 tolerance leaves room);  k = 5: 1/2 heads, bf16 inputs.
