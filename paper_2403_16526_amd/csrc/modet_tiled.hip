@@ -70,13 +70,14 @@ struct Tile {
   long long col;           // window index of (b, z=0, y, xs): + z*H*Wh
 };
 
-__device__ __forceinline__ Tile make_tile(const TiledParams& p, unsigned id) {
+__device__ __forceinline__ Tile make_tile(const TiledParams& p, unsigned id, int lane = -1) {
   Tile t;
+  if (lane < 0) lane = threadIdx.x;
   const int txi = id % p.ntx; id /= p.ntx;
   const int tyi = id % p.nty; id /= p.nty;
   const int zc = id % p.nzc;
   t.b = id / p.nzc;
-  t.tx = threadIdx.x % TX; t.ty = threadIdx.x / TX;
+  t.tx = lane % TX; t.ty = lane / TX;
   t.xs0 = txi * TX; t.y0 = tyi * TY;
   t.z0 = zc * p.ZC; t.z1 = min(p.D, t.z0 + p.ZC);
   t.xs = t.xs0 + t.tx; t.y = t.y0 + t.ty;
@@ -396,9 +397,9 @@ struct FwdPolicy {
     if (b != 0) s.S1 = fma((LT)b, rr, s.S1);
     s.S2 += (LT)ws;
   }
-  template <int PH, bool FULL, class Sh>
-  static __device__ __forceinline__ void step(State (&st)[KW], const Sh& sh, int cur, int lbase, unsigned active) {
-    const typename Lds<ET>::chunk* kb = sh.main[cur];
+  template <int PH, bool FULL>
+  static __device__ __forceinline__ void step(State (&st)[KW], const typename Lds<ET>::chunk* kb, const float4*,
+                                              const float*, int lbase, unsigned active) {
     LT plane[KW];      // per role: sum of the weights of this plane of its window
 #pragma unroll
     for (int i = 0; i < KW; ++i) plane[i] = (LT)0;
@@ -485,9 +486,22 @@ struct DqPolicy {
     s.g0 = a.g0; s.g1 = a.g1; s.g2 = a.g2;
     s.ngphi = -(a.g0 * a.f0 + a.g1 * a.f1 + a.g2 * a.f2);
   }
-  template <int PH, bool FULL, class Sh>
-  static __device__ __forceinline__ void step(State (&st)[KW], const Sh& sh, int cur, int lbase, unsigned active) {
-    const typename Lds<ET>::chunk* kb = sh.main[cur];
+  // the same from LDS: the query's features at patch position pos of a staged Q plane, its statistics from the
+  // (-lse*log2e, g) / -g.phi arrays the dK half of the workgroup keeps
+  static __device__ __forceinline__ void refill_lds(State& s, const float4* own, int pos, const float4* sa,
+                                                    const float* sc, const TiledParams& p) {
+    float qf[8];
+    Lds<float>::get8(own, P::NPOS, pos, qf);
+#pragma unroll
+    for (int c = 0; c < 8; ++c) { s.q[c] = (LT)qf[c] * (LT)p.qscale; s.acc[c] = 0.f; }
+    const float4 a4 = sa[pos];
+    s.nlse = (LT)a4.x;
+    s.g0 = a4.y; s.g1 = a4.z; s.g2 = a4.w;
+    s.ngphi = sc[pos];
+  }
+  template <int PH, bool FULL>
+  static __device__ __forceinline__ void step(State (&st)[KW], const typename Lds<ET>::chunk* kb, const float4*,
+                                              const float*, int lbase, unsigned active) {
 #pragma unroll
     for (int b = 0; b < KW; ++b)
 #pragma unroll
@@ -546,11 +560,16 @@ struct DkPolicy {
 #pragma unroll
     for (int c = 0; c < 8; ++c) { s.k[c] = (LT)pre.k[c] * (LT)p.qscale; s.acc[c] = 0.f; }
   }
-  template <int PH, bool FULL, class Sh>
-  static __device__ __forceinline__ void step(State (&st)[KW], const Sh& sh, int cur, int lbase, unsigned active) {
-    const typename Lds<ET>::chunk* qb = sh.main[cur];
-    const float4* sa = sh.sa[cur];
-    const float* sc = sh.sc[cur];
+  static __device__ __forceinline__ void refill_lds(State& s, const float4* own, int pos, const float4*, const float*,
+                                                    const TiledParams& p) {
+    float kf[8];
+    Lds<float>::get8(own, P::NPOS, pos, kf);
+#pragma unroll
+    for (int c = 0; c < 8; ++c) { s.k[c] = (LT)kf[c] * (LT)p.qscale; s.acc[c] = 0.f; }
+  }
+  template <int PH, bool FULL>
+  static __device__ __forceinline__ void step(State (&st)[KW], const typename Lds<ET>::chunk* qb, const float4* sa,
+                                              const float* sc, int lbase, unsigned active) {
 #pragma unroll
     for (int r = 0; r < KW; ++r)
 #pragma unroll
@@ -597,8 +616,11 @@ __device__ __forceinline__ void march_body(typename Pol::State (&st)[Pol::KW], c
                                            bool have_next, bool commit_next, const Stg& stg, const SStg& sst) {
   constexpr int KW = Pol::KW, R = KW / 2;
   const unsigned active = active_roles<KW>(s, t.z0, t.z1);
-  if (active == (1u << KW) - 1u) Pol::template step<PH, true>(st, sh, cur, lbase, active);
-  else Pol::template step<PH, false>(st, sh, cur, lbase, active);
+  const float4* sa = nullptr;
+  const float* sc = nullptr;
+  if constexpr (Pol::kStats) { sa = sh.sa[cur]; sc = sh.sc[cur]; }
+  if (active == (1u << KW) - 1u) Pol::template step<PH, true>(st, sh.main[cur], sa, sc, lbase, active);
+  else Pol::template step<PH, false>(st, sh.main[cur], sa, sc, lbase, active);
   // the staged plane goes to LDS before the results are stored: the wait for its loads would otherwise
   // also wait for those stores (one counter covers loads and stores on this chip)
   if (commit_next) {
@@ -733,6 +755,114 @@ march_pair_kernel(TiledParams p, float* outA, float* outB) {
   }
 }
 
+// ---- backward with both operands staged once --------------------------------------------------------
+// A 512-lane workgroup owns one tile: lanes 0..255 run the dQ march, lanes 256..511 the dK march, in the same
+// steps.  The dQ half stages the haloed K planes, the dK half the haloed Q planes and query statistics, into
+// rings of RING planes in LDS; what a half needs of the OTHER operand (the features of its own column, for the
+// plane that enters its window next) it reads from the other half's ring instead of from memory.  Every
+// input is read once per tile (plus halo) for both gradients.
+template <int KW, int HS>
+struct BwdRings {
+  typedef Patch<KW, HS> P;
+  static constexpr int RING = KW / 2 + 2;      // planes s .. s+R in use during step s, one more being written
+  float4 k[RING][2 * P::NPOS];
+  float4 q[RING][2 * P::NPOS];
+  float4 sa[RING][P::NPOS];
+  float sc[RING][P::NPOS];
+};
+
+// the part of a step after the arithmetic, for one half; OTHER = the ring this half refills from
+template <class Pol, int PH, class Commit>
+__device__ __forceinline__ void shared_step(typename Pol::State (&st)[Pol::KW], const TiledParams& p, const Tile& t,
+                                            const float4* lds_cur, const float4* sa_cur, const float* sc_cur,
+                                            const float4* own_new, const float4* sa_new, const float* sc_new,
+                                            int lbase, int s, bool fill_new, const Commit& commit_staged) {
+  constexpr int KW = Pol::KW, R = KW / 2;
+  typedef typename Pol::P P;
+  // the plane s + R enters the window of the newest role: its slot was freed by the store of the last step
+  if (fill_new) Pol::refill_lds(st[(KW - 1 + PH) % KW], own_new, lbase + R * P::PC + R * Pol::HS, sa_new, sc_new, p);
+  const unsigned active = active_roles<KW>(s, t.z0, t.z1);
+  if (active == (1u << KW) - 1u) Pol::template step<PH, true>(st, lds_cur, sa_cur, sc_cur, lbase, active);
+  else Pol::template step<PH, false>(st, lds_cur, sa_cur, sc_cur, lbase, active);
+  commit_staged();       // before the stores: its wait for the loads must not cover them
+  if ((active & 1u) && t.lane_ok)          // role 0 has seen its whole window
+    Pol::store(st[PH % KW], p, t.col + (long long)(s - R) * p.H * p.Wh);
+}
+
+template <class Pol, bool IS_DK, class Rings>
+__device__ __forceinline__ void shared_march(const TiledParams& p, const Tile& t, Rings& sh, int tid) {
+  typedef typename Pol::P P;
+  typedef typename Pol::T T;
+  constexpr int KW = Pol::KW, HS = Pol::HS, R = KW / 2, RING = Rings::RING;
+  static_assert(KW == 3, "phase rotation below is written for k = 3");
+  const T* Lb = Pol::lds_operand(p) + (long long)t.b * p.D * t.plane_elems;
+  const long long pw = (long long)p.H * p.Wh;
+  const long long wb = (long long)t.b * p.D * pw;
+  const int lbase = t.ty * P::PC + t.tx;
+  float4 (*mine)[2 * P::NPOS] = IS_DK ? sh.q : sh.k;        // the ring this half fills and marches over
+  float4 (*other)[2 * P::NPOS] = IS_DK ? sh.k : sh.q;       // the ring it takes its own column from
+
+  Stager<KW, HS, T, float> stg;
+  stg.init(tid, t.y0, t.xs0, p.H, p.Wh);
+  typename std::conditional<IS_DK, StatStager<KW, HS>, NoStats>::type sst;
+  sst.init(tid, t.y0, t.xs0, p.H, p.Wh);
+  auto fetch = [&](int z) {
+    const int zc = clampi(z, 0, p.D - 1);
+    const bool ok = z >= 0 && z < p.D;
+    stg.fetch(Lb + (long long)zc * t.plane_elems, ok);
+    sst.fetch(p, wb + (long long)zc * pw, ok);
+  };
+  auto commit = [&](int slot) {
+    stg.commit(mine[slot]);
+    if constexpr (IS_DK) sst.commit(sh.sa[slot], sh.sc[slot]);
+  };
+
+  typename Pol::State st[KW];
+#pragma unroll
+  for (int i = 0; i < KW; ++i) Pol::reset(st[i]);
+  const int s_first = t.z0 - R, s_last = t.z1 - 1 + R;
+#pragma unroll
+  for (int j = 0; j <= R; ++j) { fetch(s_first + j); commit(j); }
+  fetch(s_first + R + 1);
+  __syncthreads();
+
+  int ph = 0, cur = 0;                       // cur = (s - s_first) % RING
+  for (int s = s_first; s <= s_last; ++s) {
+    const int nw = cur + R >= RING ? cur + R - RING : cur + R;               // slot of the plane s + R
+    const int wr = nw + 1 >= RING ? nw + 1 - RING : nw + 1;                  // slot the staged plane goes to
+    const bool fill_new = s + R < t.z1;
+    // the staged plane s + R + 1 replaces the plane s - 1, which nobody reads any more
+    auto commit_staged = [&]() { if (s + R + 1 <= s_last) commit(wr); };
+    switch (ph) {
+      case 0: shared_step<Pol, 0>(st, p, t, mine[cur], sh.sa[cur], sh.sc[cur], other[nw], sh.sa[nw], sh.sc[nw],
+                                  lbase, s, fill_new, commit_staged); break;
+      case 1: shared_step<Pol, 1>(st, p, t, mine[cur], sh.sa[cur], sh.sc[cur], other[nw], sh.sa[nw], sh.sc[nw],
+                                  lbase, s, fill_new, commit_staged); break;
+      default: shared_step<Pol, 2>(st, p, t, mine[cur], sh.sa[cur], sh.sc[cur], other[nw], sh.sa[nw], sh.sc[nw],
+                                   lbase, s, fill_new, commit_staged); break;
+    }
+    fetch(s + R + 2);
+    ph = ph == KW - 1 ? 0 : ph + 1;
+    cur = cur + 1 == RING ? 0 : cur + 1;
+    __syncthreads();
+  }
+}
+
+template <int KW, int HS, class T, class LT>
+__global__ void __launch_bounds__(2 * NT) __attribute__((amdgpu_waves_per_eu(2)))
+bwd_shared_kernel(TiledParams p, float* dQ, float* dK) {
+  __shared__ BwdRings<KW, HS> sh;
+  const int tid = threadIdx.x & (NT - 1);
+  Tile t = make_tile(p, xcd_remap(blockIdx.x, gridDim.x), tid);
+  if (threadIdx.x < NT) {
+    p.out = dQ;
+    shared_march<DqPolicy<KW, HS, T, LT>, false>(p, t, sh, tid);
+  } else {
+    p.out = dK;
+    shared_march<DkPolicy<KW, HS, T, LT>, true>(p, t, sh, tid);
+  }
+}
+
 // ---- launch ------------------------------------------------------------------------------------------
 #ifndef MODET_WAVES
 #define MODET_WAVES 2
@@ -844,10 +974,23 @@ hipError_t launch_bwd_t(const Geo& g, const void* Q, const void* K, const float*
   typedef DqPolicy<KW, HS, T, LT> A;
   typedef DkPolicy<KW, HS, T, LT> B;
   constexpr int W = Waves<LT, KW>::value;
-  // two workgroups per tile: the chunk length is chosen for twice the tile count
-  TiledParams p = make_params(g, resident_pair_workgroups<A, B, W>(), 2);
-  p.Q = Q; p.K = K; p.dphi = dphi; p.phi_in = phi; p.lse_in = lse;
-  hipLaunchKernelGGL((march_pair_kernel<A, B, W>), dim3(2 * nblocks(p)), dim3(NT), 0, st, p, dQ, dK);
+  if constexpr (KW == 3) {
+    // one 512-lane workgroup per tile (both marches share their staged planes)
+    static int resident = 0;
+    if (resident == 0) {
+      int v = 0;
+      resident = (hipOccupancyMaxActiveBlocksPerMultiprocessor(&v, bwd_shared_kernel<KW, HS, T, LT>, 2 * NT, 0) ==
+                      hipSuccess && v > 0) ? v : 1;
+    }
+    TiledParams p = make_params(g, resident);
+    p.Q = Q; p.K = K; p.dphi = dphi; p.phi_in = phi; p.lse_in = lse;
+    hipLaunchKernelGGL((bwd_shared_kernel<KW, HS, T, LT>), dim3(nblocks(p)), dim3(2 * NT), 0, st, p, dQ, dK);
+  } else {
+    // two workgroups per tile: the chunk length is chosen for twice the tile count
+    TiledParams p = make_params(g, resident_pair_workgroups<A, B, W>(), 2);
+    p.Q = Q; p.K = K; p.dphi = dphi; p.phi_in = phi; p.lse_in = lse;
+    hipLaunchKernelGGL((march_pair_kernel<A, B, W>), dim3(2 * nblocks(p)), dim3(NT), 0, st, p, dQ, dK);
+  }
   return hipGetLastError();
 }
 
