@@ -524,6 +524,39 @@ struct DqPolicy {
           }
       }
   }
+  // the same step, also handing dl of every (role, offset) to the key side:
+  // dl_out[(a+R) * DLA + ((b+R)*KW + c+R) * NT + li], a = R - i the plane offset of role i; roles that are not
+  // active emit 0
+  template <int PH, bool FULL, int DLA>
+  static __device__ __forceinline__ void step_emit(State (&st)[KW], const typename Lds<ET>::chunk* kb, int lbase,
+                                                   unsigned active, float* dl_out, int li) {
+#pragma unroll
+    for (int b = 0; b < KW; ++b)
+#pragma unroll
+      for (int c = 0; c < KW; ++c) {
+        float kf[8];
+        Lds<ET>::get8(kb, P::NPOS, lbase + b * P::PC + c * HS, kf);
+        LT kv[8];
+        widen8<LT, float>(kf, kv);
+#pragma unroll
+        for (int i = 0; i < KW; ++i) {
+          const int j = (KW - 1 - i) * DLA + (b * KW + c) * NT;      // a + R = R - i + R = KW - 1 - i
+          if (FULL || (active & (1u << i))) {
+            State& s = st[(i + PH) % KW];
+            const float w = exp2_fast((float)dot8<LT>(s.q, kv, s.nlse));
+            float tt = s.ngphi;
+            if (R - i != 0) tt = fmaf((float)(R - i), s.g0, tt);
+            if (b - R != 0) tt = fmaf((float)(b - R), s.g1, tt);
+            if (c - R != 0) tt = fmaf((float)(c - R), s.g2, tt);
+            const float dl = w * tt;
+            axpy8(s.acc, dl, kf);
+            dl_out[j + li] = dl;
+          } else {
+            dl_out[j + li] = 0.f;
+          }
+        }
+      }
+  }
   static __device__ __forceinline__ void store(const State& s, const TiledParams& p, long long w) {
     store8_scaled(p.out + w * 8, s.acc, p.scale);
   }
@@ -863,6 +896,278 @@ bwd_shared_kernel(TiledParams p, float* dQ, float* dK) {
   }
 }
 
+// ---- backward with every logit computed once (k = 3, one head: fused column = voxel) ----------------------
+// 512 lanes per tile.  Lanes 0..255 ("query half") run the dQ march and hand dl of each of their 27 (query,
+// key) pairs to lanes 256..511 ("key half") through LDS; a key lane sums dl * Q over the 27 queries that see
+// its key of the current plane: dK needs no logits of its own.  Queries in the one-voxel ring around the
+// patch belong to neighbouring tiles; the key half recomputes dl for the pairs of those queries that point
+// into the patch (about 10 % of all pairs), one ring query per lane.  The key half also stages all planes.
+//   step s (K plane s current), one barrier B(s):
+//     query half:  [refill newest role] [dl, dQ of 27 pairs -> DL[s&1]] [store dQ of plane s-1]   B(s)
+//     key half:    [ring queries of step s -> DL[s&1]]   B(s)   [gather plane s from DL[s&1], store dK]
+//                  [commit K plane s+2, Q / ring statistics plane s+3] [issue loads for K s+3, Q s+4]
+// so the gather of step s overlaps the query half's arithmetic of step s+1.
+template <class T, class LT>
+struct FusedBwd {
+  static constexpr int KW = 3, HS = 1, R = 1;
+  typedef Patch<KW, HS> P;
+  typedef DqPolicy<KW, HS, T, LT> Dq;
+  static constexpr int NRP = 2 * P::PC + 2 * TY;     // ring positions: top row, bottom row, left, right column
+  static constexpr int NRC = 3 * NRP;                // (ring position, inward offset) combinations per plane
+  static constexpr int DLA = 9 * NT + NRC;           // floats per plane offset a: 9 in-plane offsets of the patch
+  static constexpr int DLN = 3 * DLA;                //   lanes, then the ring combinations; one DL buffer
+  static constexpr int QR = 5;                       // Q planes s-1 .. s+2 readable, one being written
+  struct Lds {
+    float4 k[2][2 * P::NPOS];
+    float4 q[QR][2 * P::NPOS];
+    float4 sa[QR][NRP];      // (-lse*log2e, g) of the ring queries
+    float sc[QR][NRP];       // -g.phi
+    float dl[2][DLN];
+  };
+  // ring position -> patch row / column
+  static __device__ __forceinline__ void ring_rc(int rp, int& pr, int& pc) {
+    if (rp < P::PC) { pr = 0; pc = rp; }
+    else if (rp < 2 * P::PC) { pr = P::PR - 1; pc = rp - P::PC; }
+    else if (rp < 2 * P::PC + TY) { pr = rp - 2 * P::PC + 1; pc = 0; }
+    else { pr = rp - 2 * P::PC - TY + 1; pc = P::PC - 1; }
+  }
+  // offset (b, c) number t = 0..2 of a ring query towards the patch; false if it points outside
+  static __device__ __forceinline__ bool ring_offset(int pr, int pc, int t, int& b, int& c) {
+    if (pr == 0 || pr == P::PR - 1) { b = pr == 0 ? 1 : -1; c = t - 1; }
+    else { c = pc == 0 ? 1 : -1; b = t - 1; }
+    const int kr = pr + b, kc = pc + c;
+    return kr >= 1 && kr <= TY && kc >= 1 && kc <= TX;
+  }
+};
+
+template <class T, class LT, int PH>
+__device__ __forceinline__ void fused_query_step(typename DqPolicy<3, 1, T, LT>::State (&st)[3],
+                                                 typename DqPolicy<3, 1, T, LT>::Pre& pre, const TiledParams& p,
+                                                 const Tile& t, const T* Ob, long long ccol, const float4* kcur,
+                                                 float* dl, int lbase, int tid, int s, bool fill_new, unsigned active,
+                                                 bool store_old, long long w_old) {
+  typedef DqPolicy<3, 1, T, LT> Dq;
+  constexpr int KW = 3;
+  if (fill_new) Dq::refill(st[(KW - 1 + PH) % KW], pre, p);
+  {   // own features and statistics of the plane that enters next, one step ahead
+    const int zc = clampi(s + 2, 0, p.D - 1);
+    Dq::prefetch(p, Ob + (long long)zc * t.plane_elems, ccol + (long long)zc * p.H * p.Wh, pre);
+  }
+  if (active == 7u) Dq::template step_emit<PH, true, FusedBwd<T, LT>::DLA>(st, kcur, lbase, active, dl, tid);
+  else Dq::template step_emit<PH, false, FusedBwd<T, LT>::DLA>(st, kcur, lbase, active, dl, tid);
+  if (store_old) Dq::store(st[PH % KW], p, w_old);
+}
+
+template <class T, class LT>
+__device__ __forceinline__ void fused_query_half(TiledParams p, const Tile& t, typename FusedBwd<T, LT>::Lds& sh,
+                                                 int tid) {
+  typedef FusedBwd<T, LT> F;
+  typedef typename F::Dq Dq;
+  typedef typename F::P P;
+  constexpr int KW = 3, R = 1;
+  const int cy = min(t.y, p.H - 1), cxs = min(t.xs, p.Wh - 1);
+  const long long pw = (long long)p.H * p.Wh;
+  const T* Ob = (const T*)p.Q + (long long)t.b * p.D * t.plane_elems + ((long long)cy * p.Wh + cxs) * 8;
+  const long long ccol = (long long)t.b * p.D * pw + (long long)cy * p.Wh + cxs;
+  const int lbase = t.ty * P::PC + t.tx;
+  const int s_lo = t.z0 - 1, s_hi = t.z1;
+  const int zlo = max(t.z0 - 1, 0), zhi = min(t.z1 + 1, p.D);     // planes whose dl is wanted
+
+  typename Dq::State st[KW];
+#pragma unroll
+  for (int i = 0; i < KW; ++i) Dq::reset(st[i]);
+  typename Dq::Pre pre;
+  auto prefetch = [&](int z) {
+    const int zc = clampi(z, 0, p.D - 1);
+    Dq::prefetch(p, Ob + (long long)zc * t.plane_elems, ccol + zc * pw, pre);
+  };
+  // at the first step the roles are the planes s_lo-1, s_lo, s_lo+1: the middle one is filled here, the
+  // newest at the top of the loop like in every step
+  if (s_lo >= zlo) {
+    prefetch(s_lo);
+    Dq::arrived(pre);
+    if (!t.lane_ok) { pre.g0 = pre.g1 = pre.g2 = 0.f; pre.f0 = pre.f1 = pre.f2 = 0.f; }
+    Dq::refill(st[1], pre, p);
+  }
+  prefetch(s_lo + 1);
+  __syncthreads();          // the key half has staged the first planes
+
+  int ph = 0;
+  for (int s = s_lo; s <= s_hi; ++s) {
+    const float4* kcur = sh.k[(s - s_lo) & 1];
+    float* dl = sh.dl[(s - s_lo) & 1];
+    const bool fill_new = s + 1 >= zlo && s + 1 < zhi;
+    const unsigned active = active_roles<KW>(s, zlo, zhi);
+    const bool store_old = s - 1 >= t.z0 && s - 1 < t.z1 && t.lane_ok;
+    const long long w_old = t.col + (long long)(s - 1) * pw;
+    Dq::arrived(pre);
+    if (!t.lane_ok) {      // no such query: its dl must be zero for the keys next to it
+      pre.g0 = pre.g1 = pre.g2 = 0.f;
+      pre.f0 = pre.f1 = pre.f2 = 0.f;
+    }
+    switch (ph) {
+      case 0: fused_query_step<T, LT, 0>(st, pre, p, t, Ob, ccol, kcur, dl, lbase, tid, s, fill_new, active,
+                                         store_old, w_old); break;
+      case 1: fused_query_step<T, LT, 1>(st, pre, p, t, Ob, ccol, kcur, dl, lbase, tid, s, fill_new, active,
+                                         store_old, w_old); break;
+      default: fused_query_step<T, LT, 2>(st, pre, p, t, Ob, ccol, kcur, dl, lbase, tid, s, fill_new, active,
+                                          store_old, w_old); break;
+    }
+    ph = ph == KW - 1 ? 0 : ph + 1;
+    __syncthreads();        // B(s)
+  }
+}
+
+template <class T, class LT>
+__device__ __forceinline__ void fused_key_half(TiledParams p, const Tile& t, typename FusedBwd<T, LT>::Lds& sh,
+                                               int tid) {
+  typedef FusedBwd<T, LT> F;
+  typedef typename F::P P;
+  constexpr int KW = 3, HS = 1, QR = F::QR, NRP = F::NRP, NRC = F::NRC;
+  const long long pw = (long long)p.H * p.Wh;
+  const long long wb = (long long)t.b * p.D * pw;
+  const T* Kb = (const T*)p.K + (long long)t.b * p.D * t.plane_elems;
+  const T* Qb = (const T*)p.Q + (long long)t.b * p.D * t.plane_elems;
+  const int s_lo = t.z0 - 1, s_hi = t.z1;
+
+  // ---- staging: K and Q planes (whole haloed patch), statistics of the ring queries (lanes < NRP)
+  Stager<KW, HS, T, float> stk, stq;
+  stk.init(tid, t.y0, t.xs0, p.H, p.Wh);
+  stq.init(tid, t.y0, t.xs0, p.H, p.Wh);
+  int rpr, rpc;
+  F::ring_rc(min(tid, NRP - 1), rpr, rpc);
+  const int rgy = t.y0 - 1 + rpr, rgx = t.xs0 - 1 + rpc;
+  const bool ring_in = tid < NRP && rgy >= 0 && rgy < p.H && rgx >= 0 && rgx < p.Wh;
+  const long long ring_w = (long long)min(max(rgy, 0), p.H - 1) * p.Wh + min(max(rgx, 0), p.Wh - 1);
+  float r_lse, r_g[3], r_f[3];
+  bool r_ok = false;
+  auto fetch_k = [&](int z) {
+    stk.fetch(Kb + (long long)clampi(z, 0, p.D - 1) * t.plane_elems, z >= 0 && z < p.D);
+  };
+  auto fetch_q = [&](int z) {
+    const int zc = clampi(z, 0, p.D - 1);
+    stq.fetch(Qb + (long long)zc * t.plane_elems, z >= 0 && z < p.D);
+    const long long w = wb + (long long)zc * pw + ring_w;
+    r_lse = p.lse_in[w];
+    r_g[0] = p.dphi[w * 3]; r_g[1] = p.dphi[w * 3 + 1]; r_g[2] = p.dphi[w * 3 + 2];
+    r_f[0] = p.phi_in[w * 3]; r_f[1] = p.phi_in[w * 3 + 1]; r_f[2] = p.phi_in[w * 3 + 2];
+    r_ok = ring_in && z >= 0 && z < p.D;
+  };
+  auto commit_q = [&](int slot) {
+    stq.commit(sh.q[slot]);
+    if (tid < NRP) {
+      const float g0 = r_ok ? r_g[0] : 0.f, g1 = r_ok ? r_g[1] : 0.f, g2 = r_ok ? r_g[2] : 0.f;
+      sh.sa[slot][tid] = make_float4(r_ok ? -r_lse * kLog2e : 0.f, g0, g1, g2);
+      sh.sc[slot][tid] = -(g0 * r_f[0] + g1 * r_f[1] + g2 * r_f[2]);
+    }
+  };
+  // K slot of plane z: (z - s_lo) & 1;  Q slot: (z - s_lo) mod QR, kept as running counters below
+  fetch_k(s_lo); stk.commit(sh.k[0]);
+  fetch_k(s_lo + 1); stk.commit(sh.k[1]);
+#pragma unroll
+  for (int j = 0; j < 3; ++j) { fetch_q(s_lo + j); commit_q(j); }
+  fetch_k(s_lo + 2);
+  fetch_q(s_lo + 3);
+
+  // ---- this lane's ring query: plane offset a = ra - 1 (query plane s - a), ring position rq
+  const int ra = tid / NRP, rq = tid - ra * NRP;
+  const bool has_ring = tid < 3 * NRP;
+  int qr_, qc_;
+  F::ring_rc(has_ring ? rq : 0, qr_, qc_);
+  const int ring_pos = qr_ * P::PC + qc_;
+  // ---- gather addresses: the query of offset (b, c) sits at patch position (kr - b, kc - c)
+  const int kr = t.ty + 1, kc = t.tx + 1;
+  int gidx[9];
+#pragma unroll
+  for (int bc = 0; bc < 9; ++bc) {
+    const int b = bc / 3 - 1, c = bc % 3 - 1;
+    const int qr = kr - b, qc = kc - c;
+    const bool inside = qr >= 1 && qr <= TY && qc >= 1 && qc <= TX;
+    int rp, tt;
+    if (qr == 0) { rp = qc; tt = c + 1; }
+    else if (qr == P::PR - 1) { rp = P::PC + qc; tt = c + 1; }
+    else if (qc == 0) { rp = 2 * P::PC + qr - 1; tt = b + 1; }
+    else { rp = 2 * P::PC + TY + qr - 1; tt = b + 1; }
+    gidx[bc] = inside ? (bc * NT + (qr - 1) * TX + (qc - 1)) : (9 * NT + rp * 3 + tt);
+  }
+  __syncthreads();          // first planes staged
+
+  int qs = 0;               // Q slot of plane s (s = s_lo: 0)
+  for (int s = s_lo; s <= s_hi; ++s) {
+    const int kslot = (s - s_lo) & 1;
+    float* dl = sh.dl[kslot];
+    const bool key_plane = s >= t.z0 && s < t.z1;
+    auto qslot = [&](int d) { int v = qs + d; v += v < 0 ? QR : 0; v -= v >= QR ? QR : 0; return v; };
+    // ---- ring queries of this step
+    if (key_plane && has_ring) {
+      const int sl = qslot(1 - ra);                 // query plane z = s - a, a = ra - 1
+      float qf[8];
+      Lds<float>::get8(sh.q[sl], P::NPOS, ring_pos, qf);
+      LT qv[8];
+      widen8<LT, float>(qf, qv);
+      const float4 a4 = sh.sa[sl][rq];
+      const float base = fmaf((float)(ra - 1), a4.y, sh.sc[sl][rq]);
+#pragma unroll
+      for (int tt = 0; tt < 3; ++tt) {
+        int b, c;
+        const bool valid = F::ring_offset(qr_, qc_, tt, b, c);
+        const int kpos = valid ? (qr_ + b) * P::PC + qc_ + c : ring_pos;
+        float kf[8];
+        Lds<float>::get8(sh.k[kslot], P::NPOS, kpos, kf);
+        LT kv[8];
+        widen8<LT, float>(kf, kv);
+        const LT l = fma(dot8<LT>(qv, kv), (LT)p.qscale, (LT)a4.x);
+        const float tq = fmaf((float)b, a4.z, fmaf((float)c, a4.w, base));
+        dl[ra * F::DLA + 9 * NT + rq * 3 + tt] = valid ? exp2_fast((float)l) * tq : 0.f;
+      }
+    }
+    __syncthreads();        // B(s)
+    // ---- gather: dK of this lane's key in plane s
+    if (key_plane) {
+      float acc[8];
+#pragma unroll
+      for (int c = 0; c < 8; ++c) acc[c] = 0.f;
+#pragma unroll 1                                     // (unrolled, all 27 vector reads get hoisted and spill)
+      for (int a = 0; a < 3; ++a) {                 // plane offset a - 1: query plane s - (a - 1)
+        const float4* qp = sh.q[qslot(1 - a)];
+#pragma unroll
+        for (int bc = 0; bc < 9; ++bc) {
+          const int b = bc / 3 - 1, c = bc % 3 - 1;
+          const float d = dl[a * F::DLA + gidx[bc]];
+          float qf[8];
+          Lds<float>::get8(qp, P::NPOS, (kr - b) * P::PC + kc - c, qf);
+          axpy8(acc, d, qf);
+        }
+      }
+      // the staged planes go to LDS before the store (the wait for their loads must not cover it)
+      stk.commit(sh.k[kslot]);                      // K plane s + 2 replaces plane s
+      commit_q(qslot(3));                           // Q plane s + 3 replaces plane s - 2
+      if (t.lane_ok) store8_scaled(p.out + (t.col + (long long)s * pw) * 8, acc, p.scale);
+    } else {
+      stk.commit(sh.k[kslot]);
+      commit_q(qslot(3));
+    }
+    fetch_k(s + 3);
+    fetch_q(s + 4);
+    qs = qs + 1 == QR ? 0 : qs + 1;
+  }
+}
+
+template <class T, class LT>
+__global__ void __launch_bounds__(2 * NT) __attribute__((amdgpu_waves_per_eu(2)))
+bwd_fused_kernel(TiledParams p, float* dQ, float* dK) {
+  __shared__ typename FusedBwd<T, LT>::Lds sh;
+  const int tid = threadIdx.x & (NT - 1);
+  const Tile t = make_tile(p, xcd_remap(blockIdx.x, gridDim.x), tid);
+  if (threadIdx.x < NT) {
+    p.out = dQ;
+    fused_query_half<T, LT>(p, t, sh, tid);
+  } else {
+    p.out = dK;
+    fused_key_half<T, LT>(p, t, sh, tid);
+  }
+}
+
 // ---- launch ------------------------------------------------------------------------------------------
 #ifndef MODET_WAVES
 #define MODET_WAVES 2
@@ -974,6 +1279,25 @@ hipError_t launch_bwd_t(const Geo& g, const void* Q, const void* K, const float*
   typedef DqPolicy<KW, HS, T, LT> A;
   typedef DkPolicy<KW, HS, T, LT> B;
   constexpr int W = Waves<LT, KW>::value;
+  bool fused = KW == 3 && HS == 1;
+#ifdef MODET_TUNING_ENV
+  if (const char* e = getenv("MODET_BWD_KERNEL")) fused = fused && atoi(e) == 0;
+#endif
+  if constexpr (KW == 3 && HS == 1) {
+    if (fused) {
+      // one 512-lane workgroup per tile; every logit computed once
+      static int resident = 0;
+      if (resident == 0) {
+        int v = 0;
+        resident = (hipOccupancyMaxActiveBlocksPerMultiprocessor(&v, bwd_fused_kernel<T, LT>, 2 * NT, 0) ==
+                        hipSuccess && v > 0) ? v : 1;
+      }
+      TiledParams p = make_params(g, resident);
+      p.Q = Q; p.K = K; p.dphi = dphi; p.phi_in = phi; p.lse_in = lse;
+      hipLaunchKernelGGL((bwd_fused_kernel<T, LT>), dim3(nblocks(p)), dim3(2 * NT), 0, st, p, dQ, dK);
+      return hipGetLastError();
+    }
+  }
   if constexpr (KW == 3) {
     // one 512-lane workgroup per tile (both marches share their staged planes)
     static int resident = 0;
