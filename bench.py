@@ -25,7 +25,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per modet_bwd call (one kernel: the dQ and dK marches of a tile side by side) from rocprofv3 --pmc
 # FETCH_SIZE / WRITE_SIZE runs of this command, scaled by what the same counters read for the device copy
 # below (profiles/config3_fwd_bwd_warp_kernels.txt); None where not measured.
-MEASURED_TRAFFIC_BYTES = {3: 1200892966}
+MEASURED_TRAFFIC_BYTES = {3: 1174769009}
 
 
 def main():
@@ -115,7 +115,7 @@ def main():
     # algorithmic bytes (each tensor moved once, no stored attention)
     fwd_bytes = nvox * (2 * C * esz + 12 * heads)
     bwd_bytes = nvox * (2 * C * esz + 12 * heads + 8 * C)
-    dom_bytes, dom_ms, dom_name = ((bwd_bytes, t_bwd, "modet_bwd (bwd_shared_kernel: dQ + dK marches)") if t_bwd >= t_fwd
+    dom_bytes, dom_ms, dom_name = ((bwd_bytes, t_bwd, "modet_bwd (bwd_fused_kernel)") if t_bwd >= t_fwd
                                   else (fwd_bytes, t_fwd, "modet_fwd"))
     achieved = dom_bytes / (dom_ms * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": dom_name, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
