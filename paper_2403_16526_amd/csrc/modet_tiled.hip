@@ -173,15 +173,26 @@ struct Stager {
     for (int i = 0; i < P::NL; ++i) v[i] = Ld<T>::vec4(plane + goff[i]);
     plane_ok = ok;
   }
-  __device__ __forceinline__ void commit(typename Lds<ET>::chunk* buf) const {
+  // Patch slots outside the volume (in H, W) never change: they are zeroed once per LDS buffer, and commit
+  // writes the others only; a plane outside the volume (in D) is a uniform case, so nothing is selected per
+  // lane and component.
+  __device__ __forceinline__ void zero_outside(typename Lds<ET>::chunk* buf) const {
 #pragma unroll
     for (int i = 0; i < P::NL; ++i)
-      if (loff[i] >= 0) {
-        const bool keep = plane_ok && (loff[i] & 1);
-        const float4 w = make_float4(keep ? v[i].x : 0.f, keep ? v[i].y : 0.f, keep ? v[i].z : 0.f,
-                                     keep ? v[i].w : 0.f);
-        Lds<ET>::put4(buf, P::NPOS, loff[i] >> 2, (loff[i] >> 1) & 1, w);
-      }
+      if (loff[i] >= 0 && !(loff[i] & 1))
+        Lds<ET>::put4(buf, P::NPOS, loff[i] >> 2, (loff[i] >> 1) & 1, make_float4(0.f, 0.f, 0.f, 0.f));
+  }
+  __device__ __forceinline__ void commit(typename Lds<ET>::chunk* buf) const {
+    if (plane_ok) {
+#pragma unroll
+      for (int i = 0; i < P::NL; ++i)
+        if (loff[i] >= 0 && (loff[i] & 1)) Lds<ET>::put4(buf, P::NPOS, loff[i] >> 2, (loff[i] >> 1) & 1, v[i]);
+    } else {
+#pragma unroll
+      for (int i = 0; i < P::NL; ++i)
+        if (loff[i] >= 0 && (loff[i] & 1))
+          Lds<ET>::put4(buf, P::NPOS, loff[i] >> 2, (loff[i] >> 1) & 1, make_float4(0.f, 0.f, 0.f, 0.f));
+    }
   }
 };
 
@@ -222,15 +233,30 @@ struct StatStager {
     }
     plane_ok = ok;
   }
-  __device__ __forceinline__ void commit(float4* sa, float* sc) const {
+  __device__ __forceinline__ void zero_outside(float4* sa, float* sc) const {
 #pragma unroll
     for (int i = 0; i < P::NS; ++i)
-      if (loff[i] >= 0) {
-        const bool keep = plane_ok && (loff[i] & 1);
-        const float g0 = keep ? g[i][0] : 0.f, g1 = keep ? g[i][1] : 0.f, g2 = keep ? g[i][2] : 0.f;
-        sa[loff[i] >> 1] = make_float4(keep ? -lse[i] * kLog2e : 0.f, g0, g1, g2);
-        sc[loff[i] >> 1] = -(g0 * f[i][0] + g1 * f[i][1] + g2 * f[i][2]);
+      if (loff[i] >= 0 && !(loff[i] & 1)) {
+        sa[loff[i] >> 1] = make_float4(0.f, 0.f, 0.f, 0.f);
+        sc[loff[i] >> 1] = 0.f;
       }
+  }
+  __device__ __forceinline__ void commit(float4* sa, float* sc) const {
+    if (plane_ok) {
+#pragma unroll
+      for (int i = 0; i < P::NS; ++i)
+        if (loff[i] >= 0 && (loff[i] & 1)) {
+          sa[loff[i] >> 1] = make_float4(-lse[i] * kLog2e, g[i][0], g[i][1], g[i][2]);
+          sc[loff[i] >> 1] = -(g[i][0] * f[i][0] + g[i][1] * f[i][1] + g[i][2] * f[i][2]);
+        }
+    } else {
+#pragma unroll
+      for (int i = 0; i < P::NS; ++i)
+        if (loff[i] >= 0 && (loff[i] & 1)) {
+          sa[loff[i] >> 1] = make_float4(0.f, 0.f, 0.f, 0.f);
+          sc[loff[i] >> 1] = 0.f;
+        }
+    }
   }
 };
 
@@ -671,6 +697,7 @@ __device__ __forceinline__ void march_body(typename Pol::State (&st)[Pol::KW], c
 struct NoStats {
   __device__ __forceinline__ void init(int, int, int, int, int) {}
   __device__ __forceinline__ void fetch(const TiledParams&, long long, bool) {}
+  __device__ __forceinline__ void zero_outside(float4*, float*) const {}
 };
 
 __device__ __forceinline__ int clampi(int v, int lo, int hi) { return min(max(v, lo), hi); }
@@ -702,6 +729,11 @@ __device__ __forceinline__ void march(const TiledParams& p, unsigned id, void* s
   stg.init(threadIdx.x, t.y0, t.xs0, p.H, p.Wh);
   typename std::conditional<Pol::kStats, StatStager<KW, HS>, NoStats>::type sst;
   sst.init(threadIdx.x, t.y0, t.xs0, p.H, p.Wh);
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    stg.zero_outside(sh.main[j]);
+    if constexpr (Pol::kStats) sst.zero_outside(sh.sa[j], sh.sc[j]);
+  }
 
   typename Pol::State st[KW];
 #pragma unroll
@@ -736,21 +768,14 @@ __device__ __forceinline__ void march(const TiledParams& p, unsigned id, void* s
   issue_loads(s_first);
   __syncthreads();
 
-  int ph = 0;
-  for (int s = s_first; s <= s_last; ++s) {
+  // one step with the role -> register-slot phase PH fixed at compile time
+  auto one_step = [&](auto PHc, int s) __attribute__((always_inline)) {
+    constexpr int PH = decltype(PHc)::value;
     const int cur = (s - s_first) & 1;
     const bool commit_next = s + 1 <= s_last;
     const bool have_next = s + R + 1 < t.z1;
-
-    if (ROT) {
-      switch (ph) {
-        case 0: march_body<Pol, 0>(st, p, t, sh, cur, lbase, s, pre, have_next, commit_next, stg, sst); break;
-        case 1: march_body<Pol, 1 % KW>(st, p, t, sh, cur, lbase, s, pre, have_next, commit_next, stg, sst); break;
-        default: march_body<Pol, 2 % KW>(st, p, t, sh, cur, lbase, s, pre, have_next, commit_next, stg, sst); break;
-      }
-      ph = ph == KW - 1 ? 0 : ph + 1;
-    } else {
-      march_body<Pol, 0>(st, p, t, sh, cur, lbase, s, pre, have_next, commit_next, stg, sst);
+    march_body<Pol, PH>(st, p, t, sh, cur, lbase, s, pre, have_next, commit_next, stg, sst);
+    if (!ROT) {
       // rotate by moving: role i+1 becomes role i, the refilled slot 0 becomes role KW-1
       typename Pol::State tmp = st[0];
 #pragma unroll
@@ -759,6 +784,18 @@ __device__ __forceinline__ void march(const TiledParams& p, unsigned id, void* s
     }
     issue_loads(s + 1);
     __syncthreads();
+  };
+  if (ROT) {
+    // the three phases are unrolled in sequence (not selected by a switch): the state stays in the same
+    // registers from phase to phase and nothing has to be moved where the branches would meet
+    int s = s_first;
+    while (true) {
+      one_step(std::integral_constant<int, 0>(), s); if (++s > s_last) break;
+      one_step(std::integral_constant<int, 1 % KW>(), s); if (++s > s_last) break;
+      one_step(std::integral_constant<int, 2 % KW>(), s); if (++s > s_last) break;
+    }
+  } else {
+    for (int s = s_first; s <= s_last; ++s) one_step(std::integral_constant<int, 0>(), s);
   }
 }
 
@@ -839,6 +876,11 @@ __device__ __forceinline__ void shared_march(const TiledParams& p, const Tile& t
   stg.init(tid, t.y0, t.xs0, p.H, p.Wh);
   typename std::conditional<IS_DK, StatStager<KW, HS>, NoStats>::type sst;
   sst.init(tid, t.y0, t.xs0, p.H, p.Wh);
+#pragma unroll
+  for (int j = 0; j < RING; ++j) {
+    stg.zero_outside(mine[j]);
+    if constexpr (IS_DK) sst.zero_outside(sh.sa[j], sh.sc[j]);
+  }
   auto fetch = [&](int z) {
     const int zc = clampi(z, 0, p.D - 1);
     const bool ok = z >= 0 && z < p.D;
@@ -859,25 +901,29 @@ __device__ __forceinline__ void shared_march(const TiledParams& p, const Tile& t
   fetch(s_first + R + 1);
   __syncthreads();
 
-  int ph = 0, cur = 0;                       // cur = (s - s_first) % RING
-  for (int s = s_first; s <= s_last; ++s) {
+  int cur = 0;                               // cur = (s - s_first) % RING
+  auto one_step = [&](auto PHc, int s) __attribute__((always_inline)) {
+    constexpr int PH = decltype(PHc)::value;
     const int nw = cur + R >= RING ? cur + R - RING : cur + R;               // slot of the plane s + R
     const int wr = nw + 1 >= RING ? nw + 1 - RING : nw + 1;                  // slot the staged plane goes to
     const bool fill_new = s + R < t.z1;
     // the staged plane s + R + 1 replaces the plane s - 1, which nobody reads any more
     auto commit_staged = [&]() { if (s + R + 1 <= s_last) commit(wr); };
-    switch (ph) {
-      case 0: shared_step<Pol, 0>(st, p, t, mine[cur], sh.sa[cur], sh.sc[cur], other[nw], sh.sa[nw], sh.sc[nw],
-                                  lbase, s, fill_new, commit_staged); break;
-      case 1: shared_step<Pol, 1>(st, p, t, mine[cur], sh.sa[cur], sh.sc[cur], other[nw], sh.sa[nw], sh.sc[nw],
-                                  lbase, s, fill_new, commit_staged); break;
-      default: shared_step<Pol, 2>(st, p, t, mine[cur], sh.sa[cur], sh.sc[cur], other[nw], sh.sa[nw], sh.sc[nw],
-                                   lbase, s, fill_new, commit_staged); break;
-    }
+    shared_step<Pol, PH>(st, p, t, mine[cur], sh.sa[cur], sh.sc[cur], other[nw], sh.sa[nw], sh.sc[nw], lbase, s,
+                         fill_new, commit_staged);
     fetch(s + R + 2);
-    ph = ph == KW - 1 ? 0 : ph + 1;
     cur = cur + 1 == RING ? 0 : cur + 1;
     __syncthreads();
+  };
+  // (here the phases are selected by a switch: unrolled in sequence, this kernel's two bodies spill)
+  int ph = 0;
+  for (int s = s_first; s <= s_last; ++s) {
+    switch (ph) {
+      case 0: one_step(std::integral_constant<int, 0>(), s); break;
+      case 1: one_step(std::integral_constant<int, 1>(), s); break;
+      default: one_step(std::integral_constant<int, 2>(), s); break;
+    }
+    ph = ph == KW - 1 ? 0 : ph + 1;
   }
 }
 
@@ -992,8 +1038,8 @@ __device__ __forceinline__ void fused_query_half(TiledParams p, const Tile& t, t
   prefetch(s_lo + 1);
   __syncthreads();          // the key half has staged the first planes
 
-  int ph = 0;
-  for (int s = s_lo; s <= s_hi; ++s) {
+  auto one_step = [&](auto PHc, int s) __attribute__((always_inline)) {
+    constexpr int PH = decltype(PHc)::value;
     const float4* kcur = sh.k[(s - s_lo) & 1];
     float* dl = sh.dl[(s - s_lo) & 1];
     const bool fill_new = s + 1 >= zlo && s + 1 < zhi;
@@ -1005,16 +1051,27 @@ __device__ __forceinline__ void fused_query_half(TiledParams p, const Tile& t, t
       pre.g0 = pre.g1 = pre.g2 = 0.f;
       pre.f0 = pre.f1 = pre.f2 = 0.f;
     }
-    switch (ph) {
-      case 0: fused_query_step<T, LT, 0>(st, pre, p, t, Ob, ccol, kcur, dl, lbase, tid, s, fill_new, active,
-                                         store_old, w_old); break;
-      case 1: fused_query_step<T, LT, 1>(st, pre, p, t, Ob, ccol, kcur, dl, lbase, tid, s, fill_new, active,
-                                         store_old, w_old); break;
-      default: fused_query_step<T, LT, 2>(st, pre, p, t, Ob, ccol, kcur, dl, lbase, tid, s, fill_new, active,
-                                          store_old, w_old); break;
-    }
-    ph = ph == KW - 1 ? 0 : ph + 1;
+    fused_query_step<T, LT, PH>(st, pre, p, t, Ob, ccol, kcur, dl, lbase, tid, s, fill_new, active, store_old,
+                                w_old);
     __syncthreads();        // B(s)
+  };
+  if (sizeof(LT) == 8) {
+    int s = s_lo;           // the three phases in sequence: the state never changes registers
+    while (true) {
+      one_step(std::integral_constant<int, 0>(), s); if (++s > s_hi) break;
+      one_step(std::integral_constant<int, 1>(), s); if (++s > s_hi) break;
+      one_step(std::integral_constant<int, 2>(), s); if (++s > s_hi) break;
+    }
+  } else {                  // (measured: the all-fp32 variant is 2 % faster with the phases under a switch)
+    int ph = 0;
+    for (int s = s_lo; s <= s_hi; ++s) {
+      switch (ph) {
+        case 0: one_step(std::integral_constant<int, 0>(), s); break;
+        case 1: one_step(std::integral_constant<int, 1>(), s); break;
+        default: one_step(std::integral_constant<int, 2>(), s); break;
+      }
+      ph = ph == KW - 1 ? 0 : ph + 1;
+    }
   }
 }
 
@@ -1034,6 +1091,10 @@ __device__ __forceinline__ void fused_key_half(TiledParams p, const Tile& t, typ
   Stager<KW, HS, T, float> stk, stq;
   stk.init(tid, t.y0, t.xs0, p.H, p.Wh);
   stq.init(tid, t.y0, t.xs0, p.H, p.Wh);
+  stk.zero_outside(sh.k[0]);
+  stk.zero_outside(sh.k[1]);
+#pragma unroll
+  for (int j = 0; j < QR; ++j) stq.zero_outside(sh.q[j]);
   int rpr, rpc;
   F::ring_rc(min(tid, NRP - 1), rpr, rpc);
   const int rgy = t.y0 - 1 + rpr, rgx = t.xs0 - 1 + rpc;
