@@ -950,9 +950,10 @@ bwd_shared_kernel(TiledParams p, float* dQ, float* dK) {
 // into the patch (about 10 % of all pairs), one ring query per lane.  The key half also stages all planes.
 //   step s (K plane s current), one barrier B(s):
 //     query half:  [refill newest role] [dl, dQ of 27 pairs -> DL[s&1]] [store dQ of plane s-1]   B(s)
-//     key half:    [ring queries of step s -> DL[s&1]]   B(s)   [gather plane s from DL[s&1], store dK]
-//                  [commit K plane s+2, Q / ring statistics plane s+3] [issue loads for K s+3, Q s+4]
-// so the gather of step s overlaps the query half's arithmetic of step s+1.
+//     key half:    B(s)   [gather plane s from DL[s&1]] [ring queries of step s+1 -> DL[(s+1)&1]]
+//                  [commit K plane s+2, Q / ring statistics plane s+3] [store dK] [issue loads for K s+3, Q s+4]
+// so the gather of step s overlaps the query half's arithmetic of step s+1, and the staged loads have a
+// whole step to arrive.
 template <class T, class LT>
 struct FusedBwd {
   static constexpr int KW = 3, HS = 1, R = 1;
@@ -1001,6 +1002,13 @@ __device__ __forceinline__ void fused_query_step(typename DqPolicy<3, 1, T, LT>:
   }
   if (active == 7u) Dq::template step_emit<PH, true, FusedBwd<T, LT>::DLA>(st, kcur, lbase, active, dl, tid);
   else Dq::template step_emit<PH, false, FusedBwd<T, LT>::DLA>(st, kcur, lbase, active, dl, tid);
+  // the prefetched registers are pinned here, before the store: a wait for them at the top of the next step
+  // would wait for the store as well
+  Dq::arrived(pre);
+  if (!t.lane_ok) {      // no such query: its dl must be zero for the keys next to it
+    pre.g0 = pre.g1 = pre.g2 = 0.f;
+    pre.f0 = pre.f1 = pre.f2 = 0.f;
+  }
   if (store_old) Dq::store(st[PH % KW], p, w_old);
 }
 
@@ -1036,6 +1044,8 @@ __device__ __forceinline__ void fused_query_half(TiledParams p, const Tile& t, t
     Dq::refill(st[1], pre, p);
   }
   prefetch(s_lo + 1);
+  Dq::arrived(pre);
+  if (!t.lane_ok) { pre.g0 = pre.g1 = pre.g2 = 0.f; pre.f0 = pre.f1 = pre.f2 = 0.f; }
   __syncthreads();          // the key half has staged the first planes
 
   auto one_step = [&](auto PHc, int s) __attribute__((always_inline)) {
@@ -1046,11 +1056,6 @@ __device__ __forceinline__ void fused_query_half(TiledParams p, const Tile& t, t
     const unsigned active = active_roles<KW>(s, zlo, zhi);
     const bool store_old = s - 1 >= t.z0 && s - 1 < t.z1 && t.lane_ok;
     const long long w_old = t.col + (long long)(s - 1) * pw;
-    Dq::arrived(pre);
-    if (!t.lane_ok) {      // no such query: its dl must be zero for the keys next to it
-      pre.g0 = pre.g1 = pre.g2 = 0.f;
-      pre.f0 = pre.f1 = pre.f2 = 0.f;
-    }
     fused_query_step<T, LT, PH>(st, pre, p, t, Ob, ccol, kcur, dl, lbase, tid, s, fill_new, active, store_old,
                                 w_old);
     __syncthreads();        // B(s)
@@ -1159,35 +1164,12 @@ __device__ __forceinline__ void fused_key_half(TiledParams p, const Tile& t, typ
     float* dl = sh.dl[kslot];
     const bool key_plane = s >= t.z0 && s < t.z1;
     auto qslot = [&](int d) { int v = qs + d; v += v < 0 ? QR : 0; v -= v >= QR ? QR : 0; return v; };
-    // ---- ring queries of this step
-    if (key_plane && has_ring) {
-      const int sl = qslot(1 - ra);                 // query plane z = s - a, a = ra - 1
-      float qf[8];
-      Lds<float>::get8(sh.q[sl], P::NPOS, ring_pos, qf);
-      LT qv[8];
-      widen8<LT, float>(qf, qv);
-      const float4 a4 = sh.sa[sl][rq];
-      const float base = fmaf((float)(ra - 1), a4.y, sh.sc[sl][rq]);
-#pragma unroll
-      for (int tt = 0; tt < 3; ++tt) {
-        int b, c;
-        const bool valid = F::ring_offset(qr_, qc_, tt, b, c);
-        const int kpos = valid ? (qr_ + b) * P::PC + qc_ + c : ring_pos;
-        float kf[8];
-        Lds<float>::get8(sh.k[kslot], P::NPOS, kpos, kf);
-        LT kv[8];
-        widen8<LT, float>(kf, kv);
-        const LT l = fma(dot8<LT>(qv, kv), (LT)p.qscale, (LT)a4.x);
-        const float tq = fmaf((float)b, a4.z, fmaf((float)c, a4.w, base));
-        dl[ra * F::DLA + 9 * NT + rq * 3 + tt] = valid ? exp2_fast((float)l) * tq : 0.f;
-      }
-    }
     __syncthreads();        // B(s)
     // ---- gather: dK of this lane's key in plane s
-    if (key_plane) {
-      float acc[8];
+    float acc[8];
 #pragma unroll
-      for (int c = 0; c < 8; ++c) acc[c] = 0.f;
+    for (int c = 0; c < 8; ++c) acc[c] = 0.f;
+    if (key_plane) {
 #pragma unroll 1                                     // (unrolled, all 27 vector reads get hoisted and spill)
       for (int a = 0; a < 3; ++a) {                 // plane offset a - 1: query plane s - (a - 1)
         const float4* qp = sh.q[qslot(1 - a)];
@@ -1200,14 +1182,37 @@ __device__ __forceinline__ void fused_key_half(TiledParams p, const Tile& t, typ
           axpy8(acc, d, qf);
         }
       }
-      // the staged planes go to LDS before the store (the wait for their loads must not cover it)
-      stk.commit(sh.k[kslot]);                      // K plane s + 2 replaces plane s
-      commit_q(qslot(3));                           // Q plane s + 3 replaces plane s - 2
-      if (t.lane_ok) store8_scaled(p.out + (t.col + (long long)s * pw) * 8, acc, p.scale);
-    } else {
-      stk.commit(sh.k[kslot]);
-      commit_q(qslot(3));
     }
+    // ---- ring queries of the NEXT step (their K and Q planes are already in LDS): ahead of the barrier that
+    // hands them to the gather, and ahead of the commit below, whose loads thereby get a whole step to arrive
+    if (s + 1 >= t.z0 && s + 1 < t.z1 && has_ring) {
+      float* dln = sh.dl[kslot ^ 1];
+      const int sl = qslot(2 - ra);                 // query plane z = (s + 1) - a, a = ra - 1
+      float qf[8];
+      Lds<float>::get8(sh.q[sl], P::NPOS, ring_pos, qf);
+      LT qv[8];
+      widen8<LT, float>(qf, qv);
+      const float4 a4 = sh.sa[sl][rq];
+      const float base = fmaf((float)(ra - 1), a4.y, sh.sc[sl][rq]);
+#pragma unroll
+      for (int tt = 0; tt < 3; ++tt) {
+        int b, c;
+        const bool valid = F::ring_offset(qr_, qc_, tt, b, c);
+        const int kpos = valid ? (qr_ + b) * P::PC + qc_ + c : ring_pos;
+        float kf[8];
+        Lds<float>::get8(sh.k[kslot ^ 1], P::NPOS, kpos, kf);
+        LT kv[8];
+        widen8<LT, float>(kf, kv);
+        const LT l = fma(dot8<LT>(qv, kv), (LT)p.qscale, (LT)a4.x);
+        const float tq = fmaf((float)b, a4.z, fmaf((float)c, a4.w, base));
+        dln[ra * F::DLA + 9 * NT + rq * 3 + tt] = valid ? exp2_fast((float)l) * tq : 0.f;
+      }
+    }
+    // the staged planes go to LDS last: K plane s + 2 replaces plane s, Q plane s + 3 replaces plane s - 2
+    stk.commit(sh.k[kslot]);
+    commit_q(qslot(3));
+    // (the store after the commit: the commit's wait for its loads must not cover it)
+    if (key_plane && t.lane_ok) store8_scaled(p.out + (t.col + (long long)s * pw) * 8, acc, p.scale);
     fetch_k(s + 3);
     fetch_q(s + 4);
     qs = qs + 1 == QR ? 0 : qs + 1;
