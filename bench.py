@@ -25,7 +25,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per modet_bwd call (one kernel: the dQ and dK marches of a tile side by side) from rocprofv3 --pmc
 # FETCH_SIZE / WRITE_SIZE runs of this command, scaled by what the same counters read for the device copy
 # below (profiles/config3_fwd_bwd_warp_kernels.txt); None where not measured.
-MEASURED_TRAFFIC_BYTES = {3: 1174769009}
+MEASURED_TRAFFIC_BYTES = {3: 1175499489}
 
 
 def main():
