@@ -42,24 +42,35 @@ template <> struct Vec<bf16_t, 8> {
   }
 };
 
-// displacement at fine voxel (z,y,x) from the half-resolution field fc[Dc,Hc,Wc,3] of one batch item:
-// the fine voxel centre sits at coarse coordinate (i + 0.5)/2 - 0.5 = i/2 - 0.25, clamped to the grid.
-// The interpolation runs in fp64: an fp32 result would carry ~2e-7 of rounding on a displacement of a
-// few voxels, and the warp multiplies that by the local feature gradient.
-__device__ __forceinline__ void upsampled_disp(const float* __restrict__ fc, int Dc, int Hc, int Wc, int z, int y,
-                                               int x, double* u) {
-  float cz = fminf(fmaxf(0.5f * z - 0.25f, 0.f), (float)(Dc - 1));
-  float cy = fminf(fmaxf(0.5f * y - 0.25f, 0.f), (float)(Hc - 1));
-  float cx = fminf(fmaxf(0.5f * x - 0.25f, 0.f), (float)(Wc - 1));
-  int z0 = (int)cz, y0 = (int)cy, x0 = (int)cx;       // coordinates are >= 0: truncation is floor
-  float tz = cz - z0, ty = cy - y0, tx = cx - x0;     // exact: multiples of 1/4
-  int z1 = min(z0 + 1, Dc - 1), y1 = min(y0 + 1, Hc - 1), x1 = min(x0 + 1, Wc - 1);  // weight 0 when clamped
+// Half-resolution field: the fine voxel centre i sits at coarse coordinate (i + 0.5)/2 - 0.5 = i/2 - 0.25,
+// clamped to the grid, so its lower coarse neighbour is (i - 1) >> 1 (0 for i = 0) and the weight of the
+// upper one is 1/4 for odd i, 3/4 for even i >= 2 (0 at i = 0 and wherever the upper neighbour is clamped).
+__device__ __forceinline__ int coarse_lo(int i) { return i > 0 ? (i - 1) >> 1 : 0; }
+
+// The coarse voxels a brick of fine voxels needs, staged once per workgroup in LDS: per axis the range
+// [coarse_lo(first), coarse_lo(last) + 1], at most extent/2 + 2 values.
+constexpr int kMaxTile = 192;     // coarse voxels per workgroup: bricks are at most 16 x 4 x 4 -> 10 x 4 x 4
+struct CoarseTile {
+  int oz, oy, ox, nz, ny, nx;     // origin and extents (clamped to the coarse grid)
+};
+
+// displacement at fine voxel (z,y,x) from the staged tile.  The interpolation runs in fp64: an fp32 result
+// would carry ~2e-7 of rounding on a displacement of a few voxels, and the warp multiplies that by the local
+// feature gradient.
+__device__ __forceinline__ void upsampled_disp(const float* __restrict__ tile, const CoarseTile& ct, int Dc, int Hc,
+                                               int Wc, int z, int y, int x, double* u) {
+  const int z0 = coarse_lo(z), y0 = coarse_lo(y), x0 = coarse_lo(x);
+  const int z1 = min(z0 + 1, Dc - 1), y1 = min(y0 + 1, Hc - 1), x1 = min(x0 + 1, Wc - 1);
+  // fractions are multiples of 1/4: exact in fp32; 0 where the coordinate was clamped
+  const float tz = (z == 0 || z1 == z0) ? 0.f : ((z & 1) ? 0.25f : 0.75f);
+  const float ty = (y == 0 || y1 == y0) ? 0.f : ((y & 1) ? 0.25f : 0.75f);
+  const float tx = (x == 0 || x1 == x0) ? 0.f : ((x & 1) ? 0.25f : 0.75f);
   u[0] = u[1] = u[2] = 0.0;
 #pragma unroll
   for (int c = 0; c < 8; ++c) {
-    int zi = (c & 4) ? z1 : z0, yi = (c & 2) ? y1 : y0, xi = (c & 1) ? x1 : x0;
-    double w = (double)(((c & 4) ? tz : 1.f - tz) * ((c & 2) ? ty : 1.f - ty) * ((c & 1) ? tx : 1.f - tx));
-    const float* p = fc + (((long long)zi * Hc + yi) * Wc + xi) * 3;
+    const int zi = ((c & 4) ? z1 : z0) - ct.oz, yi = ((c & 2) ? y1 : y0) - ct.oy, xi = ((c & 1) ? x1 : x0) - ct.ox;
+    const double w = (double)(((c & 4) ? tz : 1.f - tz) * ((c & 2) ? ty : 1.f - ty) * ((c & 1) ? tx : 1.f - tx));
+    const float* p = tile + ((zi * ct.ny + yi) * ct.nx + xi) * 3;
     u[0] = fma(w, (double)p[0], u[0]); u[1] = fma(w, (double)p[1], u[1]); u[2] = fma(w, (double)p[2], u[2]);
   }
   u[0] *= 2.0; u[1] *= 2.0; u[2] *= 2.0;
@@ -98,12 +109,31 @@ warp_kernel(const T* __restrict__ src, const float* __restrict__ field, T* __res
   const int ibz = blk % bk.nbz;
   const int b = blk / bk.nbz;
   const int x = ibx * bk.bx + lx, y = iby * bk.by + ly, z = ibz * bk.bz + lz;
-  if (lz >= bk.bz || x >= W || y >= H || z >= D) return;
+  const bool live = lz < bk.bz && x < W && y < H && z < D;
+  __shared__ float tile[HALF ? kMaxTile * 3 : 1];
+  CoarseTile ct = {};
+  if (HALF) {
+    // stage the coarse voxels this brick needs (every lane helps, also those outside the volume)
+    const int Dc = D / 2, Hc = H / 2, Wc = W / 2;
+    const int xf = ibx * bk.bx, yf = iby * bk.by, zf = ibz * bk.bz;
+    ct.ox = coarse_lo(xf); ct.oy = coarse_lo(yf); ct.oz = coarse_lo(zf);
+    ct.nx = min(coarse_lo(min(xf + bk.bx, W) - 1) + 1, Wc - 1) - ct.ox + 1;
+    ct.ny = min(coarse_lo(min(yf + bk.by, H) - 1) + 1, Hc - 1) - ct.oy + 1;
+    ct.nz = min(coarse_lo(min(zf + bk.bz, D) - 1) + 1, Dc - 1) - ct.oz + 1;
+    const float* fc = field + (long long)b * Dc * Hc * Wc * 3;
+    const int n = ct.nx * ct.ny * ct.nz;
+    for (int e = threadIdx.x; e < n; e += kThreads) {
+      const int ex = e % ct.nx, ey = (e / ct.nx) % ct.ny, ez = e / (ct.nx * ct.ny);
+      const float* p = fc + (((long long)(ct.oz + ez) * Hc + ct.oy + ey) * Wc + ct.ox + ex) * 3;
+      tile[e * 3] = p[0]; tile[e * 3 + 1] = p[1]; tile[e * 3 + 2] = p[2];
+    }
+    __syncthreads();
+  }
+  if (!live) return;
   const long long v = (((long long)b * D + z) * H + y) * W + x;
   double u[3];
   if (HALF) {
-    const int Dc = D / 2, Hc = H / 2, Wc = W / 2;
-    upsampled_disp(field + (long long)b * Dc * Hc * Wc * 3, Dc, Hc, Wc, z, y, x, u);
+    upsampled_disp(tile, ct, D / 2, H / 2, W / 2, z, y, x, u);
   } else {
     u[0] = field[v * 3]; u[1] = field[v * 3 + 1]; u[2] = field[v * 3 + 2];
   }
