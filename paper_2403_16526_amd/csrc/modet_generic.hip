@@ -142,16 +142,17 @@ __global__ void fill_zero_kernel(float* p, int n) {
   if (i < n) p[i] = 0.f;
 }
 
-// dbias[s, j] = sum over voxels of dl_j(p, s): per-block partial sums in LDS, one global atomic per
-// entry and block.  Accumulation order is not fixed, so the result is reproducible only to rounding.
+// dbias[s, j] = sum over voxels of dl_j(p, s): per-block partial sums in LDS (in fp64: a block sums tens of
+// thousands of cancelling terms), one global fp32 atomic per entry and block.  Accumulation order is not
+// fixed, so the result is reproducible only to rounding.
 template <class T>
 __global__ void __launch_bounds__(kThreads)
 dbias_kernel(Geo g, const T* __restrict__ Q, const T* __restrict__ K, const float* __restrict__ bias,
              const float* __restrict__ dphi, const float* __restrict__ phi, const float* __restrict__ lse,
              float* __restrict__ dbias, long long per_block) {
-  extern __shared__ float part[];
+  extern __shared__ double part[];
   const int nent = g.heads * g.k3;
-  for (int i = threadIdx.x; i < nent; i += kThreads) part[i] = 0.f;
+  for (int i = threadIdx.x; i < nent; i += kThreads) part[i] = 0.0;
   __syncthreads();
   const long long lo = (long long)blockIdx.x * per_block;
   const long long hi = lo + per_block < g.nvn ? lo + per_block : g.nvn;
@@ -173,11 +174,11 @@ dbias_kernel(Geo g, const T* __restrict__ Q, const T* __restrict__ K, const floa
             l = fma((double)g.scale, dot_d(q, K + nb * g.C + s * g.d, g.d), l);
           }
           const float dl = expf((float)(l - (double)ls)) * (g0 * (float)a + g1 * (float)bb + g2 * (float)c - gphi);
-          atomicAdd(&part[s * g.k3 + j], dl);
+          atomicAdd(&part[s * g.k3 + j], (double)dl);
         }
   }
   __syncthreads();
-  for (int i = threadIdx.x; i < nent; i += kThreads) atomicAdd(&dbias[i], part[i]);
+  for (int i = threadIdx.x; i < nent; i += kThreads) atomicAdd(&dbias[i], (float)part[i]);
 }
 
 inline unsigned blocks_for(long long n) { return (unsigned)((n + kThreads - 1) / kThreads); }
@@ -235,7 +236,7 @@ hipError_t launch_dbias(const Geo& g, int dtype, const void* Q, const void* K, c
   hipLaunchKernelGGL(fill_zero_kernel, dim3((nent + 255) / 256), dim3(256), 0, st, dbias, nent);
   long long per_block = 8192;
   unsigned nblk = (unsigned)((g.nvn + per_block - 1) / per_block);
-  size_t shm = sizeof(float) * (size_t)nent;
+  size_t shm = sizeof(double) * (size_t)nent;
   if (dtype == 0)
     hipLaunchKernelGGL((dbias_kernel<float>), dim3(nblk), dim3(kThreads), shm, st, g, (const float*)Q,
                        (const float*)K, bias, dphi, phi, lse, dbias, per_block);

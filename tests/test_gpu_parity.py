@@ -36,6 +36,9 @@ SMALL = [
     (1, 4, 5, 6, 24, 2, 3, "bf16"),         # the paper's large model: 12 channels per head
     (1, 4, 5, 6, 8, 1, 1, "f32"),           # k = 1
     (1, 5, 6, 9, 4, 1, 7, "f32"),
+    (1, 57, 17, 65, 8, 1, 3, "f32"),        # several chunks along D with ragged tiles: chunk seams of the marches
+    (2, 20, 9, 33, 8, 1, 3, "bf16"),
+    (1, 41, 12, 40, 16, 2, 3, "f32"),       # the same for the several-heads backward
 ]
 
 
