@@ -942,24 +942,25 @@ bwd_shared_kernel(TiledParams p, float* dQ, float* dK) {
   }
 }
 
-// ---- backward with every logit computed once (k = 3, one head: fused column = voxel) ----------------------
+// ---- backward with every logit computed once (k = 3, one or two heads) --------------------------------
 // 512 lanes per tile.  Lanes 0..255 ("query half") run the dQ march and hand dl of each of their 27 (query,
 // key) pairs to lanes 256..511 ("key half") through LDS; a key lane sums dl * Q over the 27 queries that see
 // its key of the current plane: dK needs no logits of its own.  Queries in the one-voxel ring around the
 // patch belong to neighbouring tiles; the key half recomputes dl for the pairs of those queries that point
-// into the patch (about 10 % of all pairs), one ring query per lane.  The key half also stages all planes.
+// into the patch (about 10 % of all pairs with one head), one or two ring queries per lane.  The ring is one
+// row above and below and HS fused columns (one voxel) left and right.  The key half also stages all planes.
 //   step s (K plane s current), one barrier B(s):
 //     query half:  [refill newest role] [dl, dQ of 27 pairs -> DL[s&1]] [store dQ of plane s-1]   B(s)
 //     key half:    B(s)   [gather plane s from DL[s&1]] [ring queries of step s+1 -> DL[(s+1)&1]]
 //                  [commit K plane s+2, Q / ring statistics plane s+3] [store dK] [issue loads for K s+3, Q s+4]
 // so the gather of step s overlaps the query half's arithmetic of step s+1, and the staged loads have a
 // whole step to arrive.
-template <class T, class LT>
+template <class T, class LT, int HS_>
 struct FusedBwd {
-  static constexpr int KW = 3, HS = 1, R = 1;
+  static constexpr int KW = 3, HS = HS_, R = 1;
   typedef Patch<KW, HS> P;
   typedef DqPolicy<KW, HS, T, LT> Dq;
-  static constexpr int NRP = 2 * P::PC + 2 * TY;     // ring positions: top row, bottom row, left, right column
+  static constexpr int NRP = 2 * P::PC + 2 * HS * TY;   // ring positions: top row, bottom row, left, right columns
   static constexpr int NRC = 3 * NRP;                // (ring position, inward offset) combinations per plane
   static constexpr int DLA = 9 * NT + NRC;           // floats per plane offset a: 9 in-plane offsets of the patch
   static constexpr int DLN = 3 * DLA;                //   lanes, then the ring combinations; one DL buffer
@@ -975,33 +976,40 @@ struct FusedBwd {
   static __device__ __forceinline__ void ring_rc(int rp, int& pr, int& pc) {
     if (rp < P::PC) { pr = 0; pc = rp; }
     else if (rp < 2 * P::PC) { pr = P::PR - 1; pc = rp - P::PC; }
-    else if (rp < 2 * P::PC + TY) { pr = rp - 2 * P::PC + 1; pc = 0; }
-    else { pr = rp - 2 * P::PC - TY + 1; pc = P::PC - 1; }
+    else if (rp < 2 * P::PC + HS * TY) { const int e = rp - 2 * P::PC; pr = e / HS + 1; pc = e % HS; }
+    else { const int e = rp - 2 * P::PC - HS * TY; pr = e / HS + 1; pc = HS + TX + e % HS; }
+  }
+  // the inverse, for a patch position outside the interior
+  static __device__ __forceinline__ int ring_index(int pr, int pc) {
+    if (pr == 0) return pc;
+    if (pr == P::PR - 1) return P::PC + pc;
+    if (pc < HS) return 2 * P::PC + (pr - 1) * HS + pc;
+    return 2 * P::PC + HS * TY + (pr - 1) * HS + (pc - HS - TX);
   }
   // offset (b, c) number t = 0..2 of a ring query towards the patch; false if it points outside
   static __device__ __forceinline__ bool ring_offset(int pr, int pc, int t, int& b, int& c) {
     if (pr == 0 || pr == P::PR - 1) { b = pr == 0 ? 1 : -1; c = t - 1; }
-    else { c = pc == 0 ? 1 : -1; b = t - 1; }
-    const int kr = pr + b, kc = pc + c;
-    return kr >= 1 && kr <= TY && kc >= 1 && kc <= TX;
+    else { c = pc < HS ? 1 : -1; b = t - 1; }
+    const int kr = pr + b, kc = pc + c * HS;
+    return kr >= 1 && kr <= TY && kc >= HS && kc < HS + TX;
   }
 };
 
-template <class T, class LT, int PH>
-__device__ __forceinline__ void fused_query_step(typename DqPolicy<3, 1, T, LT>::State (&st)[3],
-                                                 typename DqPolicy<3, 1, T, LT>::Pre& pre, const TiledParams& p,
+template <class T, class LT, int HS, int PH>
+__device__ __forceinline__ void fused_query_step(typename DqPolicy<3, HS, T, LT>::State (&st)[3],
+                                                 typename DqPolicy<3, HS, T, LT>::Pre& pre, const TiledParams& p,
                                                  const Tile& t, const T* Ob, long long ccol, const float4* kcur,
                                                  float* dl, int lbase, int tid, int s, bool fill_new, unsigned active,
                                                  bool store_old, long long w_old) {
-  typedef DqPolicy<3, 1, T, LT> Dq;
+  typedef DqPolicy<3, HS, T, LT> Dq;
   constexpr int KW = 3;
   if (fill_new) Dq::refill(st[(KW - 1 + PH) % KW], pre, p);
   {   // own features and statistics of the plane that enters next, one step ahead
     const int zc = clampi(s + 2, 0, p.D - 1);
     Dq::prefetch(p, Ob + (long long)zc * t.plane_elems, ccol + (long long)zc * p.H * p.Wh, pre);
   }
-  if (active == 7u) Dq::template step_emit<PH, true, FusedBwd<T, LT>::DLA>(st, kcur, lbase, active, dl, tid);
-  else Dq::template step_emit<PH, false, FusedBwd<T, LT>::DLA>(st, kcur, lbase, active, dl, tid);
+  if (active == 7u) Dq::template step_emit<PH, true, FusedBwd<T, LT, HS>::DLA>(st, kcur, lbase, active, dl, tid);
+  else Dq::template step_emit<PH, false, FusedBwd<T, LT, HS>::DLA>(st, kcur, lbase, active, dl, tid);
   // the prefetched registers are pinned here, before the store: a wait for them at the top of the next step
   // would wait for the store as well
   Dq::arrived(pre);
@@ -1012,10 +1020,10 @@ __device__ __forceinline__ void fused_query_step(typename DqPolicy<3, 1, T, LT>:
   if (store_old) Dq::store(st[PH % KW], p, w_old);
 }
 
-template <class T, class LT>
-__device__ __forceinline__ void fused_query_half(TiledParams p, const Tile& t, typename FusedBwd<T, LT>::Lds& sh,
+template <class T, class LT, int HS>
+__device__ __forceinline__ void fused_query_half(TiledParams p, const Tile& t, typename FusedBwd<T, LT, HS>::Lds& sh,
                                                  int tid) {
-  typedef FusedBwd<T, LT> F;
+  typedef FusedBwd<T, LT, HS> F;
   typedef typename F::Dq Dq;
   typedef typename F::P P;
   constexpr int KW = 3, R = 1;
@@ -1056,7 +1064,7 @@ __device__ __forceinline__ void fused_query_half(TiledParams p, const Tile& t, t
     const unsigned active = active_roles<KW>(s, zlo, zhi);
     const bool store_old = s - 1 >= t.z0 && s - 1 < t.z1 && t.lane_ok;
     const long long w_old = t.col + (long long)(s - 1) * pw;
-    fused_query_step<T, LT, PH>(st, pre, p, t, Ob, ccol, kcur, dl, lbase, tid, s, fill_new, active, store_old,
+    fused_query_step<T, LT, HS, PH>(st, pre, p, t, Ob, ccol, kcur, dl, lbase, tid, s, fill_new, active, store_old,
                                 w_old);
     __syncthreads();        // B(s)
   };
@@ -1080,12 +1088,13 @@ __device__ __forceinline__ void fused_query_half(TiledParams p, const Tile& t, t
   }
 }
 
-template <class T, class LT>
-__device__ __forceinline__ void fused_key_half(TiledParams p, const Tile& t, typename FusedBwd<T, LT>::Lds& sh,
+template <class T, class LT, int HS>
+__device__ __forceinline__ void fused_key_half(TiledParams p, const Tile& t, typename FusedBwd<T, LT, HS>::Lds& sh,
                                                int tid) {
-  typedef FusedBwd<T, LT> F;
+  typedef FusedBwd<T, LT, HS> F;
   typedef typename F::P P;
-  constexpr int KW = 3, HS = 1, QR = F::QR, NRP = F::NRP, NRC = F::NRC;
+  constexpr int KW = 3, QR = F::QR, NRP = F::NRP, NRC = F::NRC;
+  constexpr int NRQ = 3 * NRP, RPL = (NRQ + NT - 1) / NT;      // ring queries per step; per lane (1 or 2)
   const long long pw = (long long)p.H * p.Wh;
   const long long wb = (long long)t.b * p.D * pw;
   const T* Kb = (const T*)p.K + (long long)t.b * p.D * t.plane_elems;
@@ -1102,7 +1111,7 @@ __device__ __forceinline__ void fused_key_half(TiledParams p, const Tile& t, typ
   for (int j = 0; j < QR; ++j) stq.zero_outside(sh.q[j]);
   int rpr, rpc;
   F::ring_rc(min(tid, NRP - 1), rpr, rpc);
-  const int rgy = t.y0 - 1 + rpr, rgx = t.xs0 - 1 + rpc;
+  const int rgy = t.y0 - 1 + rpr, rgx = t.xs0 - HS + rpc;
   const bool ring_in = tid < NRP && rgy >= 0 && rgy < p.H && rgx >= 0 && rgx < p.Wh;
   const long long ring_w = (long long)min(max(rgy, 0), p.H - 1) * p.Wh + min(max(rgx, 0), p.Wh - 1);
   float r_lse, r_g[3], r_f[3];
@@ -1135,26 +1144,30 @@ __device__ __forceinline__ void fused_key_half(TiledParams p, const Tile& t, typ
   fetch_k(s_lo + 2);
   fetch_q(s_lo + 3);
 
-  // ---- this lane's ring query: plane offset a = ra - 1 (query plane s - a), ring position rq
-  const int ra = tid / NRP, rq = tid - ra * NRP;
-  const bool has_ring = tid < 3 * NRP;
-  int qr_, qc_;
-  F::ring_rc(has_ring ? rq : 0, qr_, qc_);
-  const int ring_pos = qr_ * P::PC + qc_;
-  // ---- gather addresses: the query of offset (b, c) sits at patch position (kr - b, kc - c)
-  const int kr = t.ty + 1, kc = t.tx + 1;
+  // ---- this lane's ring queries (number i: ring query tid + i * NT): plane offset a = ra - 1 (query plane
+  // s - a), ring position rq
+  int ra[RPL], rq[RPL], qr_[RPL], qc_[RPL], ring_pos[RPL];
+  bool has_ring[RPL];
+#pragma unroll
+  for (int i = 0; i < RPL; ++i) {
+    const int e = tid + i * NT;
+    has_ring[i] = e < NRQ;
+    ra[i] = has_ring[i] ? e / NRP : 0;
+    rq[i] = has_ring[i] ? e - ra[i] * NRP : 0;
+    F::ring_rc(rq[i], qr_[i], qc_[i]);
+    ring_pos[i] = qr_[i] * P::PC + qc_[i];
+  }
+  // ---- gather addresses: the query of offset (b, c) sits at patch position (kr - b, kc - c * HS)
+  const int kr = t.ty + 1, kc = t.tx + HS;
   int gidx[9];
 #pragma unroll
   for (int bc = 0; bc < 9; ++bc) {
     const int b = bc / 3 - 1, c = bc % 3 - 1;
-    const int qr = kr - b, qc = kc - c;
-    const bool inside = qr >= 1 && qr <= TY && qc >= 1 && qc <= TX;
-    int rp, tt;
-    if (qr == 0) { rp = qc; tt = c + 1; }
-    else if (qr == P::PR - 1) { rp = P::PC + qc; tt = c + 1; }
-    else if (qc == 0) { rp = 2 * P::PC + qr - 1; tt = b + 1; }
-    else { rp = 2 * P::PC + TY + qr - 1; tt = b + 1; }
-    gidx[bc] = inside ? (bc * NT + (qr - 1) * TX + (qc - 1)) : (9 * NT + rp * 3 + tt);
+    const int qr = kr - b, qc = kc - c * HS;
+    const bool inside = qr >= 1 && qr <= TY && qc >= HS && qc < HS + TX;
+    const bool row = qr == 0 || qr == P::PR - 1;      // ring rows number their offsets by c, ring columns by b
+    gidx[bc] = inside ? (bc * NT + (qr - 1) * TX + (qc - HS))
+                      : (9 * NT + F::ring_index(qr, qc) * 3 + (row ? c + 1 : b + 1));
   }
   __syncthreads();          // first planes staged
 
@@ -1178,34 +1191,38 @@ __device__ __forceinline__ void fused_key_half(TiledParams p, const Tile& t, typ
           const int b = bc / 3 - 1, c = bc % 3 - 1;
           const float d = dl[a * F::DLA + gidx[bc]];
           float qf[8];
-          Lds<float>::get8(qp, P::NPOS, (kr - b) * P::PC + kc - c, qf);
+          Lds<float>::get8(qp, P::NPOS, (kr - b) * P::PC + kc - c * HS, qf);
           axpy8(acc, d, qf);
         }
       }
     }
     // ---- ring queries of the NEXT step (their K and Q planes are already in LDS): ahead of the barrier that
     // hands them to the gather, and ahead of the commit below, whose loads thereby get a whole step to arrive
-    if (s + 1 >= t.z0 && s + 1 < t.z1 && has_ring) {
+    if (s + 1 >= t.z0 && s + 1 < t.z1) {
       float* dln = sh.dl[kslot ^ 1];
-      const int sl = qslot(2 - ra);                 // query plane z = (s + 1) - a, a = ra - 1
-      float qf[8];
-      Lds<float>::get8(sh.q[sl], P::NPOS, ring_pos, qf);
-      LT qv[8];
-      widen8<LT, float>(qf, qv);
-      const float4 a4 = sh.sa[sl][rq];
-      const float base = fmaf((float)(ra - 1), a4.y, sh.sc[sl][rq]);
 #pragma unroll
-      for (int tt = 0; tt < 3; ++tt) {
-        int b, c;
-        const bool valid = F::ring_offset(qr_, qc_, tt, b, c);
-        const int kpos = valid ? (qr_ + b) * P::PC + qc_ + c : ring_pos;
-        float kf[8];
-        Lds<float>::get8(sh.k[kslot ^ 1], P::NPOS, kpos, kf);
-        LT kv[8];
-        widen8<LT, float>(kf, kv);
-        const LT l = fma(dot8<LT>(qv, kv), (LT)p.qscale, (LT)a4.x);
-        const float tq = fmaf((float)b, a4.z, fmaf((float)c, a4.w, base));
-        dln[ra * F::DLA + 9 * NT + rq * 3 + tt] = valid ? exp2_fast((float)l) * tq : 0.f;
+      for (int i = 0; i < RPL; ++i) {
+        if (!has_ring[i]) continue;
+        const int sl = qslot(2 - ra[i]);              // query plane z = (s + 1) - a, a = ra - 1
+        float qf[8];
+        Lds<float>::get8(sh.q[sl], P::NPOS, ring_pos[i], qf);
+        LT qv[8];
+        widen8<LT, float>(qf, qv);
+        const float4 a4 = sh.sa[sl][rq[i]];
+        const float base = fmaf((float)(ra[i] - 1), a4.y, sh.sc[sl][rq[i]]);
+#pragma unroll
+        for (int tt = 0; tt < 3; ++tt) {
+          int b, c;
+          const bool valid = F::ring_offset(qr_[i], qc_[i], tt, b, c);
+          const int kpos = valid ? (qr_[i] + b) * P::PC + qc_[i] + c * HS : ring_pos[i];
+          float kf[8];
+          Lds<float>::get8(sh.k[kslot ^ 1], P::NPOS, kpos, kf);
+          LT kv[8];
+          widen8<LT, float>(kf, kv);
+          const LT l = fma(dot8<LT>(qv, kv), (LT)p.qscale, (LT)a4.x);
+          const float tq = fmaf((float)b, a4.z, fmaf((float)c, a4.w, base));
+          dln[ra[i] * F::DLA + 9 * NT + rq[i] * 3 + tt] = valid ? exp2_fast((float)l) * tq : 0.f;
+        }
       }
     }
     // the staged planes go to LDS last: K plane s + 2 replaces plane s, Q plane s + 3 replaces plane s - 2
@@ -1219,18 +1236,18 @@ __device__ __forceinline__ void fused_key_half(TiledParams p, const Tile& t, typ
   }
 }
 
-template <class T, class LT>
+template <class T, class LT, int HS>
 __global__ void __launch_bounds__(2 * NT) __attribute__((amdgpu_waves_per_eu(2)))
 bwd_fused_kernel(TiledParams p, float* dQ, float* dK) {
-  __shared__ typename FusedBwd<T, LT>::Lds sh;
+  __shared__ typename FusedBwd<T, LT, HS>::Lds sh;
   const int tid = threadIdx.x & (NT - 1);
   const Tile t = make_tile(p, xcd_remap(blockIdx.x, gridDim.x), tid);
   if (threadIdx.x < NT) {
     p.out = dQ;
-    fused_query_half<T, LT>(p, t, sh, tid);
+    fused_query_half<T, LT, HS>(p, t, sh, tid);
   } else {
     p.out = dK;
-    fused_key_half<T, LT>(p, t, sh, tid);
+    fused_key_half<T, LT, HS>(p, t, sh, tid);
   }
 }
 
@@ -1345,22 +1362,22 @@ hipError_t launch_bwd_t(const Geo& g, const void* Q, const void* K, const float*
   typedef DqPolicy<KW, HS, T, LT> A;
   typedef DkPolicy<KW, HS, T, LT> B;
   constexpr int W = Waves<LT, KW>::value;
-  bool fused = KW == 3 && HS == 1;
+  bool fused = KW == 3 && HS <= 2;      // (with 4 or 8 heads the fused kernel's LDS layout exceeds 160 KB)
 #ifdef MODET_TUNING_ENV
   if (const char* e = getenv("MODET_BWD_KERNEL")) fused = fused && atoi(e) == 0;
 #endif
-  if constexpr (KW == 3 && HS == 1) {
+  if constexpr (KW == 3 && HS <= 2) {
     if (fused) {
       // one 512-lane workgroup per tile; every logit computed once
       static int resident = 0;
       if (resident == 0) {
         int v = 0;
-        resident = (hipOccupancyMaxActiveBlocksPerMultiprocessor(&v, bwd_fused_kernel<T, LT>, 2 * NT, 0) ==
+        resident = (hipOccupancyMaxActiveBlocksPerMultiprocessor(&v, bwd_fused_kernel<T, LT, HS>, 2 * NT, 0) ==
                         hipSuccess && v > 0) ? v : 1;
       }
       TiledParams p = make_params(g, resident);
       p.Q = Q; p.K = K; p.dphi = dphi; p.phi_in = phi; p.lse_in = lse;
-      hipLaunchKernelGGL((bwd_fused_kernel<T, LT>), dim3(nblocks(p)), dim3(2 * NT), 0, st, p, dQ, dK);
+      hipLaunchKernelGGL((bwd_fused_kernel<T, LT, HS>), dim3(nblocks(p)), dim3(2 * NT), 0, st, p, dQ, dK);
       return hipGetLastError();
     }
   }
