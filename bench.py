@@ -115,13 +115,32 @@ def main():
     # algorithmic bytes (each tensor moved once, no stored attention)
     fwd_bytes = nvox * (2 * C * esz + 12 * heads)
     bwd_bytes = nvox * (2 * C * esz + 12 * heads + 8 * C)
-    dom_bytes, dom_ms, dom_name = ((bwd_bytes, t_bwd, "modet_bwd (bwd_fused_kernel)") if t_bwd >= t_fwd
+    bwd_kernel = ("generic kernels" if args.generic else "bwd_fused_kernel" if k == 3 and heads <= 2 else
+                  "bwd_shared_kernel" if k == 3 else "march_pair_kernel")
+    dom_bytes, dom_ms, dom_name = ((bwd_bytes, t_bwd, f"modet_bwd ({bwd_kernel})") if t_bwd >= t_fwd
                                   else (fwd_bytes, t_fwd, "modet_fwd"))
     achieved = dom_bytes / (dom_ms * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": dom_name, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                 "traffic": MEASURED_TRAFFIC_BYTES.get(args.config) if (t_bwd >= t_fwd and not args.generic) else None,
                 "algorithmic_bytes": dom_bytes, "avg_launch_ms": round(dom_ms, 4)}
+
+    # the same step against the vector-ALU roofline.  Algorithmic flops per window: k^3 pairs, each a d-term dot
+    # product in the forward, one in the backward, and d-term updates of dQ and dK (2 flops per FMA), plus ~16 for
+    # the two softmax evaluations.  Peak: the published vector rate of the arithmetic type, fp64 78.6 TFLOP/s
+    # (fp32 inputs: logits in fp64, and unpacked fp32 FMAs issue at that same rate) or fp32 157.3 TFLOP/s
+    # (bf16 inputs: everything in fp32; reachable only with packed instructions, which this build does not use).
+    d = C // heads
+    flops = nvn * (k ** 3) * (8 * d + 16)
+    alu_peak = 157.3 if dtype == "bf16" else 78.6
+    alu_ach = flops / ((t_fwd + t_bwd) * 1e-3) / 1e12
+    roofline_alu = {"bound": "alu", "kernel": "modet_fwd + modet_bwd", "achieved": round(alu_ach, 2), "peak": alu_peak,
+                    "unit": "TFLOP/s", "frac": round(alu_ach / alu_peak, 4), "traffic": None,
+                    "algorithmic_flops": flops, "avg_launch_ms": round(t_fwd + t_bwd, 4)}
+    if args.config == 5:      # 125 pairs per window: arithmetic, not memory, bounds this workload
+        roofline, roofline_other = roofline_alu, ("roofline_hbm", roofline)
+    else:
+        roofline_other = ("roofline_alu", roofline_alu)
 
     # a plain device copy of the same byte count: the attainable ceiling on this machine
     nb = (fwd_bytes + bwd_bytes) // 2
@@ -182,6 +201,7 @@ def main():
                    "logits": ("fp32" if dtype == "bf16" else
                               "fp32 (outside the parity tolerance)" if args.fast_logits else "fp64")},
         "roofline": roofline,
+        roofline_other[0]: roofline_other[1],
         "cpu_baseline": cpu,
         "fwd_ms": round(t_fwd, 4), "bwd_ms": round(t_bwd, 4),
         "hbm_gbs_fwd_bwd": round((fwd_bytes + bwd_bytes) / ((t_fwd + t_bwd) * 1e-3) / 1e9, 1),
