@@ -72,19 +72,24 @@ int modet_fwd(const void* Q, const void* K, const float* bias, float* phi, float
  *   phi, lse   in   nullable, both or neither: the outputs of modet_fwd for the same inputs.
  *                   When NULL the library recomputes them into `workspace`.
  *   dQ, dK     out  fp32, fully overwritten (no zeroing by the caller needed)
- *   dbias      out  nullable, fully overwritten
- *   workspace       at least modet_bwd_workspace_bytes(...) bytes, 16-byte aligned; may be
- *                   NULL when that size is 0
+ *   dbias      out  nullable, fully overwritten; its sums over all voxels are formed in fp64
+ *                   in `workspace` (the order of the additions is not fixed)
+ *   workspace       at least modet_bwd_workspace_bytes(...) bytes for the same shape and the
+ *                   flags that describe this call, 16-byte aligned; may be NULL when that
+ *                   size is 0
  */
 int modet_bwd(const void* Q, const void* K, const float* bias, const float* dphi,
               const float* phi, const float* lse, float* dQ, float* dK, float* dbias,
               int B, int D, int H, int W, int C, int heads, int k, float scale,
               modet_dtype in_dtype, void* workspace, size_t workspace_bytes, void* stream);
 
-/* Bytes of scratch modet_bwd needs.  have_stats != 0 means phi and lse will be passed in.
- * Returns 0 for invalid shapes (modet_bwd itself reports the error). */
+/* Bytes of scratch modet_bwd needs.  flags: MODET_WS_HAVE_STATS = phi and lse will be passed in
+ * (otherwise they are recomputed into the workspace, 16 bytes per window), MODET_WS_WANT_DBIAS =
+ * dbias will be requested (8 bytes per bias entry).  Returns 0 for invalid shapes (modet_bwd
+ * itself reports the error). */
+enum { MODET_WS_HAVE_STATS = 1, MODET_WS_WANT_DBIAS = 2 };
 size_t modet_bwd_workspace_bytes(int B, int D, int H, int W, int C, int heads, int k,
-                                 modet_dtype in_dtype, int have_stats);
+                                 modet_dtype in_dtype, int flags);
 
 /* Trilinear feature warp between pyramid levels: paper Section 3.1 (the moving feature map
  * of the next level is deformed by the upsampled total field before it enters ModeT).
@@ -116,7 +121,7 @@ int modet_set_kernel_path(int path);
 int modet_set_math_mode(int mode);
 
 /* Bit 0: modet_fwd, bit 1: modet_bwd run on the LDS-tiled kernels for this (head size, heads, k,
- * dtype) under path 0 (without bias and attention output). */
+ * dtype) under path 0 (with or without bias; not when the attention weights are requested). */
 int modet_has_tiled_kernels(int C, int heads, int k, modet_dtype in_dtype);
 
 const char* modet_status_string(int status);

@@ -53,7 +53,7 @@ int modet_fwd(const void* Q, const void* K, const float* bias, float* phi, float
   const Geo g = make_geo(B, D, H, W, C, heads, k, scale);
   hipStream_t st = (hipStream_t)stream;
   hipError_t e;
-  if (g_kernel_path == 0 && !attn && tiled_fwd_supported(g.d, heads, k, (int)in_dtype, bias != nullptr))
+  if (g_kernel_path == 0 && !attn && tiled_fwd_supported(g.d, heads, k, (int)in_dtype))
     e = launch_fwd_tiled(g, (int)in_dtype, g_math_mode == 1, Q, K, bias, phi, lse, st);
   else
     e = launch_fwd_generic(g, (int)in_dtype, Q, K, bias, phi, attn, lse, st);
@@ -61,11 +61,15 @@ int modet_fwd(const void* Q, const void* K, const float* bias, float* phi, float
 }
 
 size_t modet_bwd_workspace_bytes(int B, int D, int H, int W, int C, int heads, int k,
-                                 modet_dtype in_dtype, int have_stats) {
+                                 modet_dtype in_dtype, int flags) {
   if (check_op_shape(B, D, H, W, C, heads, k, (int)in_dtype) != MODET_OK) return 0;
-  if (have_stats) return 0;
-  const size_t nvn = (size_t)B * D * H * W * heads;
-  return round16(nvn * 3 * sizeof(float)) + round16(nvn * sizeof(float));   // phi, lse
+  size_t n = 0;
+  if (!(flags & MODET_WS_HAVE_STATS)) {
+    const size_t nvn = (size_t)B * D * H * W * heads;
+    n += round16(nvn * 3 * sizeof(float)) + round16(nvn * sizeof(float));   // phi, lse
+  }
+  if (flags & MODET_WS_WANT_DBIAS) n += round16((size_t)heads * k * k * k * sizeof(double));   // fp64 sums
+  return n;
 }
 
 int modet_bwd(const void* Q, const void* K, const float* bias, const float* dphi,
@@ -79,27 +83,38 @@ int modet_bwd(const void* Q, const void* K, const float* bias, const float* dphi
   if (misaligned(Q) || misaligned(K) || misaligned(bias) || misaligned(dphi) || misaligned(phi) ||
       misaligned(lse) || misaligned(dQ) || misaligned(dK) || misaligned(dbias) || misaligned(workspace))
     return MODET_ERR_ALIGN;
-  const size_t need = modet_bwd_workspace_bytes(B, D, H, W, C, heads, k, in_dtype, phi != nullptr);
+  const int flags = (phi ? MODET_WS_HAVE_STATS : 0) | (dbias ? MODET_WS_WANT_DBIAS : 0);
+  const size_t need = modet_bwd_workspace_bytes(B, D, H, W, C, heads, k, in_dtype, flags);
   if (need > 0 && (!workspace || workspace_bytes < need)) return MODET_ERR_WORKSPACE;
   const Geo g = make_geo(B, D, H, W, C, heads, k, scale);
   hipStream_t st = (hipStream_t)stream;
-  const bool tiled_f = g_kernel_path == 0 && tiled_fwd_supported(g.d, heads, k, (int)in_dtype, bias != nullptr);
-  const bool tiled_b = g_kernel_path == 0 && tiled_bwd_supported(g.d, heads, k, (int)in_dtype, bias != nullptr);
+  const bool tiled_f = g_kernel_path == 0 && tiled_fwd_supported(g.d, heads, k, (int)in_dtype);
+  const bool tiled_b = g_kernel_path == 0 && tiled_bwd_supported(g.d, heads, k, (int)in_dtype);
   hipError_t e = hipSuccess;
+  char* ws = (char*)workspace;
   if (!phi) {   // statistics pass: the forward kernel writes phi and lse into the workspace
-    float* wphi = (float*)workspace;
-    float* wlse = (float*)((char*)workspace + round16((size_t)g.nvn * 3 * sizeof(float)));
+    float* wphi = (float*)ws;
+    float* wlse = (float*)(ws + round16((size_t)g.nvn * 3 * sizeof(float)));
+    ws += round16((size_t)g.nvn * 3 * sizeof(float)) + round16((size_t)g.nvn * sizeof(float));
     e = tiled_f ? launch_fwd_tiled(g, (int)in_dtype, g_math_mode == 1, Q, K, bias, wphi, wlse, st)
               : launch_fwd_generic(g, (int)in_dtype, Q, K, bias, wphi, nullptr, wlse, st);
     if (e != hipSuccess) return MODET_ERR_LAUNCH;
     phi = wphi;
     lse = wlse;
   }
-  e = tiled_b ? launch_bwd_tiled(g, (int)in_dtype, g_math_mode == 1, Q, K, bias, dphi, phi, lse, dQ, dK, st)
-            : launch_bwd_generic(g, (int)in_dtype, Q, K, bias, dphi, phi, lse, dQ, dK, st);
+  double* acc = dbias ? (double*)ws : nullptr;     // fp64 sums of the bias gradient
+  if (acc && launch_dbias_begin(g, acc, st) != hipSuccess) return MODET_ERR_LAUNCH;
+  bool dbias_done = false;
+  if (tiled_b) {
+    const BwdTensors io = {Q, K, bias, dphi, phi, lse, dQ, dK, acc};
+    e = launch_bwd_tiled(g, (int)in_dtype, g_math_mode == 1, io, st, &dbias_done);
+  } else {
+    e = launch_bwd_generic(g, (int)in_dtype, Q, K, bias, dphi, phi, lse, dQ, dK, st);
+  }
   if (e != hipSuccess) return MODET_ERR_LAUNCH;
-  if (dbias) {
-    e = launch_dbias(g, (int)in_dtype, Q, K, bias, dphi, phi, lse, dbias, st);
+  if (acc) {
+    if (!dbias_done) e = launch_dbias_generic(g, (int)in_dtype, Q, K, bias, dphi, phi, lse, acc, st);
+    if (e == hipSuccess) e = launch_dbias_end(g, acc, dbias, st);
     if (e != hipSuccess) return MODET_ERR_LAUNCH;
   }
   return MODET_OK;
@@ -134,8 +149,8 @@ int modet_set_math_mode(int mode) {
 
 int modet_has_tiled_kernels(int C, int heads, int k, modet_dtype in_dtype) {
   if (C < 1 || heads < 1 || C % heads != 0) return 0;
-  return (tiled_fwd_supported(C / heads, heads, k, (int)in_dtype, false) ? 1 : 0) |
-         (tiled_bwd_supported(C / heads, heads, k, (int)in_dtype, false) ? 2 : 0);
+  return (tiled_fwd_supported(C / heads, heads, k, (int)in_dtype) ? 1 : 0) |
+         (tiled_bwd_supported(C / heads, heads, k, (int)in_dtype) ? 2 : 0);
 }
 
 const char* modet_status_string(int status) {

@@ -33,19 +33,34 @@ hipError_t launch_fwd_generic(const Geo& g, int dtype, const void* Q, const void
 hipError_t launch_bwd_generic(const Geo& g, int dtype, const void* Q, const void* K, const float* bias,
                               const float* dphi, const float* phi, const float* lse, float* dQ, float* dK,
                               hipStream_t st);
-hipError_t launch_dbias(const Geo& g, int dtype, const void* Q, const void* K, const float* bias,
-                        const float* dphi, const float* phi, const float* lse, float* dbias, hipStream_t st);
+// Gradient of the bias.  The sums over all voxels are accumulated in fp64 in `acc` ([heads, k^3] doubles of the
+// caller's workspace): _begin zeroes it, any number of kernels add to it, _end rounds it into dbias.
+hipError_t launch_dbias_begin(const Geo& g, double* acc, hipStream_t st);
+hipError_t launch_dbias_generic(const Geo& g, int dtype, const void* Q, const void* K, const float* bias,
+                                const float* dphi, const float* phi, const float* lse, double* acc, hipStream_t st);
+hipError_t launch_dbias_end(const Geo& g, const double* acc, float* dbias, hipStream_t st);
 hipError_t launch_warp(const void* src, const float* field, void* out, int B, int D, int H, int W, int C,
                        int half, int dtype, hipStream_t st);
 
 // LDS-tiled kernels (head size 8)
-bool tiled_fwd_supported(int d, int heads, int k, int dtype, bool has_bias);
-bool tiled_bwd_supported(int d, int heads, int k, int dtype, bool has_bias);
+bool tiled_fwd_supported(int d, int heads, int k, int dtype);
+bool tiled_bwd_supported(int d, int heads, int k, int dtype);
 // fast_logits: fp32 instead of fp64 dot products for fp32 inputs (about twice as fast, logits good to ~1e-6 only)
 hipError_t launch_fwd_tiled(const Geo& g, int dtype, bool fast_logits, const void* Q, const void* K,
                             const float* bias, float* phi, float* lse, hipStream_t st);
-hipError_t launch_bwd_tiled(const Geo& g, int dtype, bool fast_logits, const void* Q, const void* K,
-                            const float* bias, const float* dphi, const float* phi, const float* lse, float* dQ,
-                            float* dK, hipStream_t st);
+struct BwdTensors {
+  const void* Q; const void* K;
+  const float* bias;          // nullable
+  const float* dphi; const float* phi; const float* lse;
+  float* dQ; float* dK;
+  double* dbias_acc;          // nullable: where the sums of dl go if the kernel can provide them
+};
+// *dbias_done: the launched kernel adds the bias gradient's sums to io.dbias_acc
+hipError_t launch_bwd_tiled(const Geo& g, int dtype, bool fast_logits, const BwdTensors& io, hipStream_t st,
+                            bool* dbias_done);
+hipError_t launch_bwd_tiled_plain(const Geo& g, int dtype, bool fast_logits, const BwdTensors& io, hipStream_t st,
+                                  bool* dbias_done);
+hipError_t launch_bwd_tiled_biased(const Geo& g, int dtype, bool fast_logits, const BwdTensors& io, hipStream_t st,
+                                   bool* dbias_done);
 
 }  // namespace modet

@@ -137,19 +137,25 @@ grad_generic_kernel(Geo g, const T* __restrict__ Q, const T* __restrict__ K, con
   for (int i = 0; i < CH; ++i) out[v * g.C + c0 + i] = g.scale * acc[i];
 }
 
-__global__ void fill_zero_kernel(float* p, int n) {
+__global__ void fill_zero_kernel(double* p, int n) {
   int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) p[i] = 0.f;
+  if (i < n) p[i] = 0.0;
 }
 
-// dbias[s, j] = sum over voxels of dl_j(p, s): per-block partial sums in LDS (in fp64: a block sums tens of
-// thousands of cancelling terms), one global fp32 atomic per entry and block.  Accumulation order is not
-// fixed, so the result is reproducible only to rounding.
+__global__ void round_to_float_kernel(const double* a, float* o, int n) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) o[i] = (float)a[i];
+}
+
+// acc[s, j] += sum over voxels of dl_j(p, s): per-block partial sums in LDS, then one global atomic per entry
+// and block, all in fp64 (the terms cancel: a sum over millions of voxels is far smaller than the sum of their
+// magnitudes).  The order of the additions is not fixed; in fp64 that leaves the rounded fp32 result unchanged
+// in practice.
 template <class T>
 __global__ void __launch_bounds__(kThreads)
 dbias_kernel(Geo g, const T* __restrict__ Q, const T* __restrict__ K, const float* __restrict__ bias,
              const float* __restrict__ dphi, const float* __restrict__ phi, const float* __restrict__ lse,
-             float* __restrict__ dbias, long long per_block) {
+             double* __restrict__ acc, long long per_block) {
   extern __shared__ double part[];
   const int nent = g.heads * g.k3;
   for (int i = threadIdx.x; i < nent; i += kThreads) part[i] = 0.0;
@@ -178,7 +184,7 @@ dbias_kernel(Geo g, const T* __restrict__ Q, const T* __restrict__ K, const floa
         }
   }
   __syncthreads();
-  for (int i = threadIdx.x; i < nent; i += kThreads) atomicAdd(&dbias[i], (float)part[i]);
+  for (int i = threadIdx.x; i < nent; i += kThreads) atomicAdd(&acc[i], part[i]);
 }
 
 inline unsigned blocks_for(long long n) { return (unsigned)((n + kThreads - 1) / kThreads); }
@@ -230,19 +236,30 @@ hipError_t launch_bwd_generic(const Geo& g, int dtype, const void* Q, const void
   return hipGetLastError();
 }
 
-hipError_t launch_dbias(const Geo& g, int dtype, const void* Q, const void* K, const float* bias,
-                        const float* dphi, const float* phi, const float* lse, float* dbias, hipStream_t st) {
+hipError_t launch_dbias_begin(const Geo& g, double* acc, hipStream_t st) {
   const int nent = g.heads * g.k3;
-  hipLaunchKernelGGL(fill_zero_kernel, dim3((nent + 255) / 256), dim3(256), 0, st, dbias, nent);
+  hipLaunchKernelGGL(fill_zero_kernel, dim3((nent + 255) / 256), dim3(256), 0, st, acc, nent);
+  return hipGetLastError();
+}
+
+hipError_t launch_dbias_end(const Geo& g, const double* acc, float* dbias, hipStream_t st) {
+  const int nent = g.heads * g.k3;
+  hipLaunchKernelGGL(round_to_float_kernel, dim3((nent + 255) / 256), dim3(256), 0, st, acc, dbias, nent);
+  return hipGetLastError();
+}
+
+hipError_t launch_dbias_generic(const Geo& g, int dtype, const void* Q, const void* K, const float* bias,
+                                const float* dphi, const float* phi, const float* lse, double* acc, hipStream_t st) {
+  const int nent = g.heads * g.k3;
   long long per_block = 8192;
   unsigned nblk = (unsigned)((g.nvn + per_block - 1) / per_block);
   size_t shm = sizeof(double) * (size_t)nent;
   if (dtype == 0)
     hipLaunchKernelGGL((dbias_kernel<float>), dim3(nblk), dim3(kThreads), shm, st, g, (const float*)Q,
-                       (const float*)K, bias, dphi, phi, lse, dbias, per_block);
+                       (const float*)K, bias, dphi, phi, lse, acc, per_block);
   else
     hipLaunchKernelGGL((dbias_kernel<bf16_t>), dim3(nblk), dim3(kThreads), shm, st, g, (const bf16_t*)Q,
-                       (const bf16_t*)K, bias, dphi, phi, lse, dbias, per_block);
+                       (const bf16_t*)K, bias, dphi, phi, lse, acc, per_block);
   return hipGetLastError();
 }
 

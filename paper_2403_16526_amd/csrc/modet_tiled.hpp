@@ -24,6 +24,7 @@
 //     is confined to the dot product, the subtraction of the softmax reference and the running softmax
 //     sums of the forward; everything else is fp32.  Logits are kept in log2 units (the in-flight
 //     operand is pre-multiplied by scale*log2(e)).
+#pragma once
 #include "modet_common.hpp"
 #include <type_traits>
 #ifdef MODET_TUNING_ENV
@@ -47,7 +48,9 @@ __device__ __forceinline__ float log2_fast(float x) { return __builtin_amdgcn_lo
 
 struct TiledParams {
   const void* Q; const void* K;
+  const float* bias;                                              // [heads, k^3] or NULL (zeros)
   const float* dphi; const float* phi_in; const float* lse_in;   // backward only
+  double* dbias_acc;                                              // backward, optional: [heads, k^3] sums of dl
   float* phi; float* lse;                                         // forward outputs
   float* out;                                                     // dQ or dK
   int B, D, H, Wh;          // Wh = W * heads fused columns
@@ -307,6 +310,20 @@ __device__ __forceinline__ void store8_scaled(float* o, const float (&acc)[8], f
   *reinterpret_cast<float4*>(o + 4) = make_float4(acc[4] * sc, acc[5] * sc, acc[6] * sc, acc[7] * sc);
 }
 
+// The bias B[s, o] of Eq. 3 lives in LDS as bt[o * HS + s], in the units and type of the logits (times log2 e).
+// A lane's head is its fused column modulo HS, so it reads through bt + head at the compile-time offset o * HS,
+// o = ((a+R)*KW + b+R)*KW + c+R.  A NULL bias is all zeros (its gradient may still be wanted).
+template <class LT, int KW, int HS>
+__device__ __forceinline__ void fill_bias_table(LT* bt, const float* bias, int tid, int nthreads) {
+  constexpr int K3 = KW * KW * KW;
+  for (int i = tid; i < K3 * HS; i += nthreads) {
+    const int j = i / HS, h = i - j * HS;
+    bt[i] = bias ? (LT)bias[h * K3 + j] * (LT)kLog2e : (LT)0;
+  }
+}
+template <class LT, int KW, int HS, bool BIAS> struct BiasTable { LT v[KW * KW * KW * HS]; };
+template <class LT, int KW, int HS> struct BiasTable<LT, KW, HS, false> {};
+
 template <int KW>
 __device__ __forceinline__ unsigned active_roles(int s, int z0, int z1) {
   constexpr int R = KW / 2;
@@ -355,6 +372,7 @@ __device__ void fwd_query_two_pass(const TiledParams& p, long long w) {
         for (int c = 0; c < 8; ++c) l = fma((double)Ld<T>::one(Qp + c), (double)Ld<T>::one(Kp + c), l);
         l *= (double)p.qscale;
       }
+      if (p.bias) l += (double)p.bias[(xs % HS) * (KW * KW * KW) + j] * (double)kLog2e;
       if (pass == 0) {
         mx = fmax(mx, l);
       } else {
@@ -367,10 +385,12 @@ __device__ void fwd_query_two_pass(const TiledParams& p, long long w) {
   if (p.lse) p.lse[w] = (float)((mx + (double)log2_fast((float)Z)) * (double)kLn2);
 }
 
-template <int KW_, int HS_, class T_, class LT>
+template <int KW_, int HS_, class T_, class LT, bool BIAS = false>
 struct FwdPolicy {
   static constexpr int KW = KW_, HS = HS_, R = KW_ / 2;
+  static constexpr bool kBias = BIAS;
   typedef T_ T;
+  typedef LT Logit;
   typedef LT ET;                           // LDS element type: no conversions in the inner loop
   typedef Patch<KW, HS> P;
   static constexpr bool kStats = false;
@@ -425,7 +445,7 @@ struct FwdPolicy {
   }
   template <int PH, bool FULL>
   static __device__ __forceinline__ void step(State (&st)[KW], const typename Lds<ET>::chunk* kb, const float4*,
-                                              const float*, int lbase, unsigned active) {
+                                              const float*, int lbase, unsigned active, const LT* bl) {
     LT plane[KW];      // per role: sum of the weights of this plane of its window
 #pragma unroll
     for (int i = 0; i < KW; ++i) plane[i] = (LT)0;
@@ -438,7 +458,12 @@ struct FwdPolicy {
         Lds<ET>::get8(kb, P::NPOS, lbase + b * P::PC + c * HS, kv);
 #pragma unroll
         for (int i = 0; i < KW; ++i)
-          if (FULL || (active & (1u << i))) l[i][c] = dot8<LT>(st[(i + PH) % KW].q, kv, st[(i + PH) % KW].nref);
+          if (FULL || (active & (1u << i))) {
+            // role i sees this plane under the plane offset a = R - i
+            LT init = st[(i + PH) % KW].nref;
+            if (BIAS) init += bl[(((KW - 1 - i) * KW + b) * KW + c) * HS];
+            l[i][c] = dot8<LT>(st[(i + PH) % KW].q, kv, init);
+          }
       }
       // role KW-1 is the plane that entered last: this step shows it the first plane of its window
 #pragma unroll
@@ -471,10 +496,12 @@ struct FwdPolicy {
 };
 
 // ---- backward, dQ: lane owns a query column; K planes in LDS (fp32); w = exp(l - lse) ----------------
-template <int KW_, int HS_, class T_, class LT>
+template <int KW_, int HS_, class T_, class LT, bool BIAS = false>
 struct DqPolicy {
   static constexpr int KW = KW_, HS = HS_, R = KW_ / 2;
+  static constexpr bool kBias = BIAS;
   typedef T_ T;
+  typedef LT Logit;
   typedef float ET;                        // the fp32 copy is needed for the fp32 accumulation anyway
   typedef Patch<KW, HS> P;
   static constexpr bool kStats = false;
@@ -527,7 +554,7 @@ struct DqPolicy {
   }
   template <int PH, bool FULL>
   static __device__ __forceinline__ void step(State (&st)[KW], const typename Lds<ET>::chunk* kb, const float4*,
-                                              const float*, int lbase, unsigned active) {
+                                              const float*, int lbase, unsigned active, const LT* bl) {
 #pragma unroll
     for (int b = 0; b < KW; ++b)
 #pragma unroll
@@ -540,7 +567,9 @@ struct DqPolicy {
         for (int i = 0; i < KW; ++i)
           if (FULL || (active & (1u << i))) {
             State& s = st[(i + PH) % KW];
-            const float w = exp2_fast((float)dot8<LT>(s.q, kv, s.nlse));
+            LT init = s.nlse;
+            if (BIAS) init += bl[(((KW - 1 - i) * KW + b) * KW + c) * HS];
+            const float w = exp2_fast((float)dot8<LT>(s.q, kv, init));
             // t = g.o - g.phi with o = (R - i, b - R, c - R)
             float tt = s.ngphi;
             if (R - i != 0) tt = fmaf((float)(R - i), s.g0, tt);
@@ -555,7 +584,7 @@ struct DqPolicy {
   // active emit 0
   template <int PH, bool FULL, int DLA>
   static __device__ __forceinline__ void step_emit(State (&st)[KW], const typename Lds<ET>::chunk* kb, int lbase,
-                                                   unsigned active, float* dl_out, int li) {
+                                                   unsigned active, float* dl_out, int li, const LT* bl) {
 #pragma unroll
     for (int b = 0; b < KW; ++b)
 #pragma unroll
@@ -569,7 +598,9 @@ struct DqPolicy {
           const int j = (KW - 1 - i) * DLA + (b * KW + c) * NT;      // a + R = R - i + R = KW - 1 - i
           if (FULL || (active & (1u << i))) {
             State& s = st[(i + PH) % KW];
-            const float w = exp2_fast((float)dot8<LT>(s.q, kv, s.nlse));
+            LT init = s.nlse;
+            if (BIAS) init += bl[(((KW - 1 - i) * KW + b) * KW + c) * HS];
+            const float w = exp2_fast((float)dot8<LT>(s.q, kv, init));
             float tt = s.ngphi;
             if (R - i != 0) tt = fmaf((float)(R - i), s.g0, tt);
             if (b - R != 0) tt = fmaf((float)(b - R), s.g1, tt);
@@ -591,10 +622,12 @@ struct DqPolicy {
 // ---- backward, dK: lane owns a key column; Q planes (fp32) + per-query statistics in LDS ----------------
 // The query at patch position (row, col) = (ty + r, tx + cc*HS) sees this lane's key of role i under the
 // offset (a, b, c) = (i - R, R - r, R - cc).
-template <int KW_, int HS_, class T_, class LT>
+template <int KW_, int HS_, class T_, class LT, bool BIAS = false>
 struct DkPolicy {
   static constexpr int KW = KW_, HS = HS_, R = KW_ / 2;
+  static constexpr bool kBias = BIAS;
   typedef T_ T;
+  typedef LT Logit;
   typedef float ET;
   typedef Patch<KW, HS> P;
   static constexpr bool kStats = true;
@@ -628,7 +661,7 @@ struct DkPolicy {
   }
   template <int PH, bool FULL>
   static __device__ __forceinline__ void step(State (&st)[KW], const typename Lds<ET>::chunk* qb, const float4* sa,
-                                              const float* sc, int lbase, unsigned active) {
+                                              const float* sc, int lbase, unsigned active, const LT* bl) {
 #pragma unroll
     for (int r = 0; r < KW; ++r)
 #pragma unroll
@@ -647,7 +680,9 @@ struct DkPolicy {
         for (int i = 0; i < KW; ++i)
           if (FULL || (active & (1u << i))) {
             State& s = st[(i + PH) % KW];
-            const float w = exp2_fast((float)dot8<LT>(s.k, qv, nlse));
+            LT init = nlse;
+            if (BIAS) init += bl[((i * KW + (KW - 1 - r)) * KW + (KW - 1 - cc)) * HS];
+            const float w = exp2_fast((float)dot8<LT>(s.k, qv, init));
             const float tt = (i - R != 0) ? fmaf((float)(i - R), a4.y, tb) : tb;
             axpy8(s.acc, w * tt, qf);
           }
@@ -662,12 +697,20 @@ struct DkPolicy {
 template <class Pol, bool STATS> struct SharedPlanes;
 template <class Pol> struct SharedPlanes<Pol, false> {
   typename Lds<typename Pol::ET>::chunk main[2][Lds<typename Pol::ET>::CH * Pol::P::NPOS];
+  BiasTable<typename Pol::Logit, Pol::KW, Pol::HS, Pol::kBias> bias;
 };
 template <class Pol> struct SharedPlanes<Pol, true> {
   typename Lds<typename Pol::ET>::chunk main[2][Lds<typename Pol::ET>::CH * Pol::P::NPOS];
   float4 sa[2][Pol::P::NPOS];
   float sc[2][Pol::P::NPOS];
+  BiasTable<typename Pol::Logit, Pol::KW, Pol::HS, Pol::kBias> bias;
 };
+// this lane's view of the bias table (NULL for a policy without bias)
+template <class Pol, class Sh>
+__device__ __forceinline__ const typename Pol::Logit* lane_bias(const Sh& sh, int xs) {
+  if constexpr (Pol::kBias) return sh.bias.v + xs % Pol::HS;
+  else return nullptr;
+}
 
 template <class Pol, int PH, class Sh, class Stg, class SStg>
 __device__ __forceinline__ void march_body(typename Pol::State (&st)[Pol::KW], const TiledParams& p, const Tile& t,
@@ -678,8 +721,9 @@ __device__ __forceinline__ void march_body(typename Pol::State (&st)[Pol::KW], c
   const float4* sa = nullptr;
   const float* sc = nullptr;
   if constexpr (Pol::kStats) { sa = sh.sa[cur]; sc = sh.sc[cur]; }
-  if (active == (1u << KW) - 1u) Pol::template step<PH, true>(st, sh.main[cur], sa, sc, lbase, active);
-  else Pol::template step<PH, false>(st, sh.main[cur], sa, sc, lbase, active);
+  const typename Pol::Logit* bl = lane_bias<Pol>(sh, t.xs);
+  if (active == (1u << KW) - 1u) Pol::template step<PH, true>(st, sh.main[cur], sa, sc, lbase, active, bl);
+  else Pol::template step<PH, false>(st, sh.main[cur], sa, sc, lbase, active, bl);
   // the staged plane goes to LDS before the results are stored: the wait for its loads would otherwise
   // also wait for those stores (one counter covers loads and stores on this chip)
   if (commit_next) {
@@ -734,6 +778,7 @@ __device__ __forceinline__ void march(const TiledParams& p, unsigned id, void* s
     stg.zero_outside(sh.main[j]);
     if constexpr (Pol::kStats) sst.zero_outside(sh.sa[j], sh.sc[j]);
   }
+  if constexpr (Pol::kBias) fill_bias_table<typename Pol::Logit, KW, HS>(sh.bias.v, p.bias, threadIdx.x, NT);
 
   typename Pol::State st[KW];
 #pragma unroll
@@ -840,20 +885,25 @@ struct BwdRings {
   float4 sa[RING][P::NPOS];
   float sc[RING][P::NPOS];
 };
+template <int KW, int HS, class LT, bool BIAS>
+struct BwdRingsB : BwdRings<KW, HS> {
+  BiasTable<LT, KW, HS, BIAS> bias;
+};
 
 // the part of a step after the arithmetic, for one half; OTHER = the ring this half refills from
 template <class Pol, int PH, class Commit>
 __device__ __forceinline__ void shared_step(typename Pol::State (&st)[Pol::KW], const TiledParams& p, const Tile& t,
                                             const float4* lds_cur, const float4* sa_cur, const float* sc_cur,
                                             const float4* own_new, const float4* sa_new, const float* sc_new,
-                                            int lbase, int s, bool fill_new, const Commit& commit_staged) {
+                                            int lbase, int s, bool fill_new, const Commit& commit_staged,
+                                            const typename Pol::Logit* bl) {
   constexpr int KW = Pol::KW, R = KW / 2;
   typedef typename Pol::P P;
   // the plane s + R enters the window of the newest role: its slot was freed by the store of the last step
   if (fill_new) Pol::refill_lds(st[(KW - 1 + PH) % KW], own_new, lbase + R * P::PC + R * Pol::HS, sa_new, sc_new, p);
   const unsigned active = active_roles<KW>(s, t.z0, t.z1);
-  if (active == (1u << KW) - 1u) Pol::template step<PH, true>(st, lds_cur, sa_cur, sc_cur, lbase, active);
-  else Pol::template step<PH, false>(st, lds_cur, sa_cur, sc_cur, lbase, active);
+  if (active == (1u << KW) - 1u) Pol::template step<PH, true>(st, lds_cur, sa_cur, sc_cur, lbase, active, bl);
+  else Pol::template step<PH, false>(st, lds_cur, sa_cur, sc_cur, lbase, active, bl);
   commit_staged();       // before the stores: its wait for the loads must not cover them
   if ((active & 1u) && t.lane_ok)          // role 0 has seen its whole window
     Pol::store(st[PH % KW], p, t.col + (long long)(s - R) * p.H * p.Wh);
@@ -899,6 +949,8 @@ __device__ __forceinline__ void shared_march(const TiledParams& p, const Tile& t
 #pragma unroll
   for (int j = 0; j <= R; ++j) { fetch(s_first + j); commit(j); }
   fetch(s_first + R + 1);
+  if constexpr (Pol::kBias && !IS_DK) fill_bias_table<typename Pol::Logit, KW, HS>(sh.bias.v, p.bias, tid, NT);
+  const typename Pol::Logit* bl = lane_bias<Pol>(sh, t.xs);
   __syncthreads();
 
   int cur = 0;                               // cur = (s - s_first) % RING
@@ -910,7 +962,7 @@ __device__ __forceinline__ void shared_march(const TiledParams& p, const Tile& t
     // the staged plane s + R + 1 replaces the plane s - 1, which nobody reads any more
     auto commit_staged = [&]() { if (s + R + 1 <= s_last) commit(wr); };
     shared_step<Pol, PH>(st, p, t, mine[cur], sh.sa[cur], sh.sc[cur], other[nw], sh.sa[nw], sh.sc[nw], lbase, s,
-                         fill_new, commit_staged);
+                         fill_new, commit_staged, bl);
     fetch(s + R + 2);
     cur = cur + 1 == RING ? 0 : cur + 1;
     __syncthreads();
@@ -927,18 +979,18 @@ __device__ __forceinline__ void shared_march(const TiledParams& p, const Tile& t
   }
 }
 
-template <int KW, int HS, class T, class LT>
+template <int KW, int HS, class T, class LT, bool BIAS>
 __global__ void __launch_bounds__(2 * NT) __attribute__((amdgpu_waves_per_eu(2)))
 bwd_shared_kernel(TiledParams p, float* dQ, float* dK) {
-  __shared__ BwdRings<KW, HS> sh;
+  __shared__ BwdRingsB<KW, HS, LT, BIAS> sh;
   const int tid = threadIdx.x & (NT - 1);
   Tile t = make_tile(p, xcd_remap(blockIdx.x, gridDim.x), tid);
   if (threadIdx.x < NT) {
     p.out = dQ;
-    shared_march<DqPolicy<KW, HS, T, LT>, false>(p, t, sh, tid);
+    shared_march<DqPolicy<KW, HS, T, LT, BIAS>, false>(p, t, sh, tid);
   } else {
     p.out = dK;
-    shared_march<DkPolicy<KW, HS, T, LT>, true>(p, t, sh, tid);
+    shared_march<DkPolicy<KW, HS, T, LT, BIAS>, true>(p, t, sh, tid);
   }
 }
 
@@ -955,11 +1007,11 @@ bwd_shared_kernel(TiledParams p, float* dQ, float* dK) {
 //                  [commit K plane s+2, Q / ring statistics plane s+3] [store dK] [issue loads for K s+3, Q s+4]
 // so the gather of step s overlaps the query half's arithmetic of step s+1, and the staged loads have a
 // whole step to arrive.
-template <class T, class LT, int HS_>
+template <class T, class LT, int HS_, bool BIAS>
 struct FusedBwd {
   static constexpr int KW = 3, HS = HS_, R = 1;
   typedef Patch<KW, HS> P;
-  typedef DqPolicy<KW, HS, T, LT> Dq;
+  typedef DqPolicy<KW, HS, T, LT, BIAS> Dq;
   static constexpr int NRP = 2 * P::PC + 2 * HS * TY;   // ring positions: top row, bottom row, left, right columns
   static constexpr int NRC = 3 * NRP;                // (ring position, inward offset) combinations per plane
   static constexpr int DLA = 9 * NT + NRC;           // floats per plane offset a: 9 in-plane offsets of the patch
@@ -971,6 +1023,7 @@ struct FusedBwd {
     float4 sa[QR][NRP];      // (-lse*log2e, g) of the ring queries
     float sc[QR][NRP];       // -g.phi
     float dl[2][DLN];
+    BiasTable<LT, KW, HS, BIAS> bias;
   };
   // ring position -> patch row / column
   static __device__ __forceinline__ void ring_rc(int rp, int& pr, int& pc) {
@@ -995,21 +1048,22 @@ struct FusedBwd {
   }
 };
 
-template <class T, class LT, int HS, int PH>
-__device__ __forceinline__ void fused_query_step(typename DqPolicy<3, HS, T, LT>::State (&st)[3],
-                                                 typename DqPolicy<3, HS, T, LT>::Pre& pre, const TiledParams& p,
+template <class T, class LT, int HS, bool BIAS, int PH>
+__device__ __forceinline__ void fused_query_step(typename DqPolicy<3, HS, T, LT, BIAS>::State (&st)[3],
+                                                 typename DqPolicy<3, HS, T, LT, BIAS>::Pre& pre, const TiledParams& p,
                                                  const Tile& t, const T* Ob, long long ccol, const float4* kcur,
                                                  float* dl, int lbase, int tid, int s, bool fill_new, unsigned active,
-                                                 bool store_old, long long w_old) {
-  typedef DqPolicy<3, HS, T, LT> Dq;
+                                                 bool store_old, long long w_old, const LT* bl) {
+  typedef DqPolicy<3, HS, T, LT, BIAS> Dq;
   constexpr int KW = 3;
   if (fill_new) Dq::refill(st[(KW - 1 + PH) % KW], pre, p);
   {   // own features and statistics of the plane that enters next, one step ahead
     const int zc = clampi(s + 2, 0, p.D - 1);
     Dq::prefetch(p, Ob + (long long)zc * t.plane_elems, ccol + (long long)zc * p.H * p.Wh, pre);
   }
-  if (active == 7u) Dq::template step_emit<PH, true, FusedBwd<T, LT, HS>::DLA>(st, kcur, lbase, active, dl, tid);
-  else Dq::template step_emit<PH, false, FusedBwd<T, LT, HS>::DLA>(st, kcur, lbase, active, dl, tid);
+  constexpr int DLA = FusedBwd<T, LT, HS, BIAS>::DLA;
+  if (active == 7u) Dq::template step_emit<PH, true, DLA>(st, kcur, lbase, active, dl, tid, bl);
+  else Dq::template step_emit<PH, false, DLA>(st, kcur, lbase, active, dl, tid, bl);
   // the prefetched registers are pinned here, before the store: a wait for them at the top of the next step
   // would wait for the store as well
   Dq::arrived(pre);
@@ -1020,10 +1074,10 @@ __device__ __forceinline__ void fused_query_step(typename DqPolicy<3, HS, T, LT>
   if (store_old) Dq::store(st[PH % KW], p, w_old);
 }
 
-template <class T, class LT, int HS>
-__device__ __forceinline__ void fused_query_half(TiledParams p, const Tile& t, typename FusedBwd<T, LT, HS>::Lds& sh,
-                                                 int tid) {
-  typedef FusedBwd<T, LT, HS> F;
+template <class T, class LT, int HS, bool BIAS>
+__device__ __forceinline__ void fused_query_half(TiledParams p, const Tile& t,
+                                                 typename FusedBwd<T, LT, HS, BIAS>::Lds& sh, int tid) {
+  typedef FusedBwd<T, LT, HS, BIAS> F;
   typedef typename F::Dq Dq;
   typedef typename F::P P;
   constexpr int KW = 3, R = 1;
@@ -1054,6 +1108,8 @@ __device__ __forceinline__ void fused_query_half(TiledParams p, const Tile& t, t
   prefetch(s_lo + 1);
   Dq::arrived(pre);
   if (!t.lane_ok) { pre.g0 = pre.g1 = pre.g2 = 0.f; pre.f0 = pre.f1 = pre.f2 = 0.f; }
+  if constexpr (BIAS) fill_bias_table<LT, KW, HS>(sh.bias.v, p.bias, tid, NT);
+  const LT* bl = lane_bias<Dq>(sh, t.xs);
   __syncthreads();          // the key half has staged the first planes
 
   auto one_step = [&](auto PHc, int s) __attribute__((always_inline)) {
@@ -1064,8 +1120,8 @@ __device__ __forceinline__ void fused_query_half(TiledParams p, const Tile& t, t
     const unsigned active = active_roles<KW>(s, zlo, zhi);
     const bool store_old = s - 1 >= t.z0 && s - 1 < t.z1 && t.lane_ok;
     const long long w_old = t.col + (long long)(s - 1) * pw;
-    fused_query_step<T, LT, HS, PH>(st, pre, p, t, Ob, ccol, kcur, dl, lbase, tid, s, fill_new, active, store_old,
-                                w_old);
+    fused_query_step<T, LT, HS, BIAS, PH>(st, pre, p, t, Ob, ccol, kcur, dl, lbase, tid, s, fill_new, active,
+                                          store_old, w_old, bl);
     __syncthreads();        // B(s)
   };
   if (sizeof(LT) == 8) {
@@ -1088,10 +1144,10 @@ __device__ __forceinline__ void fused_query_half(TiledParams p, const Tile& t, t
   }
 }
 
-template <class T, class LT, int HS>
-__device__ __forceinline__ void fused_key_half(TiledParams p, const Tile& t, typename FusedBwd<T, LT, HS>::Lds& sh,
-                                               int tid) {
-  typedef FusedBwd<T, LT, HS> F;
+template <class T, class LT, int HS, bool BIAS>
+__device__ __forceinline__ void fused_key_half(TiledParams p, const Tile& t,
+                                               typename FusedBwd<T, LT, HS, BIAS>::Lds& sh, int tid) {
+  typedef FusedBwd<T, LT, HS, BIAS> F;
   typedef typename F::P P;
   constexpr int KW = 3, QR = F::QR, NRP = F::NRP, NRC = F::NRC;
   constexpr int NRQ = 3 * NRP, RPL = (NRQ + NT - 1) / NT;      // ring queries per step; per lane (1 or 2)
@@ -1169,6 +1225,13 @@ __device__ __forceinline__ void fused_key_half(TiledParams p, const Tile& t, typ
     gidx[bc] = inside ? (bc * NT + (qr - 1) * TX + (qc - HS))
                       : (9 * NT + F::ring_index(qr, qc) * 3 + (row ? c + 1 : b + 1));
   }
+  // ---- gradient of the bias: this half also sums dl over the patch's queries.  Lane = (row, segment):
+  // row = (plane offset, in-plane offset) of the DL buffer, segment = 32 of its 256 lanes; the four components
+  // of the vector reads are columns of fixed parity, hence of a fixed head.  The reads of a lane are rotated
+  // by its row so that the rows of a wave fall into different banks.
+  const int db_row = tid >> 3, db_seg = tid & 7;
+  const bool db_on = BIAS && p.dbias_acc != nullptr && db_row < 27;
+  double db_sum[4] = {0.0, 0.0, 0.0, 0.0};
   __syncthreads();          // first planes staged
 
   int qs = 0;               // Q slot of plane s (s = s_lo: 0)
@@ -1196,6 +1259,21 @@ __device__ __forceinline__ void fused_key_half(TiledParams p, const Tile& t, typ
         }
       }
     }
+    if constexpr (BIAS) {
+      // pairs of step s whose query plane z = s + 1 - (a + 1) this workgroup owns (the halo planes' pairs are
+      // counted by the workgroups that own them)
+      const int da = db_row / 9, zq = s + 1 - da;
+      if (db_on && zq >= t.z0 && zq < t.z1) {
+        const float4* src = reinterpret_cast<const float4*>(dl + da * F::DLA + (db_row - da * 9) * NT + db_seg * 32);
+        float4 sum = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const float4 v = src[(i + db_row) & 7];
+          sum.x += v.x; sum.y += v.y; sum.z += v.z; sum.w += v.w;
+        }
+        db_sum[0] += (double)sum.x; db_sum[1] += (double)sum.y; db_sum[2] += (double)sum.z; db_sum[3] += (double)sum.w;
+      }
+    }
     // ---- ring queries of the NEXT step (their K and Q planes are already in LDS): ahead of the barrier that
     // hands them to the gather, and ahead of the commit below, whose loads thereby get a whole step to arrive
     if (s + 1 >= t.z0 && s + 1 < t.z1) {
@@ -1219,7 +1297,8 @@ __device__ __forceinline__ void fused_key_half(TiledParams p, const Tile& t, typ
           Lds<float>::get8(sh.k[kslot ^ 1], P::NPOS, kpos, kf);
           LT kv[8];
           widen8<LT, float>(kf, kv);
-          const LT l = fma(dot8<LT>(qv, kv), (LT)p.qscale, (LT)a4.x);
+          LT l = fma(dot8<LT>(qv, kv), (LT)p.qscale, (LT)a4.x);
+          if constexpr (BIAS) l += sh.bias.v[((ra[i] * 3 + b + 1) * 3 + c + 1) * HS + qc_[i] % HS];
           const float tq = fmaf((float)b, a4.z, fmaf((float)c, a4.w, base));
           dln[ra[i] * F::DLA + 9 * NT + rq[i] * 3 + tt] = valid ? exp2_fast((float)l) * tq : 0.f;
         }
@@ -1234,20 +1313,38 @@ __device__ __forceinline__ void fused_key_half(TiledParams p, const Tile& t, typ
     fetch_q(s + 4);
     qs = qs + 1 == QR ? 0 : qs + 1;
   }
+  if constexpr (BIAS) {
+    if (p.dbias_acc != nullptr) {      // (uniform) fold the components into heads, the 8 segments into one lane
+      double hsum[HS];
+#pragma unroll
+      for (int h = 0; h < HS; ++h) {
+        double v = 0.0;
+#pragma unroll
+        for (int c = h; c < 4; c += HS) v += db_sum[c];
+#pragma unroll
+        for (int m = 1; m < 8; m <<= 1) v += __shfl_xor(v, m);
+        hsum[h] = v;
+      }
+      if (db_on && db_seg == 0) {
+#pragma unroll
+        for (int h = 0; h < HS; ++h) atomicAdd(p.dbias_acc + h * 27 + db_row, hsum[h]);
+      }
+    }
+  }
 }
 
-template <class T, class LT, int HS>
+template <class T, class LT, int HS, bool BIAS>
 __global__ void __launch_bounds__(2 * NT) __attribute__((amdgpu_waves_per_eu(2)))
 bwd_fused_kernel(TiledParams p, float* dQ, float* dK) {
-  __shared__ typename FusedBwd<T, LT, HS>::Lds sh;
+  __shared__ typename FusedBwd<T, LT, HS, BIAS>::Lds sh;
   const int tid = threadIdx.x & (NT - 1);
   const Tile t = make_tile(p, xcd_remap(blockIdx.x, gridDim.x), tid);
   if (threadIdx.x < NT) {
     p.out = dQ;
-    fused_query_half<T, LT, HS>(p, t, sh, tid);
+    fused_query_half<T, LT, HS, BIAS>(p, t, sh, tid);
   } else {
     p.out = dK;
-    fused_key_half<T, LT, HS>(p, t, sh, tid);
+    fused_key_half<T, LT, HS, BIAS>(p, t, sh, tid);
   }
 }
 
@@ -1332,91 +1429,15 @@ int resident_workgroups() {
 template <class Pol, int WAVES>
 void launch_march(const Geo& g, TiledParams io, hipStream_t st) {
   TiledParams p = make_params(g, resident_workgroups<Pol, WAVES>());
-  p.Q = io.Q; p.K = io.K; p.phi = io.phi; p.lse = io.lse;
+  p.Q = io.Q; p.K = io.K; p.bias = io.bias; p.phi = io.phi; p.lse = io.lse;
   p.dphi = io.dphi; p.phi_in = io.phi_in; p.lse_in = io.lse_in; p.out = io.out;
   hipLaunchKernelGGL((march_kernel<Pol, WAVES>), dim3(nblocks(p)), dim3(NT), 0, st, p);
 }
 
-template <int KW, int HS, class T, class LT>
-hipError_t launch_fwd_t(const Geo& g, const void* Q, const void* K, float* phi, float* lse, hipStream_t st) {
-  TiledParams io = {};
-  io.Q = Q; io.K = K; io.phi = phi; io.lse = lse;
-  launch_march<FwdPolicy<KW, HS, T, LT>, Waves<LT, KW>::value>(g, io, st);
-  return hipGetLastError();
-}
-
-template <class PolA, class PolB, int WAVES>
-int resident_pair_workgroups() {
-  static int n = 0;
-  if (n == 0) {
-    int v = 0;
-    n = (hipOccupancyMaxActiveBlocksPerMultiprocessor(&v, march_pair_kernel<PolA, PolB, WAVES>, NT, 0) ==
-             hipSuccess && v > 0) ? v : WAVES;
-  }
-  return n;
-}
-
-template <int KW, int HS, class T, class LT>
-hipError_t launch_bwd_t(const Geo& g, const void* Q, const void* K, const float* dphi, const float* phi,
-                        const float* lse, float* dQ, float* dK, hipStream_t st) {
-  typedef DqPolicy<KW, HS, T, LT> A;
-  typedef DkPolicy<KW, HS, T, LT> B;
-  constexpr int W = Waves<LT, KW>::value;
-  bool fused = KW == 3 && HS <= 2;      // (with 4 or 8 heads the fused kernel's LDS layout exceeds 160 KB)
-#ifdef MODET_TUNING_ENV
-  if (const char* e = getenv("MODET_BWD_KERNEL")) fused = fused && atoi(e) == 0;
-#endif
-  if constexpr (KW == 3 && HS <= 2) {
-    if (fused) {
-      // one 512-lane workgroup per tile; every logit computed once
-      static int resident = 0;
-      if (resident == 0) {
-        int v = 0;
-        resident = (hipOccupancyMaxActiveBlocksPerMultiprocessor(&v, bwd_fused_kernel<T, LT, HS>, 2 * NT, 0) ==
-                        hipSuccess && v > 0) ? v : 1;
-      }
-      TiledParams p = make_params(g, resident);
-      p.Q = Q; p.K = K; p.dphi = dphi; p.phi_in = phi; p.lse_in = lse;
-      hipLaunchKernelGGL((bwd_fused_kernel<T, LT, HS>), dim3(nblocks(p)), dim3(2 * NT), 0, st, p, dQ, dK);
-      return hipGetLastError();
-    }
-  }
-  if constexpr (KW == 3) {
-    // one 512-lane workgroup per tile (both marches share their staged planes)
-    static int resident = 0;
-    if (resident == 0) {
-      int v = 0;
-      resident = (hipOccupancyMaxActiveBlocksPerMultiprocessor(&v, bwd_shared_kernel<KW, HS, T, LT>, 2 * NT, 0) ==
-                      hipSuccess && v > 0) ? v : 1;
-    }
-    TiledParams p = make_params(g, resident);
-    p.Q = Q; p.K = K; p.dphi = dphi; p.phi_in = phi; p.lse_in = lse;
-    hipLaunchKernelGGL((bwd_shared_kernel<KW, HS, T, LT>), dim3(nblocks(p)), dim3(2 * NT), 0, st, p, dQ, dK);
-  } else {
-    // two workgroups per tile: the chunk length is chosen for twice the tile count
-    TiledParams p = make_params(g, resident_pair_workgroups<A, B, W>(), 2);
-    p.Q = Q; p.K = K; p.dphi = dphi; p.phi_in = phi; p.lse_in = lse;
-    hipLaunchKernelGGL((march_pair_kernel<A, B, W>), dim3(2 * nblocks(p)), dim3(NT), 0, st, p, dQ, dK);
-  }
-  return hipGetLastError();
-}
-
 }  // namespace
+}  // namespace modet
 
-
-// Covered: head size 8, no bias;  k = 3: 1/2/4/8 heads, fp32 inputs (fp64 logits) and bf16 inputs (fp32
-// logits: the bf16 tolerance leaves room);  k = 5: 1/2 heads, bf16 inputs.
-bool tiled_fwd_supported(int d, int heads, int k, int dtype, bool has_bias) {
-  if (d != 8 || has_bias) return false;
-  if (k == 3) return heads == 1 || heads == 2 || heads == 4 || heads == 8;
-  if (k == 5) return dtype == 1 && (heads == 1 || heads == 2);
-  return false;
-}
-
-bool tiled_bwd_supported(int d, int heads, int k, int dtype, bool has_bias) {
-  return tiled_fwd_supported(d, heads, k, dtype, has_bias);
-}
-
+// calls CALL(KW, HS, T, LT) for the instantiation that covers (g.k, g.heads, dtype, fast_logits)
 #define MODET_DISPATCH(CALL)                                                     \
   if (g.k == 3 && dtype == 0 && fast_logits) {                                   \
     switch (g.heads) {                                                           \
@@ -1446,22 +1467,3 @@ bool tiled_bwd_supported(int d, int heads, int k, int dtype, bool has_bias) {
     }                                                                            \
   }                                                                              \
   return hipErrorNotSupported;
-
-hipError_t launch_fwd_tiled(const Geo& g, int dtype, bool fast_logits, const void* Q, const void* K,
-                            const float* bias, float* phi, float* lse, hipStream_t st) {
-  (void)bias;
-#define MODET_FWD(KW, HS, T, LT) launch_fwd_t<KW, HS, T, LT>(g, Q, K, phi, lse, st)
-  MODET_DISPATCH(MODET_FWD)
-#undef MODET_FWD
-}
-
-hipError_t launch_bwd_tiled(const Geo& g, int dtype, bool fast_logits, const void* Q, const void* K,
-                            const float* bias, const float* dphi, const float* phi, const float* lse, float* dQ,
-                            float* dK, hipStream_t st) {
-  (void)bias;
-#define MODET_BWD(KW, HS, T, LT) launch_bwd_t<KW, HS, T, LT>(g, Q, K, dphi, phi, lse, dQ, dK, st)
-  MODET_DISPATCH(MODET_BWD)
-#undef MODET_BWD
-}
-
-}  // namespace modet

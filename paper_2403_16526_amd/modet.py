@@ -126,8 +126,12 @@ def modet_fwd(Q, K, heads: int, k: int, scale: float = 0.0, bias=None, want_attn
     return out if len(out) > 1 else phi
 
 
-def modet_bwd_workspace_bytes(B, D, H, W, C, heads, k, dtype=MODET_F32, have_stats=False) -> int:
-    return int(_lib.modet_bwd_workspace_bytes(B, D, H, W, C, heads, k, dtype, int(bool(have_stats))))
+MODET_WS_HAVE_STATS, MODET_WS_WANT_DBIAS = 1, 2
+
+
+def modet_bwd_workspace_bytes(B, D, H, W, C, heads, k, dtype=MODET_F32, have_stats=False, want_dbias=False) -> int:
+    flags = (MODET_WS_HAVE_STATS if have_stats else 0) | (MODET_WS_WANT_DBIAS if want_dbias else 0)
+    return int(_lib.modet_bwd_workspace_bytes(B, D, H, W, C, heads, k, dtype, flags))
 
 
 def modet_bwd(Q, K, dphi, heads: int, k: int, scale: float = 0.0, bias=None, phi=None, lse=None,
@@ -139,7 +143,7 @@ def modet_bwd(Q, K, dphi, heads: int, k: int, scale: float = 0.0, bias=None, phi
     f32 = dict(device=Q.device, dtype=torch.float32)
     dQ, dK = out if out is not None else (torch.empty(Q.shape, **f32), torch.empty(Q.shape, **f32))
     dbias = torch.empty((heads, k ** 3), **f32) if want_dbias else None
-    need = modet_bwd_workspace_bytes(B, D, H, W, C, heads, k, _in_dtype(Q), phi is not None)
+    need = modet_bwd_workspace_bytes(B, D, H, W, C, heads, k, _in_dtype(Q), phi is not None, want_dbias)
     if workspace is None and need:
         workspace = torch.empty(need, device=Q.device, dtype=torch.uint8)
     wbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()

@@ -42,6 +42,31 @@ def test_fp32_configs_full_volume(modet, no):
     assert_close(dK.cpu().numpy(), ref_dK, "f32", f"config {no} dK")
 
 
+def test_config3_with_bias_and_bias_gradient_full_volume(modet):
+    """config 3 with a bias B (Eq. 3) of the size a trained one would have: every element of phi, lse, dQ, dK,
+    and the bias gradient, a sum over all 6.9 million voxels whose terms largely cancel."""
+    c = synth.make_config(3)
+    heads, k = c["heads"], c["k"]
+    bias = (0.5 * synth.normal(79, 0, (heads, k ** 3))).astype(np.float32)
+    Q, K, g, tb = up(c["Q"]), up(c["K"]), up(c["dphi"]), up(bias)
+    phi, lse = modet.modet_fwd(Q, K, heads, k, bias=tb, want_lse=True)
+    dQ, dK, db = modet.modet_bwd(Q, K, g, heads, k, bias=tb, phi=phi, lse=lse, want_dbias=True)
+    torch.cuda.synchronize()
+    ref_phi, ref_lse = oracle.modet_fwd(c["Q"], c["K"], heads, k, bias=bias, want_lse=True)
+    assert_close(phi.cpu().numpy(), ref_phi, "f32", "phi")
+    assert_close(lse.cpu().numpy(), ref_lse, "f32", "lse")
+    del ref_phi, ref_lse
+    ref_dQ, ref_dK, ref_db = oracle.modet_bwd(c["Q"], c["K"], c["dphi"], heads, k, bias=bias, form="scatter",
+                                              want_dbias=True)
+    assert_close(dQ.cpu().numpy(), ref_dQ, "f32", "dQ")
+    assert_close(dK.cpu().numpy(), ref_dK, "f32", "dK")
+    # each entry sums ~7e6 terms of either sign and magnitude up to ~1: the fp32 terms themselves carry ~1e-7
+    # relative rounding each, so the sum is good to ~1e-7 * sqrt(7e6) * rms(term) in absolute terms
+    err = np.abs(db.cpu().numpy() - ref_db)
+    print("dbias: max |ref|", np.abs(ref_db).max(), "max abs err", err.max())
+    assert err.max() <= 1e-5 * np.abs(ref_db).max() + 2e-4
+
+
 def test_config3_without_forward_statistics(modet):
     """the backward alone (statistics recomputed into the workspace) on a slab of config 3."""
     c = synth.make_config(3, D=24)

@@ -56,10 +56,10 @@ def run_case(modet, shape, path, with_bias=False, stats="pass"):
     try:
         phi, lse = modet.modet_fwd(Q, K, heads, k, bias=tb, want_lse=True)
         phi2, attn = modet.modet_fwd(Q, K, heads, k, bias=tb, want_attn=True)
-        if stats == "pass":
-            dQ, dK, db = modet.modet_bwd(Q, K, g, heads, k, bias=tb, phi=phi, lse=lse, want_dbias=True)
-        else:
-            dQ, dK, db = modet.modet_bwd(Q, K, g, heads, k, bias=tb, want_dbias=True)
+        given = dict(phi=phi, lse=lse) if stats == "pass" else {}
+        dQ, dK, db = modet.modet_bwd(Q, K, g, heads, k, bias=tb, want_dbias=True, **given)
+        # without the bias gradient (and without bias) other kernels run
+        dQ2, dK2 = modet.modet_bwd(Q, K, g, heads, k, bias=tb, **given)
         torch.cuda.synchronize()
     finally:
         modet.modet_set_kernel_path(old)
@@ -73,6 +73,8 @@ def run_case(modet, shape, path, with_bias=False, stats="pass"):
     assert_close(lse.cpu().numpy(), ref_lse, dtype, "lse " + tag)
     assert_close(dQ.cpu().numpy(), ref_dQ, dtype, "dQ " + tag, scale=gs)
     assert_close(dK.cpu().numpy(), ref_dK, dtype, "dK " + tag, scale=gs)
+    assert_close(dQ2.cpu().numpy(), ref_dQ, dtype, "dQ (no dbias) " + tag, scale=gs)
+    assert_close(dK2.cpu().numpy(), ref_dK, dtype, "dK (no dbias) " + tag, scale=gs)
     # dbias is a sum over all voxels: its rounding grows with the number of terms
     assert_close(db.cpu().numpy(), ref_db, dtype, "dbias " + tag, scale=10.0 * gs)
 
@@ -83,10 +85,19 @@ def test_small_cases_match_oracle(modet, shape, path):
     run_case(modet, shape, path)
 
 
-@pytest.mark.parametrize("shape", [SMALL[1], SMALL[3], SMALL[6], SMALL[12]], ids=lambda s: "x".join(map(str, s)))
+# with bias: one / two heads (k = 3) with chunk seams, four and eight heads, k = 5, 6 channels per head, both dtypes
+BIASED = [SMALL[1], SMALL[3], SMALL[4], SMALL[6], SMALL[8], SMALL[12], SMALL[16], SMALL[17], SMALL[18]]
+
+
+@pytest.mark.parametrize("shape", BIASED, ids=lambda s: "x".join(map(str, s)))
 @pytest.mark.parametrize("path", [0, 1], ids=["auto", "generic"])
 def test_bias_and_recomputed_statistics(modet, shape, path):
     run_case(modet, shape, path, with_bias=True, stats="recompute")
+
+
+@pytest.mark.parametrize("shape", [SMALL[16], SMALL[18], SMALL[6]], ids=lambda s: "x".join(map(str, s)))
+def test_bias_with_statistics_passed_in(modet, shape):
+    run_case(modet, shape, 0, with_bias=True, stats="pass")
 
 
 def test_explicit_scale_and_peaked_attention(modet):
@@ -123,13 +134,18 @@ def test_forward_survives_logits_far_above_the_first_window_row(modet, dtype, he
     if dtype == "bf16":
         Q, K = synth.to_bf16_bits(Q), synth.to_bf16_bits(K)
     scale = 300.0
-    ref_phi, _, ref_lse = oracle.modet_fwd(Q, K, heads, k, scale=scale, dtype=dtype, want_attn=True, want_lse=True)
-    for path in (0, 1):
-        old = modet.modet_set_kernel_path(path)
-        phi, lse = modet.modet_fwd(up(Q, dtype), up(K, dtype), heads, k, scale=scale, want_lse=True)
-        modet.modet_set_kernel_path(old)
-        assert_close(phi.cpu().numpy(), ref_phi, dtype, f"phi path {path}")
-        np.testing.assert_allclose(lse.cpu().numpy(), ref_lse, rtol=2e-2 if dtype == "bf16" else 2e-6, atol=1e-5)
+    for bias in (None, (0.5 * synth.normal(78, 0, (heads, k ** 3))).astype(np.float32)):
+        ref_phi, _, ref_lse = oracle.modet_fwd(Q, K, heads, k, scale=scale, bias=bias, dtype=dtype, want_attn=True,
+                                               want_lse=True)
+        for path in (0, 1):
+            old = modet.modet_set_kernel_path(path)
+            phi, lse = modet.modet_fwd(up(Q, dtype), up(K, dtype), heads, k, scale=scale, bias=up(bias),
+                                       want_lse=True)
+            modet.modet_set_kernel_path(old)
+            tag = f"path {path} bias {bias is not None}"
+            assert_close(phi.cpu().numpy(), ref_phi, dtype, "phi " + tag)
+            np.testing.assert_allclose(lse.cpu().numpy(), ref_lse, rtol=2e-2 if dtype == "bf16" else 2e-6, atol=1e-5,
+                                       err_msg=tag)
     # the planted half really is (nearly always) one-hot on (r, 0, 0), the other half is not
     assert np.median(np.abs(ref_phi[:, : D - r, :, : W // 2, :, 0] - r)) < 1e-9
     assert np.median(np.abs(ref_phi[:, :, :, W // 2 + r:, :, 0] - r)) > 0.1

@@ -78,9 +78,14 @@ def test_bwd_rejects_bad_arguments(lib):
     assert bwd(lib, dK=ODD) == E_ALIGN and bwd(lib, ws=ODD, wsb=1 << 20) == E_ALIGN
     need = lib.modet_bwd_workspace_bytes(1, 4, 4, 4, 8, 1, 3, 0, 0)
     assert need == 64 * 16
-    assert lib.modet_bwd_workspace_bytes(1, 4, 4, 4, 8, 1, 3, 0, 1) == 0
+    assert lib.modet_bwd_workspace_bytes(1, 4, 4, 4, 8, 1, 3, 0, 1) == 0          # flag 1: phi and lse passed in
     assert lib.modet_bwd_workspace_bytes(1, 4, 4, 4, 8, 3, 3, 0, 0) == 0          # invalid shape
     assert bwd(lib) == E_WS and bwd(lib, ws=P, wsb=need - 1) == E_WS
+    # flag 2: the bias gradient is wanted -- 27 fp64 sums (216 bytes, rounded up to 16)
+    assert lib.modet_bwd_workspace_bytes(1, 4, 4, 4, 8, 1, 3, 0, 3) == 224
+    assert lib.modet_bwd_workspace_bytes(1, 4, 4, 4, 8, 1, 3, 0, 2) == need + 224
+    assert bwd(lib, phi=P, lse=P, db=P) == E_WS and bwd(lib, phi=P, lse=P, db=P, ws=P, wsb=223) == E_WS
+    assert bwd(lib, db=P, ws=P, wsb=need + 223) == E_WS
 
 
 def test_warp_rejects_bad_arguments(lib):
