@@ -54,6 +54,7 @@ struct TiledParams {
   float* phi; float* lse;                                         // forward outputs
   float* out;                                                     // dQ or dK
   int B, D, H, Wh;          // Wh = W * heads fused columns
+  int ch;                   // channels per fused column in memory (8, or 6: see Mem)
   int ZC, ntx, nty, nzc;    // planes per chunk; tiles along Wh, H; chunks along D
   float qscale;             // scale * log2(e)
   float scale;
@@ -69,7 +70,7 @@ __device__ __forceinline__ unsigned xcd_remap(unsigned id, unsigned n) {
 struct Tile {
   int b, z0, z1, y0, xs0, tx, ty, xs, y;
   bool lane_ok;
-  long long plane_elems;   // H * Wh * 8
+  long long plane_elems;   // H * Wh * channels per column
   long long col;           // window index of (b, z=0, y, xs): + z*H*Wh
 };
 
@@ -85,7 +86,7 @@ __device__ __forceinline__ Tile make_tile(const TiledParams& p, unsigned id, int
   t.z0 = zc * p.ZC; t.z1 = min(p.D, t.z0 + p.ZC);
   t.xs = t.xs0 + t.tx; t.y = t.y0 + t.ty;
   t.lane_ok = t.xs < p.Wh && t.y < p.H;
-  t.plane_elems = (long long)p.H * p.Wh * 8;
+  t.plane_elems = (long long)p.H * p.Wh * p.ch;
   t.col = (long long)t.b * p.D * p.H * p.Wh + (long long)t.y * p.Wh + t.xs;
   return t;
 }
@@ -128,9 +129,10 @@ template <> struct Lds<double> {
   }
 };
 
-template <class T> struct Ld;
+template <class E> struct Ld;
 template <> struct Ld<float> {
   static __device__ __forceinline__ float4 vec4(const float* p) { return *reinterpret_cast<const float4*>(p); }
+  static __device__ __forceinline__ float2 vec2(const float* p) { return *reinterpret_cast<const float2*>(p); }
   static __device__ __forceinline__ float one(const float* p) { return *p; }
 };
 template <> struct Ld<bf16_t> {
@@ -139,8 +141,22 @@ template <> struct Ld<bf16_t> {
     return make_float4(__uint_as_float(t.x << 16), __uint_as_float(t.x & 0xFFFF0000u),
                        __uint_as_float(t.y << 16), __uint_as_float(t.y & 0xFFFF0000u));
   }
+  static __device__ __forceinline__ float2 vec2(const bf16_t* p) {
+    const uint32_t t = *reinterpret_cast<const uint32_t*>(p);
+    return make_float2(__uint_as_float(t << 16), __uint_as_float(t & 0xFFFF0000u));
+  }
   static __device__ __forceinline__ float one(const bf16_t* p) { return __uint_as_float(((uint32_t)*p) << 16); }
 };
+
+// The input type T of a kernel names the element type AND the number of channels of a head in memory.  Heads
+// of six channels (the paper's small model, Section 4.2) are padded to eight in registers and in LDS: only
+// the loads from and the stores to global memory know about it, the two extra channels are zeros that take
+// part in the arithmetic.
+struct f32x6_t;
+struct bf16x6_t;
+template <class T> struct Mem { typedef T E; static constexpr int CH = 8; };
+template <> struct Mem<f32x6_t> { typedef float E; static constexpr int CH = 6; };
+template <> struct Mem<bf16x6_t> { typedef bf16_t E; static constexpr int CH = 6; };
 
 // stages one haloed plane of an [.., H, Wh, 8] tensor: global -> registers (fetch), registers -> LDS (commit).
 // The loads are unconditional (slots outside the volume read a clamped, valid address and are zeroed when
@@ -149,6 +165,8 @@ template <> struct Ld<bf16_t> {
 template <int KW, int HS, class T, class ET>
 struct Stager {
   typedef Patch<KW, HS> P;
+  typedef typename Mem<T>::E E;
+  static constexpr int CH = Mem<T>::CH;
   int goff[P::NL];      // element offset inside a plane (clamped into the plane)
   int loff[P::NL];      // (position << 2 | half << 1 | inside-the-volume) inside the patch, or -1 when unused
   float4 v[P::NL];
@@ -164,16 +182,27 @@ struct Stager {
       const bool used = e < P::NV;
       const bool in = used && gy >= 0 && gy < H && gx >= 0 && gx < Wh;
       const int cy = min(max(gy, 0), H - 1), cx = min(max(gx, 0), Wh - 1);
-      goff[i] = (cy * Wh + cx) * 8 + hv * 4;
+      goff[i] = (cy * Wh + cx) * CH + hv * 4;
       loff[i] = used ? (pos << 2 | hv << 1 | (in ? 1 : 0)) : -1;
     }
     plane_ok = false;
   }
   // `plane` must point at a plane inside the tensor; ok = false: the wanted plane lies outside the volume
   // (zero padding) and the loaded values are discarded
-  __device__ __forceinline__ void fetch(const T* plane, bool ok) {
+  __device__ __forceinline__ void fetch(const E* plane, bool ok) {
 #pragma unroll
-    for (int i = 0; i < P::NL; ++i) v[i] = Ld<T>::vec4(plane + goff[i]);
+    for (int i = 0; i < P::NL; ++i) {
+      if constexpr (CH == 8) {
+        v[i] = Ld<E>::vec4(plane + goff[i]);
+      } else {
+        // six channels: the first half of a column is channels 0..3, the second channels 4, 5 and two zeros
+        // (the second load of a second half re-reads the same address: always valid, then discarded)
+        const bool second = (loff[i] >> 1) & 1;
+        const float2 a = Ld<E>::vec2(plane + goff[i]);
+        const float2 b = Ld<E>::vec2(plane + goff[i] + (second ? 0 : 2));
+        v[i] = make_float4(a.x, a.y, second ? 0.f : b.x, second ? 0.f : b.y);
+      }
+    }
     plane_ok = ok;
   }
   // Patch slots outside the volume (in H, W) never change: they are zeroed once per LDS buffer, and commit
@@ -273,9 +302,15 @@ __device__ __forceinline__ void pin(float (&x)[8]) {
 
 // unconditional (see Stager): p must be a valid address; the caller discards the values where they are not wanted
 template <class T>
-__device__ __forceinline__ void load8(const T* p, float (&q)[8]) {
-  const float4 a = Ld<T>::vec4(p), b = Ld<T>::vec4(p + 4);
-  q[0] = a.x; q[1] = a.y; q[2] = a.z; q[3] = a.w; q[4] = b.x; q[5] = b.y; q[6] = b.z; q[7] = b.w;
+__device__ __forceinline__ void load8(const typename Mem<T>::E* p, float (&q)[8]) {
+  typedef typename Mem<T>::E E;
+  if constexpr (Mem<T>::CH == 8) {
+    const float4 a = Ld<E>::vec4(p), b = Ld<E>::vec4(p + 4);
+    q[0] = a.x; q[1] = a.y; q[2] = a.z; q[3] = a.w; q[4] = b.x; q[5] = b.y; q[6] = b.z; q[7] = b.w;
+  } else {
+    const float2 a = Ld<E>::vec2(p), b = Ld<E>::vec2(p + 2), c = Ld<E>::vec2(p + 4);
+    q[0] = a.x; q[1] = a.y; q[2] = b.x; q[3] = b.y; q[4] = c.x; q[5] = c.y; q[6] = 0.f; q[7] = 0.f;
+  }
 }
 
 // sum_c q[c] * v[c] (+ init), accumulated in LT
@@ -305,9 +340,17 @@ __device__ __forceinline__ void widen8(const ET (&v)[8], LT (&w)[8]) {
   for (int c = 0; c < 8; ++c) w[c] = (LT)v[c];
 }
 
-__device__ __forceinline__ void store8_scaled(float* o, const float (&acc)[8], float sc) {
-  *reinterpret_cast<float4*>(o) = make_float4(acc[0] * sc, acc[1] * sc, acc[2] * sc, acc[3] * sc);
-  *reinterpret_cast<float4*>(o + 4) = make_float4(acc[4] * sc, acc[5] * sc, acc[6] * sc, acc[7] * sc);
+// column w of a [.., CH] fp32 gradient tensor
+template <int CH>
+__device__ __forceinline__ void store_col_scaled(float* out, long long w, const float (&acc)[8], float sc) {
+  float* o = out + w * CH;
+  if constexpr (CH == 8) {
+    *reinterpret_cast<float4*>(o) = make_float4(acc[0] * sc, acc[1] * sc, acc[2] * sc, acc[3] * sc);
+    *reinterpret_cast<float4*>(o + 4) = make_float4(acc[4] * sc, acc[5] * sc, acc[6] * sc, acc[7] * sc);
+  } else {
+#pragma unroll
+    for (int c = 0; c < CH; c += 2) *reinterpret_cast<float2*>(o + c) = make_float2(acc[c] * sc, acc[c + 1] * sc);
+  }
 }
 
 // The bias B[s, o] of Eq. 3 lives in LDS as bt[o * HS + s], in the units and type of the logits (times log2 e).
@@ -357,7 +400,9 @@ __device__ void fwd_query_two_pass(const TiledParams& p, long long w) {
   const int xs = (int)(r % p.Wh); r /= p.Wh;
   const int y = (int)(r % p.H); r /= p.H;
   const int z = (int)(r % p.D);
-  const T* Qp = (const T*)p.Q + w * 8;     // re-read per offset: this path is rare, keep it small in registers
+  typedef typename Mem<T>::E E;
+  constexpr int CH = Mem<T>::CH;
+  const E* Qp = (const E*)p.Q + w * CH;    // re-read per offset: this path is rare, keep it small in registers
   double mx = -INFINITY, Z = 0.0, S0 = 0.0, S1 = 0.0, S2 = 0.0;
 #pragma unroll 1
   for (int pass = 0; pass < 2; ++pass)
@@ -367,9 +412,9 @@ __device__ void fwd_query_two_pass(const TiledParams& p, long long w) {
       const int zz = z + a, yy = y + bb, xx = xs + cc * HS;
       double l = 0.0;      // a neighbour outside the volume is a zero key
       if (zz >= 0 && zz < p.D && yy >= 0 && yy < p.H && xx >= 0 && xx < p.Wh) {
-        const T* Kp = (const T*)p.K + (w + ((long long)a * p.H + bb) * p.Wh + cc * HS) * 8;
+        const E* Kp = (const E*)p.K + (w + ((long long)a * p.H + bb) * p.Wh + cc * HS) * CH;
 #pragma unroll 1
-        for (int c = 0; c < 8; ++c) l = fma((double)Ld<T>::one(Qp + c), (double)Ld<T>::one(Kp + c), l);
+        for (int c = 0; c < CH; ++c) l = fma((double)Ld<E>::one(Qp + c), (double)Ld<E>::one(Kp + c), l);
         l *= (double)p.qscale;
       }
       if (p.bias) l += (double)p.bias[(xs % HS) * (KW * KW * KW) + j] * (double)kLog2e;
@@ -390,6 +435,7 @@ struct FwdPolicy {
   static constexpr int KW = KW_, HS = HS_, R = KW_ / 2;
   static constexpr bool kBias = BIAS;
   typedef T_ T;
+  typedef typename Mem<T_>::E E;
   typedef LT Logit;
   typedef LT ET;                           // LDS element type: no conversions in the inner loop
   typedef Patch<KW, HS> P;
@@ -402,15 +448,15 @@ struct FwdPolicy {
   struct Pre { float q[8]; };
   static __device__ __forceinline__ void arrived(Pre& a) { pin(a.q); }
 
-  static __device__ __forceinline__ const T* lds_operand(const TiledParams& p) { return (const T*)p.K; }
-  static __device__ __forceinline__ const T* own_operand(const TiledParams& p) { return (const T*)p.Q; }
+  static __device__ __forceinline__ const E* lds_operand(const TiledParams& p) { return (const E*)p.K; }
+  static __device__ __forceinline__ const E* own_operand(const TiledParams& p) { return (const E*)p.Q; }
 
   static __device__ __forceinline__ void reset(State& s) {
 #pragma unroll
     for (int c = 0; c < 8; ++c) s.q[c] = (LT)0;
     s.nref = (LT)0; s.Z = (LT)0; s.S0 = (LT)0; s.S1 = (LT)0; s.S2 = (LT)0;
   }
-  static __device__ __forceinline__ void prefetch(const TiledParams&, const T* own, long long, Pre& pre) {
+  static __device__ __forceinline__ void prefetch(const TiledParams&, const E* own, long long, Pre& pre) {
     load8<T>(own, pre.q);
   }
   static __device__ __forceinline__ void refill(State& s, const Pre& pre, const TiledParams& p) {
@@ -501,6 +547,7 @@ struct DqPolicy {
   static constexpr int KW = KW_, HS = HS_, R = KW_ / 2;
   static constexpr bool kBias = BIAS;
   typedef T_ T;
+  typedef typename Mem<T_>::E E;
   typedef LT Logit;
   typedef float ET;                        // the fp32 copy is needed for the fp32 accumulation anyway
   typedef Patch<KW, HS> P;
@@ -517,15 +564,15 @@ struct DqPolicy {
     pin(a.lse); pin(a.g0); pin(a.g1); pin(a.g2); pin(a.f0); pin(a.f1); pin(a.f2);
   }
 
-  static __device__ __forceinline__ const T* lds_operand(const TiledParams& p) { return (const T*)p.K; }
-  static __device__ __forceinline__ const T* own_operand(const TiledParams& p) { return (const T*)p.Q; }
+  static __device__ __forceinline__ const E* lds_operand(const TiledParams& p) { return (const E*)p.K; }
+  static __device__ __forceinline__ const E* own_operand(const TiledParams& p) { return (const E*)p.Q; }
 
   static __device__ __forceinline__ void reset(State& s) {
 #pragma unroll
     for (int c = 0; c < 8; ++c) { s.q[c] = (LT)0; s.acc[c] = 0.f; }
     s.nlse = (LT)0; s.g0 = s.g1 = s.g2 = s.ngphi = 0.f;
   }
-  static __device__ __forceinline__ void prefetch(const TiledParams& p, const T* own, long long w, Pre& a) {
+  static __device__ __forceinline__ void prefetch(const TiledParams& p, const E* own, long long w, Pre& a) {
     load8<T>(own, a.q);
     a.lse = p.lse_in[w];
     const float* g = p.dphi + w * 3;
@@ -615,7 +662,7 @@ struct DqPolicy {
       }
   }
   static __device__ __forceinline__ void store(const State& s, const TiledParams& p, long long w) {
-    store8_scaled(p.out + w * 8, s.acc, p.scale);
+    store_col_scaled<Mem<T>::CH>(p.out, w, s.acc, p.scale);
   }
 };
 
@@ -627,6 +674,7 @@ struct DkPolicy {
   static constexpr int KW = KW_, HS = HS_, R = KW_ / 2;
   static constexpr bool kBias = BIAS;
   typedef T_ T;
+  typedef typename Mem<T_>::E E;
   typedef LT Logit;
   typedef float ET;
   typedef Patch<KW, HS> P;
@@ -638,14 +686,14 @@ struct DkPolicy {
   struct Pre { float k[8]; };
   static __device__ __forceinline__ void arrived(Pre& a) { pin(a.k); }
 
-  static __device__ __forceinline__ const T* lds_operand(const TiledParams& p) { return (const T*)p.Q; }
-  static __device__ __forceinline__ const T* own_operand(const TiledParams& p) { return (const T*)p.K; }
+  static __device__ __forceinline__ const E* lds_operand(const TiledParams& p) { return (const E*)p.Q; }
+  static __device__ __forceinline__ const E* own_operand(const TiledParams& p) { return (const E*)p.K; }
 
   static __device__ __forceinline__ void reset(State& s) {
 #pragma unroll
     for (int c = 0; c < 8; ++c) { s.k[c] = (LT)0; s.acc[c] = 0.f; }
   }
-  static __device__ __forceinline__ void prefetch(const TiledParams&, const T* own, long long, Pre& pre) {
+  static __device__ __forceinline__ void prefetch(const TiledParams&, const E* own, long long, Pre& pre) {
     load8<T>(own, pre.k);
   }
   static __device__ __forceinline__ void refill(State& s, const Pre& pre, const TiledParams& p) {
@@ -689,7 +737,7 @@ struct DkPolicy {
       }
   }
   static __device__ __forceinline__ void store(const State& s, const TiledParams& p, long long w) {
-    store8_scaled(p.out + w * 8, s.acc, p.scale);
+    store_col_scaled<Mem<T>::CH>(p.out, w, s.acc, p.scale);
   }
 };
 
@@ -751,6 +799,7 @@ template <class Pol>
 __device__ __forceinline__ void march(const TiledParams& p, unsigned id, void* smem) {
   typedef typename Pol::P P;
   typedef typename Pol::T T;
+  typedef typename Pol::E E;
   constexpr int KW = Pol::KW, HS = Pol::HS, R = KW / 2;
 #ifdef MODET_NOROT
   constexpr bool ROT = false;
@@ -760,10 +809,11 @@ __device__ __forceinline__ void march(const TiledParams& p, unsigned id, void* s
   SharedPlanes<Pol, Pol::kStats>& sh = *reinterpret_cast<SharedPlanes<Pol, Pol::kStats>*>(smem);
 
   const Tile t = make_tile(p, id);
-  const T* Lb = Pol::lds_operand(p) + (long long)t.b * p.D * t.plane_elems;
+  const E* Lb = Pol::lds_operand(p) + (long long)t.b * p.D * t.plane_elems;
   // lanes outside the volume compute on a clamped (valid) column and never store
   const int cy = min(t.y, p.H - 1), cxs = min(t.xs, p.Wh - 1);
-  const T* Ob = Pol::own_operand(p) + (long long)t.b * p.D * t.plane_elems + ((long long)cy * p.Wh + cxs) * 8;
+  const E* Ob = Pol::own_operand(p) + (long long)t.b * p.D * t.plane_elems +
+                ((long long)cy * p.Wh + cxs) * Mem<T>::CH;
   const long long ccol = (long long)t.b * p.D * p.H * p.Wh + (long long)cy * p.Wh + cxs;
   const long long pw = (long long)p.H * p.Wh;
   const long long wb = (long long)t.b * p.D * pw;    // window index of (b, 0, 0, 0)
@@ -913,9 +963,10 @@ template <class Pol, bool IS_DK, class Rings>
 __device__ __forceinline__ void shared_march(const TiledParams& p, const Tile& t, Rings& sh, int tid) {
   typedef typename Pol::P P;
   typedef typename Pol::T T;
+  typedef typename Pol::E E;
   constexpr int KW = Pol::KW, HS = Pol::HS, R = KW / 2, RING = Rings::RING;
   static_assert(KW == 3, "phase rotation below is written for k = 3");
-  const T* Lb = Pol::lds_operand(p) + (long long)t.b * p.D * t.plane_elems;
+  const E* Lb = Pol::lds_operand(p) + (long long)t.b * p.D * t.plane_elems;
   const long long pw = (long long)p.H * p.Wh;
   const long long wb = (long long)t.b * p.D * pw;
   const int lbase = t.ty * P::PC + t.tx;
@@ -1051,7 +1102,8 @@ struct FusedBwd {
 template <class T, class LT, int HS, bool BIAS, int PH>
 __device__ __forceinline__ void fused_query_step(typename DqPolicy<3, HS, T, LT, BIAS>::State (&st)[3],
                                                  typename DqPolicy<3, HS, T, LT, BIAS>::Pre& pre, const TiledParams& p,
-                                                 const Tile& t, const T* Ob, long long ccol, const float4* kcur,
+                                                 const Tile& t, const typename Mem<T>::E* Ob, long long ccol,
+                                                 const float4* kcur,
                                                  float* dl, int lbase, int tid, int s, bool fill_new, unsigned active,
                                                  bool store_old, long long w_old, const LT* bl) {
   typedef DqPolicy<3, HS, T, LT, BIAS> Dq;
@@ -1083,7 +1135,8 @@ __device__ __forceinline__ void fused_query_half(TiledParams p, const Tile& t,
   constexpr int KW = 3, R = 1;
   const int cy = min(t.y, p.H - 1), cxs = min(t.xs, p.Wh - 1);
   const long long pw = (long long)p.H * p.Wh;
-  const T* Ob = (const T*)p.Q + (long long)t.b * p.D * t.plane_elems + ((long long)cy * p.Wh + cxs) * 8;
+  typedef typename Mem<T>::E E;
+  const E* Ob = (const E*)p.Q + (long long)t.b * p.D * t.plane_elems + ((long long)cy * p.Wh + cxs) * Mem<T>::CH;
   const long long ccol = (long long)t.b * p.D * pw + (long long)cy * p.Wh + cxs;
   const int lbase = t.ty * P::PC + t.tx;
   const int s_lo = t.z0 - 1, s_hi = t.z1;
@@ -1153,8 +1206,9 @@ __device__ __forceinline__ void fused_key_half(TiledParams p, const Tile& t,
   constexpr int NRQ = 3 * NRP, RPL = (NRQ + NT - 1) / NT;      // ring queries per step; per lane (1 or 2)
   const long long pw = (long long)p.H * p.Wh;
   const long long wb = (long long)t.b * p.D * pw;
-  const T* Kb = (const T*)p.K + (long long)t.b * p.D * t.plane_elems;
-  const T* Qb = (const T*)p.Q + (long long)t.b * p.D * t.plane_elems;
+  typedef typename Mem<T>::E E;
+  const E* Kb = (const E*)p.K + (long long)t.b * p.D * t.plane_elems;
+  const E* Qb = (const E*)p.Q + (long long)t.b * p.D * t.plane_elems;
   const int s_lo = t.z0 - 1, s_hi = t.z1;
 
   // ---- staging: K and Q planes (whole haloed patch), statistics of the ring queries (lanes < NRP)
@@ -1308,7 +1362,7 @@ __device__ __forceinline__ void fused_key_half(TiledParams p, const Tile& t,
     stk.commit(sh.k[kslot]);
     commit_q(qslot(3));
     // (the store after the commit: the commit's wait for its loads must not cover it)
-    if (key_plane && t.lane_ok) store8_scaled(p.out + (t.col + (long long)s * pw) * 8, acc, p.scale);
+    if (key_plane && t.lane_ok) store_col_scaled<Mem<T>::CH>(p.out, t.col + (long long)s * pw, acc, p.scale);
     fetch_k(s + 3);
     fetch_q(s + 4);
     qs = qs + 1 == QR ? 0 : qs + 1;
@@ -1404,6 +1458,7 @@ TiledParams make_params(const Geo& g, int wgs_per_cu, int wgs_per_tile = 1) {
   p.nzc = (g.D + zc - 1) / zc;
   p.scale = g.scale;
   p.qscale = g.scale * kLog2e;
+  p.ch = g.d;
   return p;
 }
 
@@ -1466,4 +1521,16 @@ void launch_march(const Geo& g, TiledParams io, hipStream_t st) {
       case 2: return CALL(5, 2, bf16_t, float);                                  \
     }                                                                            \
   }                                                                              \
+  return hipErrorNotSupported;
+
+// the same for heads of six channels (k = 3; fp64 logits for fp32 inputs whatever the math mode)
+#define MODET_DISPATCH_D6(CALL)                                                               \
+  if (g.k == 3) {                                                                             \
+    switch (g.heads) {                                                                        \
+      case 1: return dtype == 0 ? CALL(3, 1, f32x6_t, double) : CALL(3, 1, bf16x6_t, float);  \
+      case 2: return dtype == 0 ? CALL(3, 2, f32x6_t, double) : CALL(3, 2, bf16x6_t, float);  \
+      case 4: return dtype == 0 ? CALL(3, 4, f32x6_t, double) : CALL(3, 4, bf16x6_t, float);  \
+      case 8: return dtype == 0 ? CALL(3, 8, f32x6_t, double) : CALL(3, 8, bf16x6_t, float);  \
+    }                                                                                         \
+  }                                                                                           \
   return hipErrorNotSupported;

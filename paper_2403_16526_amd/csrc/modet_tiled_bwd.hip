@@ -1,6 +1,6 @@
 // Backward entry of the LDS-tiled kernels (derivatives of Eq. 3-4 with respect to Q and K): the kernels
 // without bias, and the choice between the two variants.
-#define MODET_BWD_BIAS 0
+#define MODET_BWD_VARIANT 0
 #include "modet_tiled_bwd.inc"
 
 namespace modet {
@@ -12,6 +12,7 @@ bool tiled_bwd_supported(int d, int heads, int k, int dtype) { return tiled_fwd_
 hipError_t launch_bwd_tiled(const Geo& g, int dtype, bool fast_logits, const BwdTensors& io, hipStream_t st,
                             bool* dbias_done) {
   *dbias_done = false;
+  if (g.d == 6) return launch_bwd_tiled_d6(g, dtype, io, st, dbias_done);
   if (io.bias || io.dbias_acc) return launch_bwd_tiled_biased(g, dtype, fast_logits, io, st, dbias_done);
   return launch_bwd_tiled_plain(g, dtype, fast_logits, io, st, dbias_done);
 }

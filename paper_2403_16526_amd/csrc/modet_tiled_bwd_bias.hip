@@ -1,3 +1,3 @@
 // Backward of the LDS-tiled kernels with the bias B of Eq. 3 in the logits (and its gradient).
-#define MODET_BWD_BIAS 1
+#define MODET_BWD_VARIANT 1
 #include "modet_tiled_bwd.inc"

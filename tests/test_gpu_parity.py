@@ -39,6 +39,12 @@ SMALL = [
     (1, 57, 17, 65, 8, 1, 3, "f32"),        # several chunks along D with ragged tiles: chunk seams of the marches
     (2, 20, 9, 33, 8, 1, 3, "bf16"),
     (1, 41, 12, 40, 16, 2, 3, "f32"),       # the same for the several-heads backward
+    # six channels per head on the tiled kernels: ragged tiles and chunk seams, 1 / 2 / 4 / 8 heads, both dtypes
+    (1, 45, 13, 67, 6, 1, 3, "f32"),
+    (2, 11, 9, 35, 12, 2, 3, "bf16"),
+    (1, 9, 10, 33, 24, 4, 3, "f32"),
+    (1, 6, 9, 17, 48, 8, 3, "bf16"),
+    (1, 37, 8, 40, 12, 2, 3, "f32"),
 ]
 
 
@@ -85,8 +91,10 @@ def test_small_cases_match_oracle(modet, shape, path):
     run_case(modet, shape, path)
 
 
-# with bias: one / two heads (k = 3) with chunk seams, four and eight heads, k = 5, 6 channels per head, both dtypes
-BIASED = [SMALL[1], SMALL[3], SMALL[4], SMALL[6], SMALL[8], SMALL[12], SMALL[16], SMALL[17], SMALL[18]]
+# with bias: one / two heads (k = 3) with chunk seams, four and eight heads, k = 5, 6 and 12 channels per head,
+# both dtypes
+BIASED = [SMALL[1], SMALL[3], SMALL[4], SMALL[6], SMALL[8], SMALL[12], SMALL[13], SMALL[16], SMALL[17], SMALL[18],
+          SMALL[19], SMALL[20], SMALL[21], SMALL[22], SMALL[23]]
 
 
 @pytest.mark.parametrize("shape", BIASED, ids=lambda s: "x".join(map(str, s)))
