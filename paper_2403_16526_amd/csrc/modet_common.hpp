@@ -66,5 +66,9 @@ hipError_t launch_bwd_tiled_biased(const Geo& g, int dtype, bool fast_logits, co
 hipError_t launch_fwd_tiled_d6(const Geo& g, int dtype, const void* Q, const void* K, const float* bias,
                                float* phi, float* lse, hipStream_t st);
 hipError_t launch_bwd_tiled_d6(const Geo& g, int dtype, const BwdTensors& io, hipStream_t st, bool* dbias_done);
+// heads of twelve channels
+hipError_t launch_fwd_tiled_d12(const Geo& g, int dtype, const void* Q, const void* K, const float* bias,
+                                float* phi, float* lse, hipStream_t st);
+hipError_t launch_bwd_tiled_d12(const Geo& g, int dtype, const BwdTensors& io, hipStream_t st, bool* dbias_done);
 
 }  // namespace modet

@@ -152,11 +152,42 @@ template <> struct Ld<bf16_t> {
 // of six channels (the paper's small model, Section 4.2) are padded to eight in registers and in LDS: only
 // the loads from and the stores to global memory know about it, the two extra channels are zeros that take
 // part in the arithmetic.
+//
+// Heads of twelve channels (the paper's large model) are two six-channel HALF-HEADS in neighbouring fused
+// columns, hence in neighbouring lanes (even lane = channels 0..5): Wh = 2 * W * heads columns, the W-neighbour
+// of a column is 2 * heads columns away (that is the kernels' HS).  Each lane forms the dot product of its half
+// and adds its partner's (one cross-lane move); from there on both lanes of a pair compute the same numbers
+// and each keeps the gradient of its own six channels.  What is indexed by window (phi, lse, dphi, the bias's
+// head) uses the column index shifted right by SH = 1.
 struct f32x6_t;
 struct bf16x6_t;
-template <class T> struct Mem { typedef T E; static constexpr int CH = 8; };
-template <> struct Mem<f32x6_t> { typedef float E; static constexpr int CH = 6; };
-template <> struct Mem<bf16x6_t> { typedef bf16_t E; static constexpr int CH = 6; };
+struct f32x12_t;
+struct bf16x12_t;
+template <class T> struct Mem { typedef T E; static constexpr int CH = 8; static constexpr bool PAIR = false; };
+template <> struct Mem<f32x6_t> { typedef float E; static constexpr int CH = 6; static constexpr bool PAIR = false; };
+template <> struct Mem<bf16x6_t> { typedef bf16_t E; static constexpr int CH = 6; static constexpr bool PAIR = false; };
+template <> struct Mem<f32x12_t> { typedef float E; static constexpr int CH = 6; static constexpr bool PAIR = true; };
+template <> struct Mem<bf16x12_t> { typedef bf16_t E; static constexpr int CH = 6; static constexpr bool PAIR = true; };
+template <class T> struct Win {       // column index -> window index, and the share of a logit's additive terms
+  static constexpr int SH = Mem<T>::PAIR ? 1 : 0;                 // (reference, lse, bias) a lane's partial sum
+  static constexpr float kShare = Mem<T>::PAIR ? 0.5f : 1.0f;     // starts from: the two halves add up to the whole
+};
+
+// the value the other lane of a pair (lane ^ 1) holds; all lanes of the wave execute it together
+__device__ __forceinline__ float partner(float x) {
+  return __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(x), 0xB1, 0xF, 0xF, true));   // quad_perm [1,0,3,2]
+}
+__device__ __forceinline__ double partner(double x) {
+  const int lo = __builtin_amdgcn_mov_dpp(__double2loint(x), 0xB1, 0xF, 0xF, true);
+  const int hi = __builtin_amdgcn_mov_dpp(__double2hiint(x), 0xB1, 0xF, 0xF, true);
+  return __hiloint2double(hi, lo);
+}
+// a logit from this lane's partial sum
+template <class T, class LT>
+__device__ __forceinline__ LT whole_logit(LT part) {
+  if constexpr (Mem<T>::PAIR) return part + partner(part);
+  else return part;
+}
 
 // stages one haloed plane of an [.., H, Wh, 8] tensor: global -> registers (fetch), registers -> LDS (commit).
 // The loads are unconditional (slots outside the volume read a clamped, valid address and are zeroed when
@@ -237,8 +268,12 @@ struct StatStager {
   int loff[P::NS];   // (position << 1 | inside-the-volume), or -1
   float lse[P::NS], g[P::NS][3], f[P::NS][3];
   bool plane_ok;
+  int sh;            // column index -> window index (1 for half-head columns)
+  float nshare;      // -log2(e) * the share of lse a lane's partial logit starts from
 
-  __device__ __forceinline__ void init(int tid, int y0, int xs0, int H, int Wh) {
+  __device__ __forceinline__ void init(int tid, int y0, int xs0, int H, int Wh, int sh_ = 0) {
+    sh = sh_;
+    nshare = sh_ ? -0.5f * kLog2e : -kLog2e;
 #pragma unroll
     for (int i = 0; i < P::NS; ++i) {
       const int pos = tid + i * NT;
@@ -256,7 +291,7 @@ struct StatStager {
   __device__ __forceinline__ void fetch(const TiledParams& p, long long base, bool ok) {
 #pragma unroll
     for (int i = 0; i < P::NS; ++i) {
-      const long long w = base + goff[i];
+      const long long w = (base + goff[i]) >> sh;
       const float* gp = p.dphi + w * 3;
       const float* fp = p.phi_in + w * 3;
       lse[i] = p.lse_in[w];
@@ -278,7 +313,7 @@ struct StatStager {
 #pragma unroll
       for (int i = 0; i < P::NS; ++i)
         if (loff[i] >= 0 && (loff[i] & 1)) {
-          sa[loff[i] >> 1] = make_float4(-lse[i] * kLog2e, g[i][0], g[i][1], g[i][2]);
+          sa[loff[i] >> 1] = make_float4(lse[i] * nshare, g[i][0], g[i][1], g[i][2]);
           sc[loff[i] >> 1] = -(g[i][0] * f[i][0] + g[i][1] * f[i][1] + g[i][2] * f[i][2]);
         }
     } else {
@@ -356,12 +391,12 @@ __device__ __forceinline__ void store_col_scaled(float* out, long long w, const 
 // The bias B[s, o] of Eq. 3 lives in LDS as bt[o * HS + s], in the units and type of the logits (times log2 e).
 // A lane's head is its fused column modulo HS, so it reads through bt + head at the compile-time offset o * HS,
 // o = ((a+R)*KW + b+R)*KW + c+R.  A NULL bias is all zeros (its gradient may still be wanted).
-template <class LT, int KW, int HS>
+template <class T, class LT, int KW, int HS>
 __device__ __forceinline__ void fill_bias_table(LT* bt, const float* bias, int tid, int nthreads) {
   constexpr int K3 = KW * KW * KW;
   for (int i = tid; i < K3 * HS; i += nthreads) {
-    const int j = i / HS, h = i - j * HS;
-    bt[i] = bias ? (LT)bias[h * K3 + j] * (LT)kLog2e : (LT)0;
+    const int j = i / HS, h = (i - j * HS) >> Win<T>::SH;
+    bt[i] = bias ? (LT)bias[h * K3 + j] * (LT)kLog2e * (LT)Win<T>::kShare : (LT)0;
   }
 }
 template <class LT, int KW, int HS, bool BIAS> struct BiasTable { LT v[KW * KW * KW * HS]; };
@@ -401,7 +436,8 @@ __device__ void fwd_query_two_pass(const TiledParams& p, long long w) {
   const int y = (int)(r % p.H); r /= p.H;
   const int z = (int)(r % p.D);
   typedef typename Mem<T>::E E;
-  constexpr int CH = Mem<T>::CH;
+  constexpr int CH = Mem<T>::CH, SH = Win<T>::SH;
+  constexpr int CHW = CH << SH;            // channels of the whole head (w is the even column of a pair)
   const E* Qp = (const E*)p.Q + w * CH;    // re-read per offset: this path is rare, keep it small in registers
   double mx = -INFINITY, Z = 0.0, S0 = 0.0, S1 = 0.0, S2 = 0.0;
 #pragma unroll 1
@@ -414,10 +450,10 @@ __device__ void fwd_query_two_pass(const TiledParams& p, long long w) {
       if (zz >= 0 && zz < p.D && yy >= 0 && yy < p.H && xx >= 0 && xx < p.Wh) {
         const E* Kp = (const E*)p.K + (w + ((long long)a * p.H + bb) * p.Wh + cc * HS) * CH;
 #pragma unroll 1
-        for (int c = 0; c < CH; ++c) l = fma((double)Ld<E>::one(Qp + c), (double)Ld<E>::one(Kp + c), l);
+        for (int c = 0; c < CHW; ++c) l = fma((double)Ld<E>::one(Qp + c), (double)Ld<E>::one(Kp + c), l);
         l *= (double)p.qscale;
       }
-      if (p.bias) l += (double)p.bias[(xs % HS) * (KW * KW * KW) + j] * (double)kLog2e;
+      if (p.bias) l += (double)p.bias[((xs % HS) >> SH) * (KW * KW * KW) + j] * (double)kLog2e;
       if (pass == 0) {
         mx = fmax(mx, l);
       } else {
@@ -425,9 +461,9 @@ __device__ void fwd_query_two_pass(const TiledParams& p, long long w) {
         Z += e; S0 += a * e; S1 += bb * e; S2 += cc * e;
       }
     }
-  float* ph = p.phi + w * 3;
+  float* ph = p.phi + (w >> SH) * 3;
   ph[0] = (float)(S0 / Z); ph[1] = (float)(S1 / Z); ph[2] = (float)(S2 / Z);
-  if (p.lse) p.lse[w] = (float)((mx + (double)log2_fast((float)Z)) * (double)kLn2);
+  if (p.lse) p.lse[w >> SH] = (float)((mx + (double)log2_fast((float)Z)) * (double)kLn2);
 }
 
 template <int KW_, int HS_, class T_, class LT, bool BIAS = false>
@@ -442,7 +478,7 @@ struct FwdPolicy {
   static constexpr bool kStats = false;
   struct State {
     LT q[8];            // Q * scale * log2e
-    LT nref;            // minus the reference (log2 units); the dot products start from it
+    LT nref;            // minus the reference (log2 units) times Win<T>::kShare; the dot products start from it
     LT Z, S0, S1, S2;   // sum of weights and of weight*offset, relative to the reference.  Kept in LT: phi
   };                    // feeds the backward, where its error is multiplied by the upstream gradient
   struct Pre { float q[8]; };
@@ -473,7 +509,7 @@ struct FwdPolicy {
       float mx = (float)l[0];
 #pragma unroll
       for (int c = 1; c < KW; ++c) mx = fmaxf(mx, (float)l[c]);
-      s.nref = -(LT)mx;
+      s.nref = -(LT)mx * (LT)Win<T>::kShare;
 #pragma unroll
       for (int c = 0; c < KW; ++c) l[c] -= (LT)mx;
     }
@@ -508,7 +544,7 @@ struct FwdPolicy {
             // role i sees this plane under the plane offset a = R - i
             LT init = st[(i + PH) % KW].nref;
             if (BIAS) init += bl[(((KW - 1 - i) * KW + b) * KW + c) * HS];
-            l[i][c] = dot8<LT>(st[(i + PH) % KW].q, kv, init);
+            l[i][c] = whole_logit<T, LT>(dot8<LT>(st[(i + PH) % KW].q, kv, init));
           }
       }
       // role KW-1 is the plane that entered last: this step shows it the first plane of its window
@@ -528,6 +564,7 @@ struct FwdPolicy {
       }
   }
   static __device__ __forceinline__ void store(const State& s, const TiledParams& p, long long w) {
+    if (Mem<T>::PAIR && (w & 1)) return;      // the even lane of a pair stores for both
     const float zf = (float)s.Z;
     if (!(zf >= 1e-30f && zf <= 1e30f)) {     // overflowed, all underflowed, or NaN: this query alone, safely
       fwd_query_two_pass<KW, HS, T>(p, w);
@@ -535,9 +572,10 @@ struct FwdPolicy {
     }
     LT inv = (LT)__builtin_amdgcn_rcpf(zf);
     inv = inv * ((LT)2 - s.Z * inv);          // one Newton step: relative error ~1e-14 in fp64
-    float* ph = p.phi + w * 3;
+    float* ph = p.phi + (w >> Win<T>::SH) * 3;
     ph[0] = (float)(s.S0 * inv); ph[1] = (float)(s.S1 * inv); ph[2] = (float)(s.S2 * inv);
-    if (p.lse) p.lse[w] = (float)(((LT)log2_fast(zf) - s.nref) * (LT)kLn2);
+    if (p.lse)
+      p.lse[w >> Win<T>::SH] = (float)(((LT)log2_fast(zf) - s.nref * (LT)(1.0f / Win<T>::kShare)) * (LT)kLn2);
   }
 };
 
@@ -554,7 +592,7 @@ struct DqPolicy {
   static constexpr bool kStats = false;
   struct State {
     LT q[8];          // Q * scale * log2e
-    LT nlse;          // -lse * log2e
+    LT nlse;          // -lse * log2e * Win<T>::kShare
     float g0, g1, g2, ngphi;
     float acc[8];
   };
@@ -574,15 +612,16 @@ struct DqPolicy {
   }
   static __device__ __forceinline__ void prefetch(const TiledParams& p, const E* own, long long w, Pre& a) {
     load8<T>(own, a.q);
-    a.lse = p.lse_in[w];
-    const float* g = p.dphi + w * 3;
-    const float* f = p.phi_in + w * 3;
+    const long long ww = w >> Win<T>::SH;
+    a.lse = p.lse_in[ww];
+    const float* g = p.dphi + ww * 3;
+    const float* f = p.phi_in + ww * 3;
     a.g0 = g[0]; a.g1 = g[1]; a.g2 = g[2]; a.f0 = f[0]; a.f1 = f[1]; a.f2 = f[2];
   }
   static __device__ __forceinline__ void refill(State& s, const Pre& a, const TiledParams& p) {
 #pragma unroll
     for (int c = 0; c < 8; ++c) { s.q[c] = (LT)a.q[c] * (LT)p.qscale; s.acc[c] = 0.f; }
-    s.nlse = -(LT)a.lse * (LT)kLog2e;
+    s.nlse = -(LT)a.lse * (LT)kLog2e * (LT)Win<T>::kShare;
     s.g0 = a.g0; s.g1 = a.g1; s.g2 = a.g2;
     s.ngphi = -(a.g0 * a.f0 + a.g1 * a.f1 + a.g2 * a.f2);
   }
@@ -616,7 +655,7 @@ struct DqPolicy {
             State& s = st[(i + PH) % KW];
             LT init = s.nlse;
             if (BIAS) init += bl[(((KW - 1 - i) * KW + b) * KW + c) * HS];
-            const float w = exp2_fast((float)dot8<LT>(s.q, kv, init));
+            const float w = exp2_fast((float)whole_logit<T, LT>(dot8<LT>(s.q, kv, init)));
             // t = g.o - g.phi with o = (R - i, b - R, c - R)
             float tt = s.ngphi;
             if (R - i != 0) tt = fmaf((float)(R - i), s.g0, tt);
@@ -647,7 +686,7 @@ struct DqPolicy {
             State& s = st[(i + PH) % KW];
             LT init = s.nlse;
             if (BIAS) init += bl[(((KW - 1 - i) * KW + b) * KW + c) * HS];
-            const float w = exp2_fast((float)dot8<LT>(s.q, kv, init));
+            const float w = exp2_fast((float)whole_logit<T, LT>(dot8<LT>(s.q, kv, init)));
             float tt = s.ngphi;
             if (R - i != 0) tt = fmaf((float)(R - i), s.g0, tt);
             if (b - R != 0) tt = fmaf((float)(b - R), s.g1, tt);
@@ -730,7 +769,7 @@ struct DkPolicy {
             State& s = st[(i + PH) % KW];
             LT init = nlse;
             if (BIAS) init += bl[((i * KW + (KW - 1 - r)) * KW + (KW - 1 - cc)) * HS];
-            const float w = exp2_fast((float)dot8<LT>(s.k, qv, init));
+            const float w = exp2_fast((float)whole_logit<T, LT>(dot8<LT>(s.k, qv, init)));
             const float tt = (i - R != 0) ? fmaf((float)(i - R), a4.y, tb) : tb;
             axpy8(s.acc, w * tt, qf);
           }
@@ -787,12 +826,19 @@ __device__ __forceinline__ void march_body(typename Pol::State (&st)[Pol::KW], c
 }
 
 struct NoStats {
-  __device__ __forceinline__ void init(int, int, int, int, int) {}
+  __device__ __forceinline__ void init(int, int, int, int, int, int = 0) {}
   __device__ __forceinline__ void fetch(const TiledParams&, long long, bool) {}
   __device__ __forceinline__ void zero_outside(float4*, float*) const {}
 };
 
 __device__ __forceinline__ int clampi(int v, int lo, int hi) { return min(max(v, lo), hi); }
+// a valid column for a lane right of the volume; a half-head column keeps its parity, so that the two lanes of
+// a pair still hold the two halves of one head
+template <class T>
+__device__ __forceinline__ int clamp_column(int xs, int Wh) {
+  if (xs < Wh) return xs;
+  return Mem<T>::PAIR ? Wh - 2 + (xs & 1) : Wh - 1;
+}
 
 // One workgroup's march over its chunk.  id: logical tile index (after the XCD remap); smem: the workgroup's LDS.
 template <class Pol>
@@ -811,7 +857,7 @@ __device__ __forceinline__ void march(const TiledParams& p, unsigned id, void* s
   const Tile t = make_tile(p, id);
   const E* Lb = Pol::lds_operand(p) + (long long)t.b * p.D * t.plane_elems;
   // lanes outside the volume compute on a clamped (valid) column and never store
-  const int cy = min(t.y, p.H - 1), cxs = min(t.xs, p.Wh - 1);
+  const int cy = min(t.y, p.H - 1), cxs = clamp_column<T>(t.xs, p.Wh);
   const E* Ob = Pol::own_operand(p) + (long long)t.b * p.D * t.plane_elems +
                 ((long long)cy * p.Wh + cxs) * Mem<T>::CH;
   const long long ccol = (long long)t.b * p.D * p.H * p.Wh + (long long)cy * p.Wh + cxs;
@@ -822,13 +868,13 @@ __device__ __forceinline__ void march(const TiledParams& p, unsigned id, void* s
   Stager<KW, HS, T, typename Pol::ET> stg;
   stg.init(threadIdx.x, t.y0, t.xs0, p.H, p.Wh);
   typename std::conditional<Pol::kStats, StatStager<KW, HS>, NoStats>::type sst;
-  sst.init(threadIdx.x, t.y0, t.xs0, p.H, p.Wh);
+  sst.init(threadIdx.x, t.y0, t.xs0, p.H, p.Wh, Win<T>::SH);
 #pragma unroll
   for (int j = 0; j < 2; ++j) {
     stg.zero_outside(sh.main[j]);
     if constexpr (Pol::kStats) sst.zero_outside(sh.sa[j], sh.sc[j]);
   }
-  if constexpr (Pol::kBias) fill_bias_table<typename Pol::Logit, KW, HS>(sh.bias.v, p.bias, threadIdx.x, NT);
+  if constexpr (Pol::kBias) fill_bias_table<T, typename Pol::Logit, KW, HS>(sh.bias.v, p.bias, threadIdx.x, NT);
 
   typename Pol::State st[KW];
 #pragma unroll
@@ -976,7 +1022,7 @@ __device__ __forceinline__ void shared_march(const TiledParams& p, const Tile& t
   Stager<KW, HS, T, float> stg;
   stg.init(tid, t.y0, t.xs0, p.H, p.Wh);
   typename std::conditional<IS_DK, StatStager<KW, HS>, NoStats>::type sst;
-  sst.init(tid, t.y0, t.xs0, p.H, p.Wh);
+  sst.init(tid, t.y0, t.xs0, p.H, p.Wh, Win<T>::SH);
 #pragma unroll
   for (int j = 0; j < RING; ++j) {
     stg.zero_outside(mine[j]);
@@ -1000,7 +1046,7 @@ __device__ __forceinline__ void shared_march(const TiledParams& p, const Tile& t
 #pragma unroll
   for (int j = 0; j <= R; ++j) { fetch(s_first + j); commit(j); }
   fetch(s_first + R + 1);
-  if constexpr (Pol::kBias && !IS_DK) fill_bias_table<typename Pol::Logit, KW, HS>(sh.bias.v, p.bias, tid, NT);
+  if constexpr (Pol::kBias && !IS_DK) fill_bias_table<T, typename Pol::Logit, KW, HS>(sh.bias.v, p.bias, tid, NT);
   const typename Pol::Logit* bl = lane_bias<Pol>(sh, t.xs);
   __syncthreads();
 
@@ -1133,7 +1179,7 @@ __device__ __forceinline__ void fused_query_half(TiledParams p, const Tile& t,
   typedef typename F::Dq Dq;
   typedef typename F::P P;
   constexpr int KW = 3, R = 1;
-  const int cy = min(t.y, p.H - 1), cxs = min(t.xs, p.Wh - 1);
+  const int cy = min(t.y, p.H - 1), cxs = clamp_column<T>(t.xs, p.Wh);
   const long long pw = (long long)p.H * p.Wh;
   typedef typename Mem<T>::E E;
   const E* Ob = (const E*)p.Q + (long long)t.b * p.D * t.plane_elems + ((long long)cy * p.Wh + cxs) * Mem<T>::CH;
@@ -1161,7 +1207,7 @@ __device__ __forceinline__ void fused_query_half(TiledParams p, const Tile& t,
   prefetch(s_lo + 1);
   Dq::arrived(pre);
   if (!t.lane_ok) { pre.g0 = pre.g1 = pre.g2 = 0.f; pre.f0 = pre.f1 = pre.f2 = 0.f; }
-  if constexpr (BIAS) fill_bias_table<LT, KW, HS>(sh.bias.v, p.bias, tid, NT);
+  if constexpr (BIAS) fill_bias_table<T, LT, KW, HS>(sh.bias.v, p.bias, tid, NT);
   const LT* bl = lane_bias<Dq>(sh, t.xs);
   __syncthreads();          // the key half has staged the first planes
 
@@ -1232,7 +1278,7 @@ __device__ __forceinline__ void fused_key_half(TiledParams p, const Tile& t,
   auto fetch_q = [&](int z) {
     const int zc = clampi(z, 0, p.D - 1);
     stq.fetch(Qb + (long long)zc * t.plane_elems, z >= 0 && z < p.D);
-    const long long w = wb + (long long)zc * pw + ring_w;
+    const long long w = (wb + (long long)zc * pw + ring_w) >> Win<T>::SH;
     r_lse = p.lse_in[w];
     r_g[0] = p.dphi[w * 3]; r_g[1] = p.dphi[w * 3 + 1]; r_g[2] = p.dphi[w * 3 + 2];
     r_f[0] = p.phi_in[w * 3]; r_f[1] = p.phi_in[w * 3 + 1]; r_f[2] = p.phi_in[w * 3 + 2];
@@ -1242,7 +1288,7 @@ __device__ __forceinline__ void fused_key_half(TiledParams p, const Tile& t,
     stq.commit(sh.q[slot]);
     if (tid < NRP) {
       const float g0 = r_ok ? r_g[0] : 0.f, g1 = r_ok ? r_g[1] : 0.f, g2 = r_ok ? r_g[2] : 0.f;
-      sh.sa[slot][tid] = make_float4(r_ok ? -r_lse * kLog2e : 0.f, g0, g1, g2);
+      sh.sa[slot][tid] = make_float4(r_ok ? -r_lse * kLog2e * Win<T>::kShare : 0.f, g0, g1, g2);
       sh.sc[slot][tid] = -(g0 * r_f[0] + g1 * r_f[1] + g2 * r_f[2]);
     }
   };
@@ -1353,6 +1399,7 @@ __device__ __forceinline__ void fused_key_half(TiledParams p, const Tile& t,
           widen8<LT, float>(kf, kv);
           LT l = fma(dot8<LT>(qv, kv), (LT)p.qscale, (LT)a4.x);
           if constexpr (BIAS) l += sh.bias.v[((ra[i] * 3 + b + 1) * 3 + c + 1) * HS + qc_[i] % HS];
+          l = whole_logit<T, LT>(l);      // (ring queries of a pair sit in neighbouring lanes: NRP is even)
           const float tq = fmaf((float)b, a4.z, fmaf((float)c, a4.w, base));
           dln[ra[i] * F::DLA + 9 * NT + rq[i] * 3 + tt] = valid ? exp2_fast((float)l) * tq : 0.f;
         }
@@ -1369,19 +1416,22 @@ __device__ __forceinline__ void fused_key_half(TiledParams p, const Tile& t,
   }
   if constexpr (BIAS) {
     if (p.dbias_acc != nullptr) {      // (uniform) fold the components into heads, the 8 segments into one lane
-      double hsum[HS];
+      // a component's columns have a fixed position in the group of HS columns; of a pair of half-head
+      // columns (which hold the same dl) only the even one counts
+      constexpr int SH = Win<T>::SH, NH = HS >> SH;
+      double hsum[NH];
 #pragma unroll
-      for (int h = 0; h < HS; ++h) {
+      for (int h = 0; h < NH; ++h) {
         double v = 0.0;
 #pragma unroll
-        for (int c = h; c < 4; c += HS) v += db_sum[c];
+        for (int c = h << SH; c < 4; c += HS) v += db_sum[c];
 #pragma unroll
         for (int m = 1; m < 8; m <<= 1) v += __shfl_xor(v, m);
         hsum[h] = v;
       }
       if (db_on && db_seg == 0) {
 #pragma unroll
-        for (int h = 0; h < HS; ++h) atomicAdd(p.dbias_acc + h * 27 + db_row, hsum[h]);
+        for (int h = 0; h < NH; ++h) atomicAdd(p.dbias_acc + h * 27 + db_row, hsum[h]);
       }
     }
   }
@@ -1445,7 +1495,8 @@ int chunk_length(long long tiles, int D, int k, int wgs_per_cu) {
 
 TiledParams make_params(const Geo& g, int wgs_per_cu, int wgs_per_tile = 1) {
   TiledParams p = {};
-  p.B = g.B; p.D = g.D; p.H = g.H; p.Wh = g.W * g.heads;
+  p.B = g.B; p.D = g.D; p.H = g.H;
+  p.Wh = g.W * g.heads * (g.d == 12 ? 2 : 1);      // twelve channels: two half-head columns per head
   p.ntx = (p.Wh + TX - 1) / TX;
   p.nty = (g.H + TY - 1) / TY;
   int zc = chunk_length((long long)p.ntx * p.nty * g.B * wgs_per_tile, g.D, g.k, wgs_per_cu);
@@ -1458,7 +1509,7 @@ TiledParams make_params(const Geo& g, int wgs_per_cu, int wgs_per_tile = 1) {
   p.nzc = (g.D + zc - 1) / zc;
   p.scale = g.scale;
   p.qscale = g.scale * kLog2e;
-  p.ch = g.d;
+  p.ch = g.d == 12 ? 6 : g.d;
   return p;
 }
 
@@ -1533,4 +1584,15 @@ void launch_march(const Geo& g, TiledParams io, hipStream_t st) {
       case 8: return dtype == 0 ? CALL(3, 8, f32x6_t, double) : CALL(3, 8, bf16x6_t, float);  \
     }                                                                                         \
   }                                                                                           \
+  return hipErrorNotSupported;
+
+// heads of twelve channels as pairs of half-heads: the kernels' HS is twice the number of heads
+#define MODET_DISPATCH_D12(CALL)                                                                \
+  if (g.k == 3) {                                                                               \
+    switch (g.heads) {                                                                          \
+      case 1: return dtype == 0 ? CALL(3, 2, f32x12_t, double) : CALL(3, 2, bf16x12_t, float);  \
+      case 2: return dtype == 0 ? CALL(3, 4, f32x12_t, double) : CALL(3, 4, bf16x12_t, float);  \
+      case 4: return dtype == 0 ? CALL(3, 8, f32x12_t, double) : CALL(3, 8, bf16x12_t, float);  \
+    }                                                                                           \
+  }                                                                                             \
   return hipErrorNotSupported;

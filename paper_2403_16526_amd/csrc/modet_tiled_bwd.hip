@@ -13,6 +13,7 @@ hipError_t launch_bwd_tiled(const Geo& g, int dtype, bool fast_logits, const Bwd
                             bool* dbias_done) {
   *dbias_done = false;
   if (g.d == 6) return launch_bwd_tiled_d6(g, dtype, io, st, dbias_done);
+  if (g.d == 12) return launch_bwd_tiled_d12(g, dtype, io, st, dbias_done);
   if (io.bias || io.dbias_acc) return launch_bwd_tiled_biased(g, dtype, fast_logits, io, st, dbias_done);
   return launch_bwd_tiled_plain(g, dtype, fast_logits, io, st, dbias_done);
 }

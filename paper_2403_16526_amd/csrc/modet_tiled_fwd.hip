@@ -31,9 +31,10 @@ hipError_t launch_fwd_biased(const Geo& g, int dtype, bool fast_logits, const vo
 
 // Covered, with or without bias.  Head size 8:  k = 3: 1/2/4/8 heads, fp32 inputs (fp64 logits) and bf16 inputs
 // (fp32 logits: the bf16 tolerance leaves room);  k = 5: 1/2 heads, bf16 inputs.  Head size 6: k = 3, 1/2/4/8
-// heads, both input types.
+// heads, both input types.  Head size 12: k = 3, 1/2/4 heads, both input types.
 bool tiled_fwd_supported(int d, int heads, int k, int dtype) {
   if (d == 6) return k == 3 && (heads == 1 || heads == 2 || heads == 4 || heads == 8);
+  if (d == 12) return k == 3 && (heads == 1 || heads == 2 || heads == 4);
   if (d != 8) return false;
   if (k == 3) return heads == 1 || heads == 2 || heads == 4 || heads == 8;
   if (k == 5) return dtype == 1 && (heads == 1 || heads == 2);
@@ -43,6 +44,7 @@ bool tiled_fwd_supported(int d, int heads, int k, int dtype) {
 hipError_t launch_fwd_tiled(const Geo& g, int dtype, bool fast_logits, const void* Q, const void* K,
                             const float* bias, float* phi, float* lse, hipStream_t st) {
   if (g.d == 6) return launch_fwd_tiled_d6(g, dtype, Q, K, bias, phi, lse, st);
+  if (g.d == 12) return launch_fwd_tiled_d12(g, dtype, Q, K, bias, phi, lse, st);
   if (bias) return launch_fwd_biased(g, dtype, fast_logits, Q, K, bias, phi, lse, st);
   return launch_fwd_plain(g, dtype, fast_logits, Q, K, phi, lse, st);
 }

@@ -45,6 +45,11 @@ SMALL = [
     (1, 9, 10, 33, 24, 4, 3, "f32"),
     (1, 6, 9, 17, 48, 8, 3, "bf16"),
     (1, 37, 8, 40, 12, 2, 3, "f32"),
+    # twelve channels per head on the tiled kernels (two half-head lanes per window): 1 / 2 / 4 heads, both dtypes
+    (1, 45, 13, 35, 12, 1, 3, "f32"),
+    (2, 9, 10, 19, 24, 2, 3, "f32"),
+    (1, 6, 9, 9, 48, 4, 3, "bf16"),
+    (1, 37, 9, 33, 12, 1, 3, "bf16"),
 ]
 
 
@@ -94,7 +99,7 @@ def test_small_cases_match_oracle(modet, shape, path):
 # with bias: one / two heads (k = 3) with chunk seams, four and eight heads, k = 5, 6 and 12 channels per head,
 # both dtypes
 BIASED = [SMALL[1], SMALL[3], SMALL[4], SMALL[6], SMALL[8], SMALL[12], SMALL[13], SMALL[16], SMALL[17], SMALL[18],
-          SMALL[19], SMALL[20], SMALL[21], SMALL[22], SMALL[23]]
+          SMALL[19], SMALL[20], SMALL[21], SMALL[22], SMALL[23], SMALL[24], SMALL[25], SMALL[26], SMALL[27]]
 
 
 @pytest.mark.parametrize("shape", BIASED, ids=lambda s: "x".join(map(str, s)))
@@ -103,7 +108,8 @@ def test_bias_and_recomputed_statistics(modet, shape, path):
     run_case(modet, shape, path, with_bias=True, stats="recompute")
 
 
-@pytest.mark.parametrize("shape", [SMALL[16], SMALL[18], SMALL[6]], ids=lambda s: "x".join(map(str, s)))
+@pytest.mark.parametrize("shape", [SMALL[16], SMALL[18], SMALL[6], SMALL[19], SMALL[24]],
+                         ids=lambda s: "x".join(map(str, s)))
 def test_bias_with_statistics_passed_in(modet, shape):
     run_case(modet, shape, 0, with_bias=True, stats="pass")
 
@@ -127,13 +133,14 @@ def test_explicit_scale_and_peaked_attention(modet):
         assert np.abs(phi - ref).max() < 5e-2
 
 
-@pytest.mark.parametrize("dtype,heads,k", [("f32", 1, 3), ("f32", 2, 3), ("bf16", 2, 3), ("bf16", 1, 5)])
-def test_forward_survives_logits_far_above_the_first_window_row(modet, dtype, heads, k):
+@pytest.mark.parametrize("dtype,heads,k,d", [("f32", 1, 3, 8), ("f32", 2, 3, 8), ("bf16", 2, 3, 8), ("bf16", 1, 5, 8),
+                                             ("f32", 2, 3, 6), ("bf16", 1, 3, 6), ("f32", 1, 3, 12), ("bf16", 2, 3, 12)])
+def test_forward_survives_logits_far_above_the_first_window_row(modet, dtype, heads, k, d):
     """The tiled forward measures every logit of a query against the largest one of the first window row it
     meets.  Here half of the queries have their match in the LAST plane of the window with a logit ~400 (log2
     units) above everything else, which overflows fp32 exponentials: those queries take the two-pass path and
     must still agree with the oracle, the other half must be untouched by it."""
-    B, D, H, W, d = 1, 9, 12, 70, 8
+    B, D, H, W = 1, 9, 12, 70
     r = k // 2
     Q = synth.normal(31, 0, (B, D, H, W, heads, d), dtype=np.float64)
     Q = (Q / np.linalg.norm(Q, axis=-1, keepdims=True)).reshape(B, D, H, W, heads * d).astype(np.float32)
@@ -151,7 +158,11 @@ def test_forward_survives_logits_far_above_the_first_window_row(modet, dtype, he
                                        want_lse=True)
             modet.modet_set_kernel_path(old)
             tag = f"path {path} bias {bias is not None}"
-            assert_close(phi.cpu().numpy(), ref_phi, dtype, "phi " + tag)
+            # The exponent of a weight, (logit - reference), is rounded to fp32 before exp2.  The logits of this
+            # test spread over +-60 (log2 units) around a query's reference instead of the few units normalised
+            # features give, so that rounding alone is up to 2^-24 * 64 = 4e-6 relative per weight: four times
+            # the stated tolerance is what the arithmetic supports here.
+            assert_close(phi.cpu().numpy(), ref_phi, dtype, "phi " + tag, scale=4.0)
             np.testing.assert_allclose(lse.cpu().numpy(), ref_lse, rtol=2e-2 if dtype == "bf16" else 2e-6, atol=1e-5,
                                        err_msg=tag)
     # the planted half really is (nearly always) one-hot on (r, 0, 0), the other half is not
