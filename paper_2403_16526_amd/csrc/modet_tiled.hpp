@@ -665,6 +665,41 @@ struct DqPolicy {
           }
       }
   }
+  // the same step, also adding dl of every (role, offset) to this lane's running sums for the bias gradient:
+  // sums[(((a+R)*KW + b+R)*KW + c+R) * NT] is a lane-private column of an LDS array: a plain read, add and
+  // write (nobody else touches the address; LDS atomics are an order of magnitude slower).  The three sums of
+  // an in-plane offset are read before its dot products and written after them.
+  template <int PH, bool FULL>
+  static __device__ __forceinline__ void step_sum(State (&st)[KW], const typename Lds<ET>::chunk* kb, int lbase,
+                                                  unsigned active, const LT* bl, float* sums) {
+#pragma unroll
+    for (int b = 0; b < KW; ++b)
+#pragma unroll
+      for (int c = 0; c < KW; ++c) {
+        float kf[8];
+        Lds<ET>::get8(kb, P::NPOS, lbase + b * P::PC + c * HS, kf);
+        LT kv[8];
+        widen8<LT, float>(kf, kv);
+        float run[KW];
+#pragma unroll
+        for (int i = 0; i < KW; ++i) run[i] = sums[(((KW - 1 - i) * KW + b) * KW + c) * NT];
+#pragma unroll
+        for (int i = 0; i < KW; ++i)
+          if (FULL || (active & (1u << i))) {
+            State& s = st[(i + PH) % KW];
+            LT init = s.nlse;
+            if (BIAS) init += bl[(((KW - 1 - i) * KW + b) * KW + c) * HS];
+            const float w = exp2_fast((float)whole_logit<T, LT>(dot8<LT>(s.q, kv, init)));
+            float tt = s.ngphi;
+            if (R - i != 0) tt = fmaf((float)(R - i), s.g0, tt);
+            if (b - R != 0) tt = fmaf((float)(b - R), s.g1, tt);
+            if (c - R != 0) tt = fmaf((float)(c - R), s.g2, tt);
+            const float dl = w * tt;
+            axpy8(s.acc, dl, kf);
+            sums[(((KW - 1 - i) * KW + b) * KW + c) * NT] = run[i] + dl;
+          }
+      }
+  }
   // the same step, also handing dl of every (role, offset) to the key side:
   // dl_out[(a+R) * DLA + ((b+R)*KW + c+R) * NT + li], a = R - i the plane offset of role i; roles that are not
   // active emit 0
@@ -966,6 +1001,40 @@ march_pair_kernel(TiledParams p, float* outA, float* outB) {
   }
 }
 
+// Adds a workgroup's per-lane sums of dl (dlsum[o * NT + lane], lane = column of the patch) to the fp64 sums
+// of the bias gradient: lane = (window offset o, 32-lane segment) adds up its segment by the columns' position
+// in a group of HS columns (position >> SH is the head; of a pair of half-head columns, which hold the same dl,
+// only the even one counts), the 8 segments are folded across lanes, and one lane per offset issues the atomics.
+// Called by NT lanes, tid = 0..NT-1, all of them.
+template <class T, int KW, int HS>
+__device__ __forceinline__ void reduce_dl_sums(const float* dlsum, int tid, double* acc) {
+  static_assert(KW == 3 && HS <= 8 && NT == 256, "27 offsets x 8 segments of 32 lanes");
+  constexpr int SH = Win<T>::SH, NH = HS >> SH;
+  const int row = tid >> 3, seg = tid & 7;
+  const bool on = row < 27;
+  double cls[8];              // by (column mod 8)
+#pragma unroll
+  for (int c = 0; c < 8; ++c) cls[c] = 0.0;
+  if (on) {
+    const float4* src = reinterpret_cast<const float4*>(dlsum + row * NT + seg * 32);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const float4 v = src[i];
+      cls[4 * (i & 1) + 0] += (double)v.x; cls[4 * (i & 1) + 1] += (double)v.y;
+      cls[4 * (i & 1) + 2] += (double)v.z; cls[4 * (i & 1) + 3] += (double)v.w;
+    }
+  }
+#pragma unroll
+  for (int h = 0; h < NH; ++h) {
+    double v = 0.0;
+#pragma unroll
+    for (int c = h << SH; c < 8; c += HS) v += cls[c];
+#pragma unroll
+    for (int m = 1; m < 8; m <<= 1) v += __shfl_xor(v, m);
+    if (on && seg == 0) atomicAdd(acc + h * 27 + row, v);
+  }
+}
+
 // ---- backward with both operands staged once --------------------------------------------------------
 // A 512-lane workgroup owns one tile: lanes 0..255 run the dQ march, lanes 256..511 the dK march, in the same
 // steps.  The dQ half stages the haloed K planes, the dK half the haloed Q planes and query statistics, into
@@ -984,6 +1053,7 @@ struct BwdRings {
 template <int KW, int HS, class LT, bool BIAS>
 struct BwdRingsB : BwdRings<KW, HS> {
   BiasTable<LT, KW, HS, BIAS> bias;
+  alignas(16) float dlsum[BIAS ? KW * KW * KW * NT : 4];   // per query lane: running sums of dl per window offset
 };
 
 // the part of a step after the arithmetic, for one half; OTHER = the ring this half refills from
@@ -992,14 +1062,24 @@ __device__ __forceinline__ void shared_step(typename Pol::State (&st)[Pol::KW], 
                                             const float4* lds_cur, const float4* sa_cur, const float* sc_cur,
                                             const float4* own_new, const float4* sa_new, const float* sc_new,
                                             int lbase, int s, bool fill_new, const Commit& commit_staged,
-                                            const typename Pol::Logit* bl) {
+                                            const typename Pol::Logit* bl, float* sums) {
   constexpr int KW = Pol::KW, R = KW / 2;
   typedef typename Pol::P P;
   // the plane s + R enters the window of the newest role: its slot was freed by the store of the last step
   if (fill_new) Pol::refill_lds(st[(KW - 1 + PH) % KW], own_new, lbase + R * P::PC + R * Pol::HS, sa_new, sc_new, p);
   const unsigned active = active_roles<KW>(s, t.z0, t.z1);
-  if (active == (1u << KW) - 1u) Pol::template step<PH, true>(st, lds_cur, sa_cur, sc_cur, lbase, active, bl);
-  else Pol::template step<PH, false>(st, lds_cur, sa_cur, sc_cur, lbase, active, bl);
+  bool summed = false;
+  if constexpr (Pol::kBias && !Pol::kStats) {      // (the dQ half, when the bias gradient is wanted: uniform)
+    if (sums != nullptr) {
+      if (active == (1u << KW) - 1u) Pol::template step_sum<PH, true>(st, lds_cur, lbase, active, bl, sums);
+      else Pol::template step_sum<PH, false>(st, lds_cur, lbase, active, bl, sums);
+      summed = true;
+    }
+  }
+  if (!summed) {
+    if (active == (1u << KW) - 1u) Pol::template step<PH, true>(st, lds_cur, sa_cur, sc_cur, lbase, active, bl);
+    else Pol::template step<PH, false>(st, lds_cur, sa_cur, sc_cur, lbase, active, bl);
+  }
   commit_staged();       // before the stores: its wait for the loads must not cover them
   if ((active & 1u) && t.lane_ok)          // role 0 has seen its whole window
     Pol::store(st[PH % KW], p, t.col + (long long)(s - R) * p.H * p.Wh);
@@ -1048,6 +1128,14 @@ __device__ __forceinline__ void shared_march(const TiledParams& p, const Tile& t
   fetch(s_first + R + 1);
   if constexpr (Pol::kBias && !IS_DK) fill_bias_table<T, typename Pol::Logit, KW, HS>(sh.bias.v, p.bias, tid, NT);
   const typename Pol::Logit* bl = lane_bias<Pol>(sh, t.xs);
+  float* sums = nullptr;      // the dQ half's sums of dl, when the bias gradient is wanted
+  if constexpr (Pol::kBias && !IS_DK) {
+    if (p.dbias_acc != nullptr) {
+      sums = sh.dlsum + tid;
+#pragma unroll
+      for (int j = 0; j < KW * KW * KW; ++j) sums[j * NT] = 0.f;
+    }
+  }
   __syncthreads();
 
   int cur = 0;                               // cur = (s - s_first) % RING
@@ -1059,7 +1147,7 @@ __device__ __forceinline__ void shared_march(const TiledParams& p, const Tile& t
     // the staged plane s + R + 1 replaces the plane s - 1, which nobody reads any more
     auto commit_staged = [&]() { if (s + R + 1 <= s_last) commit(wr); };
     shared_step<Pol, PH>(st, p, t, mine[cur], sh.sa[cur], sh.sc[cur], other[nw], sh.sa[nw], sh.sc[nw], lbase, s,
-                         fill_new, commit_staged, bl);
+                         fill_new, commit_staged, bl, sums);
     fetch(s + R + 2);
     cur = cur + 1 == RING ? 0 : cur + 1;
     __syncthreads();
@@ -1073,6 +1161,10 @@ __device__ __forceinline__ void shared_march(const TiledParams& p, const Tile& t
       default: one_step(std::integral_constant<int, 2>(), s); break;
     }
     ph = ph == KW - 1 ? 0 : ph + 1;
+  }
+  if constexpr (Pol::kBias && !IS_DK) {
+    if (sums != nullptr)      // (uniform; the last step ended with a barrier, so every lane's sums are visible)
+      reduce_dl_sums<T, KW, HS>(sh.dlsum, tid, p.dbias_acc);
   }
 }
 

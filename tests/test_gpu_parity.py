@@ -50,6 +50,9 @@ SMALL = [
     (2, 9, 10, 19, 24, 2, 3, "f32"),
     (1, 6, 9, 9, 48, 4, 3, "bf16"),
     (1, 37, 9, 33, 12, 1, 3, "bf16"),
+    # chunk seams of the four-heads-and-more backward (and of its bias gradient)
+    (1, 45, 9, 20, 32, 4, 3, "f32"),
+    (1, 41, 9, 17, 24, 2, 3, "bf16"),
 ]
 
 
@@ -99,7 +102,8 @@ def test_small_cases_match_oracle(modet, shape, path):
 # with bias: one / two heads (k = 3) with chunk seams, four and eight heads, k = 5, 6 and 12 channels per head,
 # both dtypes
 BIASED = [SMALL[1], SMALL[3], SMALL[4], SMALL[6], SMALL[8], SMALL[12], SMALL[13], SMALL[16], SMALL[17], SMALL[18],
-          SMALL[19], SMALL[20], SMALL[21], SMALL[22], SMALL[23], SMALL[24], SMALL[25], SMALL[26], SMALL[27]]
+          SMALL[19], SMALL[20], SMALL[21], SMALL[22], SMALL[23], SMALL[24], SMALL[25], SMALL[26], SMALL[27],
+          SMALL[28], SMALL[29]]
 
 
 @pytest.mark.parametrize("shape", BIASED, ids=lambda s: "x".join(map(str, s)))
