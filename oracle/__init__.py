@@ -156,3 +156,23 @@ def upsample2x(coarse):
     rc = lib().oracle_upsample2x(_ptr(coarse), B, 2 * Dc, 2 * Hc, 2 * Wc, _ptr(fine))
     assert rc == 0
     return fine
+
+
+def compose(outer, inner):
+    """Displacement of "move by inner, then by outer" (Section 3.1): inner + outer sampled at p + inner(p);
+    fields [B,D,H,W,3] (taken as fp32), float64 result."""
+    inner32 = np.ascontiguousarray(inner, dtype=np.float32)
+    return inner32.astype(np.float64) + warp(outer, inner32)
+
+
+def integrate_velocity(v, T):
+    """Scaling and squaring (Section 3.3.2, Eq. 6; the doubling recurrence of the work the paper cites for it):
+    phi_0 = v / 2^T, then T times phi <- phi o phi.  Every intermediate field is an fp32 tensor, as it is for
+    any caller that composes fields through the fp32 interface; float64 result of the last step."""
+    phi = np.ascontiguousarray(v, dtype=np.float32) * np.float32(2.0 ** -T)
+    out = phi.astype(np.float64)
+    for t in range(T):
+        out = compose(phi, phi)
+        phi = out.astype(np.float32)
+    return out
+
