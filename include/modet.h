@@ -108,6 +108,32 @@ int modet_warp(const void* src, const float* field, void* out,
                int B, int D, int H, int W, int C, int field_half_res,
                modet_dtype dtype, void* stream);
 
+/* Composition of two displacement fields: paper Section 3.1 (the total field of a pyramid level is
+ * the level's residual field composed with the upsampled total field of the level below).
+ *
+ *   out[b, p, :] = inner[b, p, :] + trilinear(outer[b], p + inner[b, p, :]),
+ * the displacement of "move by inner, then by outer"; same sampling rules as modet_warp (voxel
+ * units, components ordered (D, H, W), zero outside the volume).
+ *   outer, inner  in   [B, D, H, W, 3] fp32; they may be the same buffer
+ *   out           out  [B, D, H, W, 3] fp32; must not alias an input
+ */
+int modet_compose(const float* outer, const float* inner, float* out,
+                  int B, int D, int H, int W, void* stream);
+
+/* Integration of a stationary velocity field by scaling and squaring: paper Section 3.3.2, Eq. 6
+ * (the optional diffeomorphic layer of the registration head).
+ *
+ *   phi_0 = v / 2^T;   phi_t = phi_{t-1} o phi_{t-1}  (modet_compose of the field with itself), T times;
+ *   out = phi_T, the displacement field at time 1.  T = 0 copies v.
+ *   v     in   [B, D, H, W, 3] fp32
+ *   out   out  [B, D, H, W, 3] fp32
+ *   tmp        scratch of the same size, required for T >= 2 (MODET_ERR_WORKSPACE if NULL), else
+ *              may be NULL; v, out and tmp must not alias
+ *   T     0..30
+ */
+int modet_integrate_velocity(const float* v, float* out, float* tmp,
+                             int B, int D, int H, int W, int T, void* stream);
+
 /* Kernel selection, for tests and profiling.  0 = automatic (LDS-tiled kernels where the
  * shape is covered, generic otherwise), 1 = always the generic kernels.  Returns the
  * previous value.  Process-wide, not thread safe. */

@@ -135,6 +135,40 @@ int modet_warp(const void* src, const float* field, void* out,
   return e == hipSuccess ? MODET_OK : MODET_ERR_LAUNCH;
 }
 
+int modet_compose(const float* outer, const float* inner, float* out, int B, int D, int H, int W, void* stream) {
+  if (!outer || !inner || !out) return MODET_ERR_NULL;
+  if (B < 1 || D < 1 || H < 1 || W < 1) return MODET_ERR_SHAPE;
+  if ((long long)B * D * H * W * 3 >= (1LL << 31)) return MODET_ERR_UNSUPPORTED;
+  if (misaligned(outer) || misaligned(inner) || misaligned(out)) return MODET_ERR_ALIGN;
+  hipError_t e = launch_compose(outer, inner, out, B, D, H, W, 1.0f, (hipStream_t)stream);
+  return e == hipSuccess ? MODET_OK : MODET_ERR_LAUNCH;
+}
+
+int modet_integrate_velocity(const float* v, float* out, float* tmp, int B, int D, int H, int W, int T,
+                             void* stream) {
+  if (!v || !out) return MODET_ERR_NULL;
+  if (B < 1 || D < 1 || H < 1 || W < 1 || T < 0) return MODET_ERR_SHAPE;
+  if (T > 30) return MODET_ERR_UNSUPPORTED;
+  const long long n = (long long)B * D * H * W * 3;
+  if (n >= (1LL << 31)) return MODET_ERR_UNSUPPORTED;
+  if (T >= 2 && !tmp) return MODET_ERR_WORKSPACE;
+  if (misaligned(v) || misaligned(out) || misaligned(tmp)) return MODET_ERR_ALIGN;
+  hipStream_t st = (hipStream_t)stream;
+  if (T == 0)
+    return hipMemcpyAsync(out, v, (size_t)n * sizeof(float), hipMemcpyDeviceToDevice, st) == hipSuccess
+               ? MODET_OK : MODET_ERR_LAUNCH;
+  // step t = 1..T writes `out` when T - t is even, `tmp` otherwise: the last step lands in `out`, and a step
+  // never writes the buffer it reads.  The first step also scales by 2^-T.
+  const float* src = v;
+  for (int t = 1; t <= T; ++t) {
+    float* dst = ((T - t) & 1) ? tmp : out;
+    const float s = t == 1 ? ldexpf(1.0f, -T) : 1.0f;
+    if (launch_compose(src, src, dst, B, D, H, W, s, st) != hipSuccess) return MODET_ERR_LAUNCH;
+    src = dst;
+  }
+  return MODET_OK;
+}
+
 int modet_set_kernel_path(int path) {
   int old = g_kernel_path;
   g_kernel_path = path == 1 ? 1 : 0;

@@ -194,7 +194,65 @@ hipError_t launch_t(const void* src, const float* field, void* out, int B, int D
   return hipGetLastError();
 }
 
+// ---- composition of displacement fields --------------------------------------------------------------
+// out[p] = s * (inner[p] + trilinear(outer, p + s * inner[p])), zero outside the volume, one lane per voxel
+// (three channels share the corner weights).  s = 1 is the composition of Section 3.1 (a level's residual
+// field with the upsampled total field of the level below); s = 2^-T folds the scaling of a velocity
+// field into the first squaring step of the integration of Eq. 6 (scaling by a power of two is exact).
+struct Disp { float z, y, x; };      // one voxel of a field: a single 12-byte load or store
+
+__global__ void __launch_bounds__(kThreads)
+compose_kernel(const float* __restrict__ outer, const float* __restrict__ inner, float* __restrict__ out, int B,
+               int D, int H, int W, float s) {
+  const long long nvox = (long long)B * D * H * W;
+  const long long v = (long long)blockIdx.x * kThreads + threadIdx.x;
+  if (v >= nvox) return;
+  long long t = v;
+  const int x = (int)(t % W); t /= W;
+  const int y = (int)(t % H); t /= H;
+  const int z = (int)(t % D);
+  const int b = (int)(t / D);
+  const Disp iv = *reinterpret_cast<const Disp*>(inner + v * 3);
+  const float i0 = iv.z, i1 = iv.y, i2 = iv.x;
+  const double u0 = (double)(s * i0), u1 = (double)(s * i1), u2 = (double)(s * i2);
+  // integer and fractional parts as in the warp kernel: the fraction of an fp32 displacement is exact
+  const double fz = floor(u0), fy = floor(u1), fx = floor(u2);
+  const float tz = (float)(u0 - fz), ty = (float)(u1 - fy), tx = (float)(u2 - fx);
+  const int z0 = z + (int)fmin(fmax(fz, -1.0e6), 1.0e6);
+  const int y0 = y + (int)fmin(fmax(fy, -1.0e6), 1.0e6);
+  const int x0 = x + (int)fmin(fmax(fx, -1.0e6), 1.0e6);
+  const float* ob = outer + (long long)b * D * H * W * 3;
+  float val[8][3];
+  bool in[8];
+#pragma unroll
+  for (int c = 0; c < 8; ++c) {     // all corner loads first, from clamped addresses
+    const int zi = z0 + ((c >> 2) & 1), yi = y0 + ((c >> 1) & 1), xi = x0 + (c & 1);
+    in[c] = (unsigned)zi < (unsigned)D && (unsigned)yi < (unsigned)H && (unsigned)xi < (unsigned)W;
+    const int zc = min(max(zi, 0), D - 1), yc = min(max(yi, 0), H - 1), xc = min(max(xi, 0), W - 1);
+    const Disp q = *reinterpret_cast<const Disp*>(ob + (((long long)zc * H + yc) * W + xc) * 3);
+    val[c][0] = q.z; val[c][1] = q.y; val[c][2] = q.x;
+  }
+  float acc[3] = {0.f, 0.f, 0.f};
+#pragma unroll
+  for (int c = 0; c < 8; ++c) {
+    const float w = ((c & 4) ? tz : 1.f - tz) * ((c & 2) ? ty : 1.f - ty) * ((c & 1) ? tx : 1.f - tx);
+#pragma unroll
+    for (int i = 0; i < 3; ++i) acc[i] = fmaf(w, in[c] ? val[c][i] : 0.f, acc[i]);
+  }
+  Disp r;
+  r.z = s * (i0 + acc[0]); r.y = s * (i1 + acc[1]); r.x = s * (i2 + acc[2]);
+  *reinterpret_cast<Disp*>(out + v * 3) = r;
+}
+
 }  // namespace
+
+hipError_t launch_compose(const float* outer, const float* inner, float* out, int B, int D, int H, int W, float s,
+                          hipStream_t st) {
+  const long long nvox = (long long)B * D * H * W;
+  hipLaunchKernelGGL(compose_kernel, dim3((unsigned)((nvox + kThreads - 1) / kThreads)), dim3(kThreads), 0, st, outer,
+                     inner, out, B, D, H, W, s);
+  return hipGetLastError();
+}
 
 hipError_t launch_warp(const void* src, const float* field, void* out, int B, int D, int H, int W, int C,
                        int half, int dtype, hipStream_t st) {

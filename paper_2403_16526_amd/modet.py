@@ -18,7 +18,8 @@ LIB_PATH = os.environ.get("MODET_LIBRARY") or os.path.join(_HERE, "libmodet.so")
 MODET_F32, MODET_BF16 = 0, 1
 MODET_OK = 0
 
-EXPORTS = ("modet_fwd", "modet_bwd", "modet_bwd_workspace_bytes", "modet_warp", "modet_set_kernel_path", "modet_set_math_mode",
+EXPORTS = ("modet_fwd", "modet_bwd", "modet_bwd_workspace_bytes", "modet_warp", "modet_compose",
+           "modet_integrate_velocity", "modet_set_kernel_path", "modet_set_math_mode",
            "modet_has_tiled_kernels", "modet_status_string", "modet_version")
 
 if not os.path.exists(LIB_PATH):
@@ -34,6 +35,10 @@ _lib.modet_bwd.restype = _ci
 _lib.modet_bwd_workspace_bytes.argtypes = [_ci] * 7 + [_ci, _ci]
 _lib.modet_bwd_workspace_bytes.restype = _sz
 _lib.modet_warp.argtypes = [_vp] * 3 + [_ci] * 5 + [_ci, _ci, _vp]
+_lib.modet_compose.restype = _ci
+_lib.modet_compose.argtypes = [_vp] * 3 + [_ci] * 4 + [_vp]
+_lib.modet_integrate_velocity.restype = _ci
+_lib.modet_integrate_velocity.argtypes = [_vp] * 3 + [_ci] * 5 + [_vp]
 _lib.modet_warp.restype = _ci
 _lib.modet_set_kernel_path.argtypes = [_ci]
 _lib.modet_set_kernel_path.restype = _ci
@@ -161,4 +166,26 @@ def modet_warp(src, field, field_half_res: bool = False, out=None):
         out = torch.empty_like(src)
     _check(_lib.modet_warp(_ptr(src), _ptr(field), _ptr(out), B, D, H, W, C, int(bool(field_half_res)),
                            _in_dtype(src), _stream()))
+    return out
+
+
+def modet_compose(outer, inner, out=None):
+    """out[b,p,:] = inner[b,p,:] + trilinear(outer[b], p + inner[b,p,:]); fields [B,D,H,W,3] fp32."""
+    _dev(outer, inner)
+    B, D, H, W, _ = inner.shape
+    if out is None:
+        out = torch.empty_like(inner)
+    _check(_lib.modet_compose(_ptr(outer), _ptr(inner), _ptr(out), B, D, H, W, _stream()))
+    return out
+
+
+def modet_integrate_velocity(v, T: int, out=None, tmp=None):
+    """Scaling and squaring: phi_0 = v / 2^T, then T self-compositions; [B,D,H,W,3] fp32."""
+    _dev(v)
+    B, D, H, W, _ = v.shape
+    if out is None:
+        out = torch.empty_like(v)
+    if tmp is None and T >= 2:
+        tmp = torch.empty_like(v)
+    _check(_lib.modet_integrate_velocity(_ptr(v), _ptr(out), _ptr(tmp), B, D, H, W, int(T), _stream()))
     return out

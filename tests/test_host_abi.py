@@ -21,6 +21,8 @@ def lib():
     L.modet_fwd.argtypes = [vp] * 6 + [ci] * 7 + [cf, ci, vp]
     L.modet_bwd.argtypes = [vp] * 9 + [ci] * 7 + [cf, ci, vp, sz, vp]
     L.modet_warp.argtypes = [vp] * 3 + [ci] * 5 + [ci, ci, vp]
+    L.modet_compose.argtypes = [vp] * 3 + [ci] * 4 + [vp]
+    L.modet_integrate_velocity.argtypes = [vp] * 3 + [ci] * 5 + [vp]
     L.modet_bwd_workspace_bytes.argtypes = [ci] * 9
     L.modet_bwd_workspace_bytes.restype = sz
     L.modet_status_string.argtypes = [ci]
@@ -95,6 +97,17 @@ def test_warp_rejects_bad_arguments(lib):
     assert w(D=0) == E_SHAPE and w(half=1, H=5) == E_SHAPE and w(half=2) == E_SHAPE
     assert w(C=5) == E_UNSUP and w(C=4, dt=1) == E_UNSUP and w(dt=7) == E_UNSUP
     assert w(out=ODD) == E_ALIGN
+
+
+def test_field_functions_reject_bad_arguments(lib):
+    comp = lambda a=P, b=P, o=P, B=1, D=4, H=4, W=4: lib.modet_compose(a, b, o, B, D, H, W, None)
+    assert comp(a=None) == E_NULL and comp(b=None) == E_NULL and comp(o=None) == E_NULL
+    assert comp(H=0) == E_SHAPE and comp(o=ODD) == E_ALIGN
+    assert comp(B=64, D=512, H=512, W=512) == E_UNSUP
+    integ = lambda v=P, o=P, t=P, B=1, D=4, H=4, W=4, T=3: lib.modet_integrate_velocity(v, o, t, B, D, H, W, T, None)
+    assert integ(v=None) == E_NULL and integ(o=None) == E_NULL
+    assert integ(t=None, T=2) == E_WS and integ(T=-1) == E_SHAPE and integ(T=31) == E_UNSUP
+    assert integ(W=0) == E_SHAPE and integ(t=ODD) == E_ALIGN
 
 
 def test_status_strings(lib):
