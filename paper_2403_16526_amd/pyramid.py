@@ -56,7 +56,9 @@ class PyramidLoop:
                 phi = varphi
             else:
                 up = upsample_field(phi_prev)
-                phi = varphi + modet.modet_warp(up, varphi)      # phi_l(p) = varphi(p) + up(p + varphi(p))
+                phi = modet.modet_compose(up, varphi)            # phi_l(p) = varphi(p) + up(p + varphi(p))
+                for name, t in (("comp_outer", up), ("comp_inner", varphi), ("comp_out", phi)):
+                    self._rec(l, name, t)
             tgt = 0.0 if self.targets is None else self.targets[l]
             diff = sub - tgt
             nvn = sub.numel() // 3

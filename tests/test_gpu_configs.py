@@ -142,5 +142,7 @@ def test_config4_pyramid_teacher_forced(modet):
                 if l > 0:
                     ref_w = oracle.warp(store[(l, "warp_src")], store[(l, "warp_field")], field_half_res=True)
                     assert_close(store[(l, "warp_out")], ref_w, "f32", f"iter {it} level {l} warp")
+                    ref_c = oracle.compose(store[(l, "comp_outer")], store[(l, "comp_inner")])
+                    assert_close(store[(l, "comp_out")], ref_c, "f32", f"iter {it} level {l} composition")
     assert np.isfinite(losses).all() and losses[-1] < losses[0]
     assert phi.shape == (1, 160, 192, 224, 3)
