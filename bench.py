@@ -41,6 +41,11 @@ def main():
     ap.add_argument("--fast-logits", action="store_true",
                     help="fp32 instead of fp64 logits (does not meet the parity tolerance; for information)")
     ap.add_argument("--recompute-stats", action="store_true", help="do not hand phi/lse of the forward to the backward")
+    # variants of the workload (not the headline configuration): the paper's own head sizes, the learned bias
+    ap.add_argument("--head-dim", type=int, default=0, choices=[0, 6, 8, 12],
+                    help="channels per head: the configuration's shape with C = heads * this (0: as configured)")
+    ap.add_argument("--bias", action="store_true",
+                    help="add a bias B (Eq. 3) to the logits; the backward then also returns its gradient")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (--gpus 1); a multi-GPU figure is not produced.",
@@ -55,7 +60,8 @@ def main():
     torch.cuda.set_device(0)
     cfg = synth.CONFIGS[args.config]
     t0 = time.time()
-    c = synth.make_config(args.config)
+    over = {"C": cfg["heads"] * args.head_dim} if args.head_dim else {}
+    c = synth.make_config(args.config, **over)
     t_gen = time.time() - t0
     B, D, H, W, C, heads, k, dtype = (c[n] for n in ("B", "D", "H", "W", "C", "heads", "k", "dtype"))
     nvox = B * D * H * W
@@ -75,21 +81,24 @@ def main():
     dK = torch.empty((B, D, H, W, C), **f32)
     in_dt = modet.MODET_BF16 if dtype == "bf16" else modet.MODET_F32
     have_stats = not args.recompute_stats
-    wsb = modet.modet_bwd_workspace_bytes(B, D, H, W, C, heads, k, in_dt, have_stats)
+    wsb = modet.modet_bwd_workspace_bytes(B, D, H, W, C, heads, k, in_dt, have_stats, want_dbias=args.bias)
     ws = torch.empty(max(wsb, 16), device="cuda", dtype=torch.uint8)
+    bias = (torch.from_numpy((0.5 * synth.normal(synth.BASE_SEED + args.config, 9, (heads, k ** 3))).astype(np.float32))
+            .cuda() if args.bias else None)
     if args.generic:
         modet.modet_set_kernel_path(1)
     if args.fast_logits:
         modet.modet_set_math_mode(1)
 
     def fwd():
-        modet.modet_fwd(Q, K, heads, k, out=(phi, lse))
+        modet.modet_fwd(Q, K, heads, k, bias=bias, out=(phi, lse))
 
     def bwd():
         if have_stats:
-            modet.modet_bwd(Q, K, g, heads, k, phi=phi, lse=lse, out=(dQ, dK), workspace=ws)
+            modet.modet_bwd(Q, K, g, heads, k, bias=bias, phi=phi, lse=lse, want_dbias=args.bias, out=(dQ, dK),
+                            workspace=ws)
         else:
-            modet.modet_bwd(Q, K, g, heads, k, out=(dQ, dK), workspace=ws)
+            modet.modet_bwd(Q, K, g, heads, k, bias=bias, want_dbias=args.bias, out=(dQ, dK), workspace=ws)
 
     # The first ~20 ms of GPU work after an idle period run ~15 % slower while the clocks ramp up.  Whatever
     # --warmup says, keep the GPU busy with the same step for PREWARM_MS before the warm-up steps (untimed, and
@@ -124,14 +133,17 @@ def main():
     # algorithmic bytes (each tensor moved once, no stored attention)
     fwd_bytes = nvox * (2 * C * esz + 12 * heads)
     bwd_bytes = nvox * (2 * C * esz + 12 * heads + 8 * C)
-    bwd_kernel = ("generic kernels" if args.generic else "bwd_fused_kernel" if k == 3 and heads <= 2 else
+    hs = heads * (2 if C // heads == 12 else 1)       # fused columns per voxel (twelve channels: two half-heads)
+    tiled = not args.generic and modet.modet_has_tiled_kernels(C, heads, k, in_dt) == 3
+    bwd_kernel = ("generic kernels" if not tiled else "bwd_fused_kernel" if k == 3 and hs <= 2 else
                   "bwd_shared_kernel" if k == 3 else "march_pair_kernel")
     dom_bytes, dom_ms, dom_name = ((bwd_bytes, t_bwd, f"modet_bwd ({bwd_kernel})") if t_bwd >= t_fwd
                                   else (fwd_bytes, t_fwd, "modet_fwd"))
     achieved = dom_bytes / (dom_ms * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": dom_name, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": MEASURED_TRAFFIC_BYTES.get(args.config) if (t_bwd >= t_fwd and not args.generic) else None,
+                "traffic": (MEASURED_TRAFFIC_BYTES.get(args.config)
+                            if (t_bwd >= t_fwd and not args.generic and not args.bias and not args.head_dim) else None),
                 "algorithmic_bytes": dom_bytes, "avg_launch_ms": round(dom_ms, 4)}
 
     # the same step against the vector-ALU roofline.  Algorithmic flops per window: k^3 pairs, each a d-term dot
@@ -179,6 +191,24 @@ def main():
     t_warp = e0.elapsed_time(e1) / 10
     warp_bytes = nvox * (2 * C * esz + 12)
 
+    # field composition and scaling-and-squaring at the same shape (also beside the metric)
+    comp, tmp = torch.empty_like(field), torch.empty_like(field)
+    for _ in range(3):
+        modet.modet_compose(field, field, out=comp)
+    e0.record()
+    for _ in range(10):
+        modet.modet_compose(field, field, out=comp)
+    e1.record()
+    torch.cuda.synchronize()
+    t_comp = e0.elapsed_time(e1) / 10
+    modet.modet_integrate_velocity(field, 7, out=comp, tmp=tmp)
+    e0.record()
+    for _ in range(5):
+        modet.modet_integrate_velocity(field, 7, out=comp, tmp=tmp)
+    e1.record()
+    torch.cuda.synchronize()
+    t_int = e0.elapsed_time(e1) / 5
+
     cpu = None
     if not args.no_cpu_baseline:
         import oracle
@@ -203,8 +233,9 @@ def main():
         "value": round(value, 1), "unit": "voxel-neighbourhoods/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32" if dtype == "f32" else "bf16-in/f32-acc", "data": "synthetic",
-        "config": {"workload": f"config {args.config}: {cfg['name']} B={B} {D}x{H}x{W} C={C} heads={heads} k={k} "
-                               f"{dtype}, fwd(phi,lse)+bwd(dQ,dK)",
+        "config": {"workload": f"config {args.config}{' (variant)' if (args.bias or args.head_dim) else ''}: "
+                               f"{cfg['name']} B={B} {D}x{H}x{W} C={C} heads={heads} k={k} {dtype}, "
+                               + ("fwd(phi,lse)+bwd(dQ,dK,dbias) with bias" if args.bias else "fwd(phi,lse)+bwd(dQ,dK)"),
                    "kernel_path": "generic" if args.generic else "auto",
                    "stats_from_forward": have_stats, "untimed_prewarm_ms": PREWARM_MS,
                    "logits": ("fp32" if dtype == "bf16" else
@@ -220,6 +251,8 @@ def main():
         "pairs_per_s": round(value * k ** 3, 1),
         "device_copy_gbs": round(copy_gbs, 1),
         "warp": {"ms": round(t_warp, 4), "gbs": round(warp_bytes / (t_warp * 1e-3) / 1e9, 1)},
+        "compose": {"ms": round(t_comp, 4), "gbs": round(nvox * 24 / (t_comp * 1e-3) / 1e9, 1),
+                    "integrate_T7_ms": round(t_int, 4)},
         "input_gen_s": round(t_gen, 1),
     }
     print(json.dumps(line))

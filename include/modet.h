@@ -102,7 +102,7 @@ size_t modet_bwd_workspace_bytes(int B, int D, int H, int W, int C, int heads, i
  *       the coarser level's field fused into the warp, values doubled because they are in
  *       voxel units of their own grid.
  *   src, out in `dtype` (bf16 output is rounded to nearest even); field is fp32.
- *   C must be a multiple of 4 (fp32) or 8 (bf16), or equal to 3 (fp32: warping a field).
+ *   C is at most 256 and, for bf16, even (C = 3 in fp32 warps a displacement field).
  */
 int modet_warp(const void* src, const float* field, void* out,
                int B, int D, int H, int W, int C, int field_half_res,

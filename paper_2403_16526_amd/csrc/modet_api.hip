@@ -128,7 +128,8 @@ int modet_warp(const void* src, const float* field, void* out,
   if (field_half_res != 0 && field_half_res != 1) return MODET_ERR_SHAPE;
   if (field_half_res && ((D | H | W) & 1)) return MODET_ERR_SHAPE;
   if (dtype != MODET_F32 && dtype != MODET_BF16) return MODET_ERR_UNSUPPORTED;
-  if (dtype == MODET_BF16 ? (C % 8 != 0) : (C % 4 != 0 && C != 3)) return MODET_ERR_UNSUPPORTED;
+  if (dtype == MODET_BF16 && (C & 1)) return MODET_ERR_UNSUPPORTED;      // bf16 channels travel in pairs
+  if (C > 256) return MODET_ERR_UNSUPPORTED;                             // a voxel's channels fit one workgroup
   if ((long long)B * D * H * W * C >= (1LL << 31)) return MODET_ERR_UNSUPPORTED;
   if (misaligned(src) || misaligned(field) || misaligned(out)) return MODET_ERR_ALIGN;
   hipError_t e = launch_warp(src, field, out, B, D, H, W, C, field_half_res, (int)dtype, (hipStream_t)stream);

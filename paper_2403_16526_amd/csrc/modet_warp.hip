@@ -20,6 +20,15 @@ template <> struct Vec<float, 4> {
     *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
   }
 };
+template <> struct Vec<float, 2> {
+  static __device__ __forceinline__ void load(const float* p, float* v) {
+    float2 t = *reinterpret_cast<const float2*>(p);
+    v[0] = t.x; v[1] = t.y;
+  }
+  static __device__ __forceinline__ void store(float* p, const float* v) {
+    *reinterpret_cast<float2*>(p) = make_float2(v[0], v[1]);
+  }
+};
 template <> struct Vec<float, 1> {
   static __device__ __forceinline__ void load(const float* p, float* v) { v[0] = p[0]; }
   static __device__ __forceinline__ void store(float* p, const float* v) { p[0] = v[0]; }
@@ -39,6 +48,27 @@ template <> struct Vec<bf16_t, 8> {
 #pragma unroll
     for (int i = 0; i < 4; ++i) w[i] = (uint32_t)f2bf(v[2 * i]) | ((uint32_t)f2bf(v[2 * i + 1]) << 16);
     *reinterpret_cast<uint4*>(p) = make_uint4(w[0], w[1], w[2], w[3]);
+  }
+};
+
+template <> struct Vec<bf16_t, 4> {
+  static __device__ __forceinline__ void load(const bf16_t* p, float* v) {
+    uint2 t = *reinterpret_cast<const uint2*>(p);
+    v[0] = __uint_as_float(t.x << 16); v[1] = __uint_as_float(t.x & 0xFFFF0000u);
+    v[2] = __uint_as_float(t.y << 16); v[3] = __uint_as_float(t.y & 0xFFFF0000u);
+  }
+  static __device__ __forceinline__ void store(bf16_t* p, const float* v) {
+    *reinterpret_cast<uint2*>(p) = make_uint2((uint32_t)f2bf(v[0]) | ((uint32_t)f2bf(v[1]) << 16),
+                                              (uint32_t)f2bf(v[2]) | ((uint32_t)f2bf(v[3]) << 16));
+  }
+};
+template <> struct Vec<bf16_t, 2> {
+  static __device__ __forceinline__ void load(const bf16_t* p, float* v) {
+    const uint32_t t = *reinterpret_cast<const uint32_t*>(p);
+    v[0] = __uint_as_float(t << 16); v[1] = __uint_as_float(t & 0xFFFF0000u);
+  }
+  static __device__ __forceinline__ void store(bf16_t* p, const float* v) {
+    *reinterpret_cast<uint32_t*>(p) = (uint32_t)f2bf(v[0]) | ((uint32_t)f2bf(v[1]) << 16);
   }
 };
 
@@ -256,8 +286,14 @@ hipError_t launch_compose(const float* outer, const float* inner, float* out, in
 
 hipError_t launch_warp(const void* src, const float* field, void* out, int B, int D, int H, int W, int C,
                        int half, int dtype, hipStream_t st) {
-  if (dtype == 1) return launch_t<bf16_t, 8>(src, field, out, B, D, H, W, C, half, st);
+  // the widest vector that divides the channel count (6 and 12 channels per head give C = 6, 12, 24, ...)
+  if (dtype == 1) {
+    if (C % 8 == 0) return launch_t<bf16_t, 8>(src, field, out, B, D, H, W, C, half, st);
+    if (C % 4 == 0) return launch_t<bf16_t, 4>(src, field, out, B, D, H, W, C, half, st);
+    return launch_t<bf16_t, 2>(src, field, out, B, D, H, W, C, half, st);
+  }
   if (C % 4 == 0) return launch_t<float, 4>(src, field, out, B, D, H, W, C, half, st);
+  if (C % 2 == 0) return launch_t<float, 2>(src, field, out, B, D, H, W, C, half, st);
   return launch_t<float, 1>(src, field, out, B, D, H, W, C, half, st);
 }
 

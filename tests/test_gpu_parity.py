@@ -236,6 +236,10 @@ def test_errors_surface_as_exceptions(modet):
     (1, 6, 7, 9, 8, "f32", False), (2, 8, 10, 12, 8, "f32", True), (1, 5, 9, 33, 32, "f32", False),
     (1, 6, 8, 10, 3, "f32", False), (1, 6, 8, 10, 3, "f32", True), (1, 8, 6, 14, 16, "bf16", True),
     (1, 4, 5, 70, 16, "bf16", False), (1, 1, 1, 1, 4, "f32", False), (1, 2, 2, 2, 4, "f32", True),
+    # channel counts of the paper's head sizes (6 and 12 per head) and odd ones: narrower vectors per lane
+    (1, 6, 7, 19, 6, "f32", False), (1, 6, 8, 18, 6, "bf16", True), (2, 5, 7, 9, 12, "bf16", False),
+    (1, 6, 8, 10, 12, "f32", True), (1, 5, 6, 11, 5, "f32", False), (1, 4, 6, 8, 250, "f32", True),
+    (1, 4, 5, 7, 26, "bf16", False),
 ])
 def test_warp_matches_oracle(modet, B, D, H, W, C, dtype, half):
     src = synth.normal(61, 0, (B, D, H, W, C))

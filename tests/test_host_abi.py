@@ -95,7 +95,7 @@ def test_warp_rejects_bad_arguments(lib):
                                                                                        half, dt, None)
     assert w(src=None) == E_NULL and w(f=None) == E_NULL and w(out=None) == E_NULL
     assert w(D=0) == E_SHAPE and w(half=1, H=5) == E_SHAPE and w(half=2) == E_SHAPE
-    assert w(C=5) == E_UNSUP and w(C=4, dt=1) == E_UNSUP and w(dt=7) == E_UNSUP
+    assert w(C=5, dt=1) == E_UNSUP and w(C=260) == E_UNSUP and w(dt=7) == E_UNSUP
     assert w(out=ODD) == E_ALIGN
 
 
