@@ -30,8 +30,8 @@ def lib():
         build(force=False)
         _lib = ctypes.CDLL(LIB)
         for name in ("oracle_modet_fwd", "oracle_modet_bwd_scatter", "oracle_modet_bwd_gather",
-                     "oracle_modet_fwd_at", "oracle_modet_bwd_at", "oracle_warp", "oracle_upsample2x",
-                     "oracle_threads"):
+                     "oracle_modet_fwd_at", "oracle_modet_bwd_at", "oracle_warp", "oracle_warp_bwd",
+                     "oracle_upsample2x", "oracle_threads"):
             getattr(_lib, name).restype = _c_int
     return _lib
 
@@ -146,6 +146,27 @@ def warp(src, field, field_half_res=False, dtype="f32"):
     rc = lib().oracle_warp(_ptr(src), _ptr(field), B, D, H, W, C, int(bool(field_half_res)), _DT[dtype], _ptr(out))
     assert rc == 0
     return out
+
+
+def warp_bwd(src, field, dout, field_half_res=False, dtype="f32", want_dfield=True):
+    """Gradients of L = sum(dout * warp(src, field)): dsrc [B,D,H,W,C] and dfield (shape of field), float64.
+    The derivative with respect to a displacement is the one-sided (right) derivative where the sample point
+    sits exactly on a voxel."""
+    src = np.ascontiguousarray(src, dtype=_NP[dtype])
+    field = np.ascontiguousarray(field, dtype=np.float32)
+    dout = np.ascontiguousarray(dout, dtype=np.float64)
+    B, D, H, W, C = src.shape
+    assert dout.shape == src.shape
+    if field_half_res:
+        assert D % 2 == 0 and H % 2 == 0 and W % 2 == 0 and field.shape == (B, D // 2, H // 2, W // 2, 3)
+    else:
+        assert field.shape == (B, D, H, W, 3)
+    dsrc = np.empty(src.shape, dtype=np.float64)
+    dfield = np.empty(field.shape, dtype=np.float64) if want_dfield else None
+    rc = lib().oracle_warp_bwd(_ptr(src), _ptr(field), _ptr(dout), B, D, H, W, C, int(bool(field_half_res)),
+                               _DT[dtype], _ptr(dsrc), _ptr(dfield))
+    assert rc == 0
+    return (dsrc, dfield) if want_dfield else dsrc
 
 
 def upsample2x(coarse):

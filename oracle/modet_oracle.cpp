@@ -343,6 +343,74 @@ void warp_impl(const T* src, const float* field, int B, int D, int H, int W, int
         }
 }
 
+// Adjoint of the warp (derivative of L = sum(dout * warp(src, field)) with respect to src and to the field),
+// written as the transpose of sample_zero: every output voxel hands dout back to the corners it read, with
+// the weights it read them with; the derivative with respect to a displacement component differentiates
+// the weights (d/dt of t is +1 on the upper corner, of 1-t is -1 on the lower one).  A half-resolution field
+// receives the gradient of the displacement it was upsampled to, through the upsampling weights (x2).
+template <class T>
+void warp_bwd_impl(const T* src, const float* field, const double* dout, int B, int D, int H, int W, int C,
+                   int half, double* dsrc, double* dfield) {
+  int Dc = D / 2, Hc = H / 2, Wc = W / 2;
+  for (int64_t i = 0; i < (int64_t)B * D * H * W * C; ++i) dsrc[i] = 0.0;
+  if (dfield) {
+    int64_t n = half ? (int64_t)B * Dc * Hc * Wc * 3 : (int64_t)B * D * H * W * 3;
+    for (int64_t i = 0; i < n; ++i) dfield[i] = 0.0;
+  }
+  for (int b = 0; b < B; ++b)
+    for (int z = 0; z < D; ++z)
+      for (int y = 0; y < H; ++y)
+        for (int x = 0; x < W; ++x) {
+          double u[3];
+          int64_t p = (((int64_t)b * D + z) * H + y) * W + x;
+          const float* fc = field + (int64_t)b * Dc * Hc * Wc * 3;
+          if (half) upsampled_disp(fc, Dc, Hc, Wc, z, y, x, u);
+          else for (int a = 0; a < 3; ++a) u[a] = (double)field[p * 3 + a];
+          double cz = z + u[0], cy = y + u[1], cx = x + u[2];
+          double fz = std::floor(cz), fy = std::floor(cy), fx = std::floor(cx);
+          double tz = cz - fz, ty = cy - fy, tx = cx - fx;
+          double du[3] = {0.0, 0.0, 0.0};
+          const T* sb = src + (int64_t)b * D * H * W * C;
+          double* db = dsrc + (int64_t)b * D * H * W * C;
+          for (int dz = 0; dz < 2; ++dz)
+            for (int dy = 0; dy < 2; ++dy)
+              for (int dx = 0; dx < 2; ++dx) {
+                double zz = fz + dz, yy = fy + dy, xx = fx + dx;
+                if (zz < 0 || zz > D - 1 || yy < 0 || yy > H - 1 || xx < 0 || xx > W - 1) continue;
+                double wz = dz ? tz : 1.0 - tz, wy = dy ? ty : 1.0 - ty, wx = dx ? tx : 1.0 - tx;
+                int64_t q = (((int64_t)zz * H + (int64_t)yy) * W + (int64_t)xx) * C;
+                double dot = 0.0;
+                for (int c = 0; c < C; ++c) {
+                  db[q + c] += wz * wy * wx * dout[p * C + c];
+                  dot += dout[p * C + c] * widen(sb[q + c]);
+                }
+                du[0] += (dz ? 1.0 : -1.0) * wy * wx * dot;
+                du[1] += wz * (dy ? 1.0 : -1.0) * wx * dot;
+                du[2] += wz * wy * (dx ? 1.0 : -1.0) * dot;
+              }
+          if (!dfield) continue;
+          if (!half) {
+            for (int a = 0; a < 3; ++a) dfield[p * 3 + a] = du[a];
+            continue;
+          }
+          // u = 2 * sum_corners W * fc[corner] at the clamped coarse coordinate of this fine voxel
+          double gz = clampd((z + 0.5) / 2.0 - 0.5, 0.0, Dc - 1.0), gy = clampd((y + 0.5) / 2.0 - 0.5, 0.0, Hc - 1.0);
+          double gx = clampd((x + 0.5) / 2.0 - 0.5, 0.0, Wc - 1.0);
+          double ez = std::floor(gz), ey = std::floor(gy), ex = std::floor(gx);
+          double sz = gz - ez, sy = gy - ey, sx = gx - ex;
+          double* dc = dfield + (int64_t)b * Dc * Hc * Wc * 3;
+          for (int dz = 0; dz < 2; ++dz)
+            for (int dy = 0; dy < 2; ++dy)
+              for (int dx = 0; dx < 2; ++dx) {
+                double zz = ez + dz, yy = ey + dy, xx = ex + dx;
+                if (zz > Dc - 1 || yy > Hc - 1 || xx > Wc - 1) continue;
+                double wgt = (dz ? sz : 1.0 - sz) * (dy ? sy : 1.0 - sy) * (dx ? sx : 1.0 - sx);
+                int64_t q = (((int64_t)zz * Hc + (int64_t)yy) * Wc + (int64_t)xx) * 3;
+                for (int a = 0; a < 3; ++a) dc[q + a] += 2.0 * wgt * du[a];
+              }
+        }
+}
+
 }  // namespace
 
 #define DISPATCH(dtype, CALL)                                            \
@@ -392,6 +460,11 @@ int oracle_modet_bwd_at(const void* Q, const void* K, const double* bias, const 
 int oracle_warp(const void* src, const float* field, int B, int D, int H, int W, int C, int field_half_res,
                 int dtype, double* out) {
   DISPATCH(dtype, warp_impl<T>((const T*)src, field, B, D, H, W, C, field_half_res, out));
+}
+
+int oracle_warp_bwd(const void* src, const float* field, const double* dout, int B, int D, int H, int W, int C,
+                    int field_half_res, int dtype, double* dsrc, double* dfield) {
+  DISPATCH(dtype, warp_bwd_impl<T>((const T*)src, field, dout, B, D, H, W, C, field_half_res, dsrc, dfield));
 }
 
 // the 2x upsampled, x2 scaled field on its own: fine [B,D,H,W,3] from coarse [B,D/2,H/2,W/2,3].
