@@ -108,6 +108,27 @@ int modet_warp(const void* src, const float* field, void* out,
                int B, int D, int H, int W, int C, int field_half_res,
                modet_dtype dtype, void* stream);
 
+/* Adjoint of modet_warp: the gradients of L = sum(dout * warp(src, field)), which carry a gradient with
+ * respect to the warped moving features (modet_bwd's dK) back to the un-warped features and to the field
+ * (paper Section 3.1: the warp sits between the pyramid levels, in front of the operator).
+ *
+ *   dsrc[b, q, c]   = sum over voxels p of weight(p -> q) * dout[b, p, c]     (transpose of the gather)
+ *   dfield          = derivative through the interpolation weights; where a sample point sits exactly on
+ *                     a voxel it is the one-sided derivative towards larger displacements.  For
+ *                     field_half_res == 1 it has the coarse field's shape (the 2x upsampling is
+ *                     differentiated too).
+ *   src     in   dtype; only read for dfield (may be NULL when dfield is NULL)
+ *   field   in   as in modet_warp
+ *   dout    in   fp32 [B, D, H, W, C]
+ *   dsrc    out  fp32 [B, D, H, W, C], fully overwritten: zeroed, then accumulated with fp32 atomics, so the
+ *                last bits depend on the order of the additions
+ *   dfield  out  nullable, fp32, fully overwritten
+ *   shapes and dtypes as in modet_warp
+ */
+int modet_warp_bwd(const void* src, const float* field, const float* dout, float* dsrc, float* dfield,
+                   int B, int D, int H, int W, int C, int field_half_res,
+                   modet_dtype dtype, void* stream);
+
 /* Composition of two displacement fields: paper Section 3.1 (the total field of a pyramid level is
  * the level's residual field composed with the upsampled total field of the level below).
  *

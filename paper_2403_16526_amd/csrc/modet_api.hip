@@ -136,6 +136,23 @@ int modet_warp(const void* src, const float* field, void* out,
   return e == hipSuccess ? MODET_OK : MODET_ERR_LAUNCH;
 }
 
+int modet_warp_bwd(const void* src, const float* field, const float* dout, float* dsrc, float* dfield,
+                   int B, int D, int H, int W, int C, int field_half_res, modet_dtype dtype, void* stream) {
+  if (!field || !dout || !dsrc || (dfield && !src)) return MODET_ERR_NULL;
+  if (B < 1 || D < 1 || H < 1 || W < 1 || C < 1) return MODET_ERR_SHAPE;
+  if (field_half_res != 0 && field_half_res != 1) return MODET_ERR_SHAPE;
+  if (field_half_res && ((D | H | W) & 1)) return MODET_ERR_SHAPE;
+  if (dtype != MODET_F32 && dtype != MODET_BF16) return MODET_ERR_UNSUPPORTED;
+  if (dtype == MODET_BF16 && (C & 1)) return MODET_ERR_UNSUPPORTED;
+  if (C > 256) return MODET_ERR_UNSUPPORTED;
+  if ((long long)B * D * H * W * C >= (1LL << 31)) return MODET_ERR_UNSUPPORTED;
+  if (misaligned(src) || misaligned(field) || misaligned(dout) || misaligned(dsrc) || misaligned(dfield))
+    return MODET_ERR_ALIGN;
+  hipError_t e = launch_warp_bwd(src, field, dout, dsrc, dfield, B, D, H, W, C, field_half_res, (int)dtype,
+                                 (hipStream_t)stream);
+  return e == hipSuccess ? MODET_OK : MODET_ERR_LAUNCH;
+}
+
 int modet_compose(const float* outer, const float* inner, float* out, int B, int D, int H, int W, void* stream) {
   if (!outer || !inner || !out) return MODET_ERR_NULL;
   if (B < 1 || D < 1 || H < 1 || W < 1) return MODET_ERR_SHAPE;

@@ -41,6 +41,9 @@ hipError_t launch_dbias_generic(const Geo& g, int dtype, const void* Q, const vo
 hipError_t launch_dbias_end(const Geo& g, const double* acc, float* dbias, hipStream_t st);
 hipError_t launch_warp(const void* src, const float* field, void* out, int B, int D, int H, int W, int C,
                        int half, int dtype, hipStream_t st);
+// gradients of sum(dout * warp(src, field)): dsrc [B, D, H, W, C] fp32, dfield (nullable) in the shape of field
+hipError_t launch_warp_bwd(const void* src, const float* field, const float* dout, float* dsrc, float* dfield, int B,
+                           int D, int H, int W, int C, int half, int dtype, hipStream_t st);
 // out = s * (inner + trilinear(outer, p + s * inner)); fields [B, D, H, W, 3] fp32
 hipError_t launch_compose(const float* outer, const float* inner, float* out, int B, int D, int H, int W, float s,
                           hipStream_t st);

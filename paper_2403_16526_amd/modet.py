@@ -18,7 +18,7 @@ LIB_PATH = os.environ.get("MODET_LIBRARY") or os.path.join(_HERE, "libmodet.so")
 MODET_F32, MODET_BF16 = 0, 1
 MODET_OK = 0
 
-EXPORTS = ("modet_fwd", "modet_bwd", "modet_bwd_workspace_bytes", "modet_warp", "modet_compose",
+EXPORTS = ("modet_fwd", "modet_bwd", "modet_bwd_workspace_bytes", "modet_warp", "modet_warp_bwd", "modet_compose",
            "modet_integrate_velocity", "modet_set_kernel_path", "modet_set_math_mode",
            "modet_has_tiled_kernels", "modet_status_string", "modet_version")
 
@@ -35,6 +35,8 @@ _lib.modet_bwd.restype = _ci
 _lib.modet_bwd_workspace_bytes.argtypes = [_ci] * 7 + [_ci, _ci]
 _lib.modet_bwd_workspace_bytes.restype = _sz
 _lib.modet_warp.argtypes = [_vp] * 3 + [_ci] * 5 + [_ci, _ci, _vp]
+_lib.modet_warp_bwd.restype = _ci
+_lib.modet_warp_bwd.argtypes = [_vp] * 5 + [_ci] * 5 + [_ci, _ci, _vp]
 _lib.modet_compose.restype = _ci
 _lib.modet_compose.argtypes = [_vp] * 3 + [_ci] * 4 + [_vp]
 _lib.modet_integrate_velocity.restype = _ci
@@ -167,6 +169,18 @@ def modet_warp(src, field, field_half_res: bool = False, out=None):
     _check(_lib.modet_warp(_ptr(src), _ptr(field), _ptr(out), B, D, H, W, C, int(bool(field_half_res)),
                            _in_dtype(src), _stream()))
     return out
+
+
+def modet_warp_bwd(src, field, dout, field_half_res: bool = False, want_dfield: bool = True, out=None):
+    """Gradients of sum(dout * modet_warp(src, field)): dsrc [B,D,H,W,C] fp32 (+ dfield, shaped like field)."""
+    _dev(src, field, dout)
+    B, D, H, W, C = src.shape
+    f32 = dict(device=src.device, dtype=torch.float32)
+    dsrc = out if out is not None else torch.empty(src.shape, **f32)
+    dfield = torch.empty(field.shape, **f32) if want_dfield else None
+    _check(_lib.modet_warp_bwd(_ptr(src), _ptr(field), _ptr(dout), _ptr(dsrc), _ptr(dfield), B, D, H, W, C,
+                               int(bool(field_half_res)), _in_dtype(src), _stream()))
+    return (dsrc, dfield) if want_dfield else dsrc
 
 
 def modet_compose(outer, inner, out=None):

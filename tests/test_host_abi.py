@@ -22,6 +22,7 @@ def lib():
     L.modet_bwd.argtypes = [vp] * 9 + [ci] * 7 + [cf, ci, vp, sz, vp]
     L.modet_warp.argtypes = [vp] * 3 + [ci] * 5 + [ci, ci, vp]
     L.modet_compose.argtypes = [vp] * 3 + [ci] * 4 + [vp]
+    L.modet_warp_bwd.argtypes = [vp] * 5 + [ci] * 5 + [ci, ci, vp]
     L.modet_integrate_velocity.argtypes = [vp] * 3 + [ci] * 5 + [vp]
     L.modet_bwd_workspace_bytes.argtypes = [ci] * 9
     L.modet_bwd_workspace_bytes.restype = sz
@@ -97,6 +98,16 @@ def test_warp_rejects_bad_arguments(lib):
     assert w(D=0) == E_SHAPE and w(half=1, H=5) == E_SHAPE and w(half=2) == E_SHAPE
     assert w(C=5, dt=1) == E_UNSUP and w(C=260) == E_UNSUP and w(dt=7) == E_UNSUP
     assert w(out=ODD) == E_ALIGN
+
+
+def test_warp_bwd_rejects_bad_arguments(lib):
+    wb = lambda src=P, f=P, g=P, ds=P, df=P, B=1, D=4, H=4, W=4, C=8, half=0, dt=0: lib.modet_warp_bwd(
+        src, f, g, ds, df, B, D, H, W, C, half, dt, None)
+    assert wb(f=None) == E_NULL and wb(g=None) == E_NULL and wb(ds=None) == E_NULL
+    assert wb(src=None) == E_NULL            # the field gradient needs the source values
+    assert wb(W=0) == E_SHAPE and wb(half=1, D=5) == E_SHAPE and wb(half=3) == E_SHAPE
+    assert wb(C=7, dt=1) == E_UNSUP and wb(C=300) == E_UNSUP and wb(dt=2) == E_UNSUP
+    assert wb(df=ODD) == E_ALIGN and wb(g=ODD) == E_ALIGN
 
 
 def test_field_functions_reject_bad_arguments(lib):
