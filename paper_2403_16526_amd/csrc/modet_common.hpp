@@ -68,6 +68,8 @@ hipError_t launch_bwd_tiled_plain(const Geo& g, int dtype, bool fast_logits, con
                                   bool* dbias_done);
 hipError_t launch_bwd_tiled_biased(const Geo& g, int dtype, bool fast_logits, const BwdTensors& io, hipStream_t st,
                                    bool* dbias_done);
+hipError_t launch_bwd_tiled_biased_many(const Geo& g, int dtype, bool fast_logits, const BwdTensors& io,
+                                        hipStream_t st, bool* dbias_done);
 // heads of six channels
 hipError_t launch_fwd_tiled_d6(const Geo& g, int dtype, const void* Q, const void* K, const float* bias,
                                float* phi, float* lse, hipStream_t st);

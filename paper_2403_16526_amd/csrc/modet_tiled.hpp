@@ -638,9 +638,18 @@ struct DqPolicy {
     s.g0 = a4.y; s.g1 = a4.z; s.g2 = a4.w;
     s.ngphi = sc[pos];
   }
-  template <int PH, bool FULL>
-  static __device__ __forceinline__ void step(State (&st)[KW], const typename Lds<ET>::chunk* kb, const float4*,
-                                              const float*, int lbase, unsigned active, const LT* bl) {
+  // One step: for every in-plane offset (b, c) the K vector is read once and every active role i (plane
+  // offset a = R - i) gets its pair: w = exp2(logit - lse), dl = w * (g.o - g.phi), dQ += dl * K.  What else
+  // happens to dl is the sink's business: sink.begin(b, c) runs before the dot products of an in-plane offset,
+  // sink.pair(i, b, c, dl) after each of them, sink.idle(i, b, c) for a role that is not active.
+  struct NoSink {
+    __device__ __forceinline__ void begin(int, int) {}
+    __device__ __forceinline__ void pair(int, int, int, float) {}
+    __device__ __forceinline__ void idle(int, int, int) {}
+  };
+  template <int PH, bool FULL, class Sink>
+  static __device__ __forceinline__ void pairs(State (&st)[KW], const typename Lds<ET>::chunk* kb, int lbase,
+                                               unsigned active, const LT* bl, Sink& sink) {
 #pragma unroll
     for (int b = 0; b < KW; ++b)
 #pragma unroll
@@ -649,8 +658,9 @@ struct DqPolicy {
         Lds<ET>::get8(kb, P::NPOS, lbase + b * P::PC + c * HS, kf);
         LT kv[8];
         widen8<LT, float>(kf, kv);
+        sink.begin(b, c);
 #pragma unroll
-        for (int i = 0; i < KW; ++i)
+        for (int i = 0; i < KW; ++i) {
           if (FULL || (active & (1u << i))) {
             State& s = st[(i + PH) % KW];
             LT init = s.nlse;
@@ -661,79 +671,62 @@ struct DqPolicy {
             if (R - i != 0) tt = fmaf((float)(R - i), s.g0, tt);
             if (b - R != 0) tt = fmaf((float)(b - R), s.g1, tt);
             if (c - R != 0) tt = fmaf((float)(c - R), s.g2, tt);
-            axpy8(s.acc, w * tt, kf);
-          }
-      }
-  }
-  // the same step, also adding dl of every (role, offset) to this lane's running sums for the bias gradient:
-  // sums[(((a+R)*KW + b+R)*KW + c+R) * NT] is a lane-private column of an LDS array: a plain read, add and
-  // write (nobody else touches the address; LDS atomics are an order of magnitude slower).  The three sums of
-  // an in-plane offset are read before its dot products and written after them.
-  template <int PH, bool FULL>
-  static __device__ __forceinline__ void step_sum(State (&st)[KW], const typename Lds<ET>::chunk* kb, int lbase,
-                                                  unsigned active, const LT* bl, float* sums) {
-#pragma unroll
-    for (int b = 0; b < KW; ++b)
-#pragma unroll
-      for (int c = 0; c < KW; ++c) {
-        float kf[8];
-        Lds<ET>::get8(kb, P::NPOS, lbase + b * P::PC + c * HS, kf);
-        LT kv[8];
-        widen8<LT, float>(kf, kv);
-        float run[KW];
-#pragma unroll
-        for (int i = 0; i < KW; ++i) run[i] = sums[(((KW - 1 - i) * KW + b) * KW + c) * NT];
-#pragma unroll
-        for (int i = 0; i < KW; ++i)
-          if (FULL || (active & (1u << i))) {
-            State& s = st[(i + PH) % KW];
-            LT init = s.nlse;
-            if (BIAS) init += bl[(((KW - 1 - i) * KW + b) * KW + c) * HS];
-            const float w = exp2_fast((float)whole_logit<T, LT>(dot8<LT>(s.q, kv, init)));
-            float tt = s.ngphi;
-            if (R - i != 0) tt = fmaf((float)(R - i), s.g0, tt);
-            if (b - R != 0) tt = fmaf((float)(b - R), s.g1, tt);
-            if (c - R != 0) tt = fmaf((float)(c - R), s.g2, tt);
             const float dl = w * tt;
             axpy8(s.acc, dl, kf);
-            sums[(((KW - 1 - i) * KW + b) * KW + c) * NT] = run[i] + dl;
-          }
-      }
-  }
-  // the same step, also handing dl of every (role, offset) to the key side:
-  // dl_out[(a+R) * DLA + ((b+R)*KW + c+R) * NT + li], a = R - i the plane offset of role i; roles that are not
-  // active emit 0
-  template <int PH, bool FULL, int DLA>
-  static __device__ __forceinline__ void step_emit(State (&st)[KW], const typename Lds<ET>::chunk* kb, int lbase,
-                                                   unsigned active, float* dl_out, int li, const LT* bl) {
-#pragma unroll
-    for (int b = 0; b < KW; ++b)
-#pragma unroll
-      for (int c = 0; c < KW; ++c) {
-        float kf[8];
-        Lds<ET>::get8(kb, P::NPOS, lbase + b * P::PC + c * HS, kf);
-        LT kv[8];
-        widen8<LT, float>(kf, kv);
-#pragma unroll
-        for (int i = 0; i < KW; ++i) {
-          const int j = (KW - 1 - i) * DLA + (b * KW + c) * NT;      // a + R = R - i + R = KW - 1 - i
-          if (FULL || (active & (1u << i))) {
-            State& s = st[(i + PH) % KW];
-            LT init = s.nlse;
-            if (BIAS) init += bl[(((KW - 1 - i) * KW + b) * KW + c) * HS];
-            const float w = exp2_fast((float)whole_logit<T, LT>(dot8<LT>(s.q, kv, init)));
-            float tt = s.ngphi;
-            if (R - i != 0) tt = fmaf((float)(R - i), s.g0, tt);
-            if (b - R != 0) tt = fmaf((float)(b - R), s.g1, tt);
-            if (c - R != 0) tt = fmaf((float)(c - R), s.g2, tt);
-            const float dl = w * tt;
-            axpy8(s.acc, dl, kf);
-            dl_out[j + li] = dl;
+            sink.pair(i, b, c, dl);
           } else {
-            dl_out[j + li] = 0.f;
+            sink.idle(i, b, c);
           }
         }
       }
+  }
+  template <int PH, bool FULL>
+  static __device__ __forceinline__ void step(State (&st)[KW], const typename Lds<ET>::chunk* kb, const float4*,
+                                              const float*, int lbase, unsigned active, const LT* bl) {
+    NoSink sink;
+    pairs<PH, FULL>(st, kb, lbase, active, bl, sink);
+  }
+  // The same step, also adding dl of every (role, offset) to this lane's running sums for the bias gradient:
+  // sums[(((a+R)*KW + b+R)*KW + c+R) * NT] is a lane-private column of an LDS array: a plain read, add and
+  // write (nobody else touches the address; LDS atomics are an order of magnitude slower).  The sums of an
+  // in-plane offset are read before its dot products and written after them.
+  struct SumSink {
+    float* sums;
+    float run[KW];
+    __device__ __forceinline__ void begin(int b, int c) {
+#pragma unroll
+      for (int i = 0; i < KW; ++i) run[i] = sums[(((KW - 1 - i) * KW + b) * KW + c) * NT];
+    }
+    __device__ __forceinline__ void pair(int i, int b, int c, float dl) {
+      sums[(((KW - 1 - i) * KW + b) * KW + c) * NT] = run[i] + dl;
+    }
+    __device__ __forceinline__ void idle(int, int, int) {}
+  };
+  template <int PH, bool FULL>
+  static __device__ __forceinline__ void step_sum(State (&st)[KW], const typename Lds<ET>::chunk* kb, int lbase,
+                                                  unsigned active, const LT* bl, float* sums) {
+    SumSink sink;
+    sink.sums = sums;
+    pairs<PH, FULL>(st, kb, lbase, active, bl, sink);
+  }
+  // The same step, also handing dl of every (role, offset) to the key side:
+  // dl_out[(a+R) * DLA + ((b+R)*KW + c+R) * NT + li], a = R - i the plane offset of role i; roles that are not
+  // active emit 0.
+  template <int DLA>
+  struct EmitSink {
+    float* out;      // dl_out + li
+    __device__ __forceinline__ void begin(int, int) {}
+    __device__ __forceinline__ void pair(int i, int b, int c, float dl) {
+      out[(KW - 1 - i) * DLA + (b * KW + c) * NT] = dl;      // a + R = R - i + R = KW - 1 - i
+    }
+    __device__ __forceinline__ void idle(int i, int b, int c) { out[(KW - 1 - i) * DLA + (b * KW + c) * NT] = 0.f; }
+  };
+  template <int PH, bool FULL, int DLA>
+  static __device__ __forceinline__ void step_emit(State (&st)[KW], const typename Lds<ET>::chunk* kb, int lbase,
+                                                   unsigned active, float* dl_out, int li, const LT* bl) {
+    EmitSink<DLA> sink;
+    sink.out = dl_out + li;
+    pairs<PH, FULL>(st, kb, lbase, active, bl, sink);
   }
   static __device__ __forceinline__ void store(const State& s, const TiledParams& p, long long w) {
     store_col_scaled<Mem<T>::CH>(p.out, w, s.acc, p.scale);
@@ -1635,35 +1628,50 @@ void launch_march(const Geo& g, TiledParams io, hipStream_t st) {
 }  // namespace
 }  // namespace modet
 
-// calls CALL(KW, HS, T, LT) for the instantiation that covers (g.k, g.heads, dtype, fast_logits)
-#define MODET_DISPATCH(CALL)                                                     \
+// calls CALL(KW, HS, T, LT) for the instantiation that covers (g.k, g.heads, dtype, fast_logits); the two halves
+// (one or two heads and k = 5; four or eight heads) can be instantiated in different translation units
+#define MODET_DISPATCH_FEW(CALL)                                                 \
   if (g.k == 3 && dtype == 0 && fast_logits) {                                   \
     switch (g.heads) {                                                           \
       case 1: return CALL(3, 1, float, float);                                   \
       case 2: return CALL(3, 2, float, float);                                   \
-      case 4: return CALL(3, 4, float, float);                                   \
-      case 8: return CALL(3, 8, float, float);                                   \
     }                                                                            \
   } else if (g.k == 3 && dtype == 0) {                                           \
     switch (g.heads) {                                                           \
       case 1: return CALL(3, 1, float, double);                                  \
       case 2: return CALL(3, 2, float, double);                                  \
-      case 4: return CALL(3, 4, float, double);                                  \
-      case 8: return CALL(3, 8, float, double);                                  \
     }                                                                            \
   } else if (g.k == 3) {                                                         \
     switch (g.heads) {                                                           \
       case 1: return CALL(3, 1, bf16_t, float);                                  \
       case 2: return CALL(3, 2, bf16_t, float);                                  \
-      case 4: return CALL(3, 4, bf16_t, float);                                  \
-      case 8: return CALL(3, 8, bf16_t, float);                                  \
     }                                                                            \
   } else if (g.k == 5 && dtype == 1) {                                           \
     switch (g.heads) {                                                           \
       case 1: return CALL(5, 1, bf16_t, float);                                  \
       case 2: return CALL(5, 2, bf16_t, float);                                  \
     }                                                                            \
-  }                                                                              \
+  }
+#define MODET_DISPATCH_MANY(CALL)                                                \
+  if (g.k == 3 && dtype == 0 && fast_logits) {                                   \
+    switch (g.heads) {                                                           \
+      case 4: return CALL(3, 4, float, float);                                   \
+      case 8: return CALL(3, 8, float, float);                                   \
+    }                                                                            \
+  } else if (g.k == 3 && dtype == 0) {                                           \
+    switch (g.heads) {                                                           \
+      case 4: return CALL(3, 4, float, double);                                  \
+      case 8: return CALL(3, 8, float, double);                                  \
+    }                                                                            \
+  } else if (g.k == 3) {                                                         \
+    switch (g.heads) {                                                           \
+      case 4: return CALL(3, 4, bf16_t, float);                                  \
+      case 8: return CALL(3, 8, bf16_t, float);                                  \
+    }                                                                            \
+  }
+#define MODET_DISPATCH(CALL)                                                     \
+  MODET_DISPATCH_FEW(CALL)                                                       \
+  MODET_DISPATCH_MANY(CALL)                                                      \
   return hipErrorNotSupported;
 
 // the same for heads of six channels (k = 3; fp64 logits for fp32 inputs whatever the math mode)
