@@ -182,6 +182,38 @@ __device__ __forceinline__ double partner(double x) {
   const int hi = __builtin_amdgcn_mov_dpp(__double2hiint(x), 0xB1, 0xF, 0xF, true);
   return __hiloint2double(hi, lo);
 }
+// x + (x moved across lanes by a DPP control), lanes outside the row / bank masks add 0
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_add(float x) {
+  return x + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, ROW_MASK, 0xF, true));
+}
+// Sum of x over the wave's 64 lanes, valid in lane 63.  STEP = 1: an inclusive scan inside each row of 16 lanes
+// (shifts by 1, 2, 4, 8), then row 0's total into row 1 and row 2's into row 3 (broadcast of lane 15), then
+// lane 31's into rows 2 and 3.  STEP = 2 leaves out the shift by 1: the last two lanes of a row then hold the
+// sums of the row's even and of its odd lanes.
+template <int STEP>
+__device__ __forceinline__ float row_scan(float x) {
+  if (STEP == 1) x = dpp_add<0x111, 0xF>(x);      // row_shr:1
+  x = dpp_add<0x112, 0xF>(x);                     // row_shr:2
+  x = dpp_add<0x114, 0xF>(x);                     // row_shr:4
+  x = dpp_add<0x118, 0xF>(x);                     // row_shr:8
+  return x;
+}
+__device__ __forceinline__ float across_rows(float x) {
+  x = dpp_add<0x142, 0xA>(x);                     // row_bcast:15 into rows 1 and 3
+  x = dpp_add<0x143, 0xC>(x);                     // row_bcast:31 into rows 2 and 3
+  return x;
+}
+template <int STEP>
+__device__ __forceinline__ float wave_sum_to_last_lane(float x) { return across_rows(row_scan<STEP>(x)); }
+// sums over the even and over the odd lanes, both valid in lane 63
+__device__ __forceinline__ void wave_sums_by_parity(float x, float& even, float& odd) {
+  const float s = row_scan<2>(x);                 // lane 14 / 15 of a row: the row's even / odd lanes
+  odd = across_rows(s);
+  // move every row's lane 14 to its lane 15, then the same two steps
+  even = across_rows(__int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(s), 0x111, 0xF, 0xF, true)));
+}
+
 // a logit from this lane's partial sum
 template <class T, class LT>
 __device__ __forceinline__ LT whole_logit(LT part) {
@@ -476,6 +508,7 @@ struct FwdPolicy {
   typedef LT ET;                           // LDS element type: no conversions in the inner loop
   typedef Patch<KW, HS> P;
   static constexpr bool kStats = false;
+  static constexpr bool kWaveSums = false;
   struct State {
     LT q[8];            // Q * scale * log2e
     LT nref;            // minus the reference (log2 units) times Win<T>::kShare; the dot products start from it
@@ -580,7 +613,7 @@ struct FwdPolicy {
 };
 
 // ---- backward, dQ: lane owns a query column; K planes in LDS (fp32); w = exp(l - lse) ----------------
-template <int KW_, int HS_, class T_, class LT, bool BIAS = false>
+template <int KW_, int HS_, class T_, class LT, bool BIAS = false, bool SUMS = false>
 struct DqPolicy {
   static constexpr int KW = KW_, HS = HS_, R = KW_ / 2;
   static constexpr bool kBias = BIAS;
@@ -590,6 +623,8 @@ struct DqPolicy {
   typedef float ET;                        // the fp32 copy is needed for the fp32 accumulation anyway
   typedef Patch<KW, HS> P;
   static constexpr bool kStats = false;
+  static constexpr bool kWaveSums = SUMS;      // this march also sums dl for the bias gradient: see WaveSumSink
+  static_assert(!SUMS || (BIAS && !Mem<T_>::PAIR), "the sums come with the bias variant, one lane per window");
   struct State {
     LT q[8];          // Q * scale * log2e
     LT nlse;          // -lse * log2e * Win<T>::kShare
@@ -709,6 +744,42 @@ struct DqPolicy {
     sink.sums = sums;
     pairs<PH, FULL>(st, kb, lbase, active, bl, sink);
   }
+  // The same step for a march that has no room for per-lane sums (k = 5: 125 offsets): every dl is summed across
+  // the wave right away with data-parallel-primitive moves (no LDS traffic, no waits, no branches), per head.  The
+  // wave's total of entry e = o * HS + head is kept in lane e % 64 of register e / 64 of `acc` (the total is read
+  // from lane 63 into a scalar and added under a one-lane mask).  `keep` is false for lanes that compute on a
+  // clamped column outside the volume.
+  static constexpr int kWaveAcc = SUMS ? (KW * KW * KW * HS + 63) / 64 : 1;
+  struct WaveSumSink {
+    float (&acc)[kWaveAcc];
+    int lane;
+    bool keep;
+    static_assert(HS <= 2, "the wave sums are written for one or two heads");
+    __device__ __forceinline__ void add(int e, float total_in_last_lane) {
+      const float t = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(total_in_last_lane), 63));
+      acc[e / 64] += lane == e % 64 ? t : 0.f;
+    }
+    __device__ __forceinline__ void begin(int, int) {}
+    __device__ __forceinline__ void pair(int i, int b, int c, float dl) {
+      const float v = keep ? dl : 0.f;
+      const int e = (((KW - 1 - i) * KW + b) * KW + c) * HS;
+      if (HS == 1) {
+        add(e, wave_sum_to_last_lane<1>(v));
+      } else {            // lanes alternate between the two heads
+        float even, odd;
+        wave_sums_by_parity(v, even, odd);
+        add(e, even);
+        add(e + 1, odd);
+      }
+    }
+    __device__ __forceinline__ void idle(int, int, int) {}
+  };
+  template <int PH, bool FULL>
+  static __device__ __forceinline__ void step_wavesum(State (&st)[KW], const typename Lds<ET>::chunk* kb, int lbase,
+                                                      unsigned active, const LT* bl, float (&acc)[kWaveAcc], bool keep) {
+    WaveSumSink sink = {acc, (int)(threadIdx.x & 63), keep};
+    pairs<PH, FULL>(st, kb, lbase, active, bl, sink);
+  }
   // The same step, also handing dl of every (role, offset) to the key side:
   // dl_out[(a+R) * DLA + ((b+R)*KW + c+R) * NT + li], a = R - i the plane offset of role i; roles that are not
   // active emit 0.
@@ -746,6 +817,7 @@ struct DkPolicy {
   typedef float ET;
   typedef Patch<KW, HS> P;
   static constexpr bool kStats = true;
+  static constexpr bool kWaveSums = false;
   struct State {
     LT k[8];          // K * scale * log2e
     float acc[8];
@@ -813,6 +885,8 @@ template <class Pol, bool STATS> struct SharedPlanes;
 template <class Pol> struct SharedPlanes<Pol, false> {
   typename Lds<typename Pol::ET>::chunk main[2][Lds<typename Pol::ET>::CH * Pol::P::NPOS];
   BiasTable<typename Pol::Logit, Pol::KW, Pol::HS, Pol::kBias> bias;
+  // per wave: sums of dl per (window offset, head), for the bias gradient of a dQ march (WaveSumSink)
+  float wsum[Pol::kWaveSums ? (NT / 64) * Pol::KW * Pol::KW * Pol::KW * Pol::HS : 1];
 };
 template <class Pol> struct SharedPlanes<Pol, true> {
   typename Lds<typename Pol::ET>::chunk main[2][Lds<typename Pol::ET>::CH * Pol::P::NPOS];
@@ -827,18 +901,31 @@ __device__ __forceinline__ const typename Pol::Logit* lane_bias(const Sh& sh, in
   else return nullptr;
 }
 
+// per-lane registers of a march that sums dl across its waves (one dummy register otherwise)
+template <class Pol, bool ON = Pol::kWaveSums> struct WaveAcc { float v[1]; };
+template <class Pol> struct WaveAcc<Pol, true> { float v[Pol::kWaveAcc]; };
+
 template <class Pol, int PH, class Sh, class Stg, class SStg>
 __device__ __forceinline__ void march_body(typename Pol::State (&st)[Pol::KW], const TiledParams& p, const Tile& t,
                                            Sh& sh, int cur, int lbase, int s, typename Pol::Pre& pre,
-                                           bool have_next, bool commit_next, const Stg& stg, const SStg& sst) {
+                                           bool have_next, bool commit_next, const Stg& stg, const SStg& sst,
+                                           WaveAcc<Pol>& wacc) {
   constexpr int KW = Pol::KW, R = KW / 2;
   const unsigned active = active_roles<KW>(s, t.z0, t.z1);
   const float4* sa = nullptr;
   const float* sc = nullptr;
   if constexpr (Pol::kStats) { sa = sh.sa[cur]; sc = sh.sc[cur]; }
   const typename Pol::Logit* bl = lane_bias<Pol>(sh, t.xs);
-  if (active == (1u << KW) - 1u) Pol::template step<PH, true>(st, sh.main[cur], sa, sc, lbase, active, bl);
-  else Pol::template step<PH, false>(st, sh.main[cur], sa, sc, lbase, active, bl);
+  if constexpr (Pol::kWaveSums) {      // a dQ march that also sums its dl for the bias gradient
+    // (even lanes of a wave hold head 0, odd lanes head 1: tile origins are multiples of 32 columns)
+    if (active == (1u << KW) - 1u)
+      Pol::template step_wavesum<PH, true>(st, sh.main[cur], lbase, active, bl, wacc.v, t.lane_ok);
+    else
+      Pol::template step_wavesum<PH, false>(st, sh.main[cur], lbase, active, bl, wacc.v, t.lane_ok);
+  } else {
+    if (active == (1u << KW) - 1u) Pol::template step<PH, true>(st, sh.main[cur], sa, sc, lbase, active, bl);
+    else Pol::template step<PH, false>(st, sh.main[cur], sa, sc, lbase, active, bl);
+  }
   // the staged plane goes to LDS before the results are stored: the wait for its loads would otherwise
   // also wait for those stores (one counter covers loads and stores on this chip)
   if (commit_next) {
@@ -903,6 +990,9 @@ __device__ __forceinline__ void march(const TiledParams& p, unsigned id, void* s
     if constexpr (Pol::kStats) sst.zero_outside(sh.sa[j], sh.sc[j]);
   }
   if constexpr (Pol::kBias) fill_bias_table<T, typename Pol::Logit, KW, HS>(sh.bias.v, p.bias, threadIdx.x, NT);
+  WaveAcc<Pol> wacc;
+#pragma unroll
+  for (int r = 0; r < (int)(sizeof(wacc.v) / sizeof(float)); ++r) wacc.v[r] = 0.f;
 
   typename Pol::State st[KW];
 #pragma unroll
@@ -943,7 +1033,7 @@ __device__ __forceinline__ void march(const TiledParams& p, unsigned id, void* s
     const int cur = (s - s_first) & 1;
     const bool commit_next = s + 1 <= s_last;
     const bool have_next = s + R + 1 < t.z1;
-    march_body<Pol, PH>(st, p, t, sh, cur, lbase, s, pre, have_next, commit_next, stg, sst);
+    march_body<Pol, PH>(st, p, t, sh, cur, lbase, s, pre, have_next, commit_next, stg, sst, wacc);
     if (!ROT) {
       // rotate by moving: role i+1 becomes role i, the refilled slot 0 becomes role KW-1
       typename Pol::State tmp = st[0];
@@ -965,6 +1055,21 @@ __device__ __forceinline__ void march(const TiledParams& p, unsigned id, void* s
     }
   } else {
     for (int s = s_first; s <= s_last; ++s) one_step(std::integral_constant<int, 0>(), s);
+  }
+  if constexpr (Pol::kWaveSums) {      // every wave's totals go to its row of the LDS table, then the rows are folded
+    constexpr int K3 = KW * KW * KW;
+#pragma unroll
+    for (int r = 0; r < Pol::kWaveAcc; ++r) {
+      const int e = r * 64 + (threadIdx.x & 63);
+      if (e < K3 * HS) sh.wsum[(threadIdx.x >> 6) * K3 * HS + e] = wacc.v[r];
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < K3 * HS; i += NT) {
+      double v = 0.0;
+#pragma unroll
+      for (int w = 0; w < NT / 64; ++w) v += (double)sh.wsum[w * K3 * HS + i];
+      atomicAdd(p.dbias_acc + (i % HS) * K3 + i / HS, v);
+    }
   }
 }
 
