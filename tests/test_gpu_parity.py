@@ -55,6 +55,7 @@ SMALL = [
     (1, 41, 9, 17, 24, 2, 3, "bf16"),
     (1, 30, 9, 40, 8, 1, 5, "bf16"),        # k = 5 with chunk seams (bias gradient summed wave by wave)
     (2, 23, 10, 35, 16, 2, 5, "bf16"),
+    (1, 5, 6, 7, 24, 3, 3, "f32"),          # three heads: no tiled variant, generic kernels under both paths
 ]
 
 
@@ -105,7 +106,7 @@ def test_small_cases_match_oracle(modet, shape, path):
 # both dtypes
 BIASED = [SMALL[1], SMALL[3], SMALL[4], SMALL[6], SMALL[8], SMALL[12], SMALL[13], SMALL[16], SMALL[17], SMALL[18],
           SMALL[19], SMALL[20], SMALL[21], SMALL[22], SMALL[23], SMALL[24], SMALL[25], SMALL[26], SMALL[27],
-          SMALL[28], SMALL[29], SMALL[30], SMALL[31]]
+          SMALL[28], SMALL[29], SMALL[30], SMALL[31], SMALL[32]]
 
 
 @pytest.mark.parametrize("shape", BIASED, ids=lambda s: "x".join(map(str, s)))
