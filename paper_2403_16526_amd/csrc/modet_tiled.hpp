@@ -1660,24 +1660,25 @@ int compute_units() {
   return n;
 }
 
-// Chunk length along D.  A workgroup marches through zc + k - 1 planes, and `slots` workgroups are resident at
-// a time (compute units x the workgroups of this kernel that fit one CU).  The cost of a
-// split is the number of plane steps the busiest slot runs: full rounds of resident workgroups, plus a last,
-// partly filled round that counts half when it leaves at least half of the slots empty (a workgroup alone on
-// its CU steps faster).  Short chunks are avoided because each re-reads k - 1 planes.
+// Chunk length along D.  A workgroup marches through zc + k - 1 planes, and `slots` workgroups are resident at a
+// time (compute units x the workgroups of this kernel that fit one CU).  The cost of a split is the number of
+// steps the busiest slot runs: full rounds of resident workgroups plus a last, partly filled one.  A round in
+// which every workgroup has a CU to itself counts half when the kernel normally shares the CU (a workgroup alone
+// steps almost twice as fast; a kernel that fills the CU with one workgroup gains nothing).  Small volumes thus
+// get short chunks -- the machine is empty and only the length of one march counts -- large ones long chunks,
+// because every chunk re-reads and re-computes k - 1 planes.
 int chunk_length(long long tiles, int D, int k, int wgs_per_cu) {
-  const long long slots = (long long)compute_units() * wgs_per_cu;
-  const int min_zc = D < 8 ? D : 8;
+  const int cus = compute_units();
+  const long long slots = (long long)cus * wgs_per_cu;
   int best_zc = D;
   double best = 1e30;
   for (int nz = 1; nz <= D; ++nz) {
     const int zc = (D + nz - 1) / nz;
-    if (zc < min_zc) break;
     if ((D + zc - 1) / zc != nz) continue;      // the same split as a smaller nz
     const long long wgs = tiles * nz, full = wgs / slots, rem = wgs % slots;
     const int steps = zc + k - 1;
-    double cost = (double)full * steps + (rem == 0 ? 0.0 : (2 * rem <= slots ? 0.5 : 1.0) * steps);
-    if (wgs < slots) cost = (wgs * 2 <= slots ? 0.5 : 1.0) * steps;
+    const double last = rem == 0 ? 0.0 : ((rem <= cus && wgs_per_cu >= 2) ? 0.5 : 1.0) * steps;
+    const double cost = (double)full * steps + last;
     if (cost < best - 1e-9) { best = cost; best_zc = zc; }
   }
   return best_zc;
