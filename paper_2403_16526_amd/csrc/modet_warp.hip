@@ -274,6 +274,7 @@ warp_bwd_kernel(const T* __restrict__ src, const float* __restrict__ field, cons
   const int x = ibx * bk.bx + lx, y = iby * bk.by + ly, z = ibz * bk.bz + lz;
   const bool live = lz < bk.bz && x < W && y < H && z < D;
   __shared__ float tile[HALF ? kMaxTile * 3 : 1];
+  __shared__ float dtile[(HALF && FIELD) ? kMaxTile * 3 : 1];      // gradient of the staged coarse voxels
   CoarseTile ct = {};
   const int Dc = D / 2, Hc = H / 2, Wc = W / 2;
   if (HALF) {
@@ -288,10 +289,15 @@ warp_bwd_kernel(const T* __restrict__ src, const float* __restrict__ field, cons
       const int ex = e % ct.nx, ey = (e / ct.nx) % ct.ny, ez = e / (ct.nx * ct.ny);
       const float* p = fc + (((long long)(ct.oz + ez) * Hc + ct.oy + ey) * Wc + ct.ox + ex) * 3;
       tile[e * 3] = p[0]; tile[e * 3 + 1] = p[1]; tile[e * 3 + 2] = p[2];
+      if (FIELD) { dtile[e * 3] = 0.f; dtile[e * 3 + 1] = 0.f; dtile[e * 3 + 2] = 0.f; }
     }
     __syncthreads();
   }
-  if (!live) return;
+  if (!live && !(HALF && FIELD)) return;      // (with a half-resolution field gradient everybody meets again below)
+  float du[3] = {0.f, 0.f, 0.f};
+  bool writer = false;       // does this lane hold the voxel's whole sum?
+  bool single = false;
+  if (live) {
   const long long v = (((long long)b * D + z) * H + y) * W + x;
   double u[3];
   if (HALF) {
@@ -307,7 +313,6 @@ warp_bwd_kernel(const T* __restrict__ src, const float* __restrict__ field, cons
   float g[VEC];
   Vec<float, VEC>::load(dout + v * C + chunk * VEC, g);
   const long long vol = (long long)b * D * H * W * C + chunk * VEC;
-  float du[3] = {0.f, 0.f, 0.f};
   float val[8][VEC];
   bool in[8];
   long long off[8];
@@ -336,41 +341,56 @@ warp_bwd_kernel(const T* __restrict__ src, const float* __restrict__ field, cons
       }
     }
   }
-  if (!FIELD) return;
-  bool writer = true;        // does this lane hold the voxel's whole sum?
-  bool single = false;
-  if (bk.sc >= 0) {          // (uniform) the voxel's lanes are an aligned group of 2^sc lanes
-    for (int m = 1; m < (1 << bk.sc); m <<= 1) {
-      du[0] += __shfl_xor(du[0], m); du[1] += __shfl_xor(du[1], m); du[2] += __shfl_xor(du[2], m);
+  if (FIELD) {
+    writer = true;
+    if (bk.sc >= 0) {        // (uniform) the voxel's lanes are an aligned group of 2^sc lanes
+      for (int m = 1; m < (1 << bk.sc); m <<= 1) {
+        du[0] += __shfl_xor(du[0], m); du[1] += __shfl_xor(du[1], m); du[2] += __shfl_xor(du[2], m);
+      }
+      writer = chunk == 0;
+      single = true;
     }
-    writer = chunk == 0;
-    single = true;
-  }
-  if (!writer) return;
-  if (!HALF) {
-    float* o = dfield + v * 3;
-    if (single) {            // the only writer of this voxel's entry
-      o[0] = du[0]; o[1] = du[1]; o[2] = du[2];
-    } else {
-      unsafeAtomicAdd(o, du[0]); unsafeAtomicAdd(o + 1, du[1]); unsafeAtomicAdd(o + 2, du[2]);
+    if (!HALF && writer) {
+      float* o = dfield + v * 3;
+      if (single) {          // the only writer of this voxel's entry
+        o[0] = du[0]; o[1] = du[1]; o[2] = du[2];
+      } else {
+        unsafeAtomicAdd(o, du[0]); unsafeAtomicAdd(o + 1, du[1]); unsafeAtomicAdd(o + 2, du[2]);
+      }
     }
-    return;
   }
-  // half resolution: u = 2 * sum of weight * coarse value over the (clamped) coarse corners of this voxel
-  const int cz0 = coarse_lo(z), cy0 = coarse_lo(y), cx0 = coarse_lo(x);
-  const int cz1 = min(cz0 + 1, Dc - 1), cy1 = min(cy0 + 1, Hc - 1), cx1 = min(cx0 + 1, Wc - 1);
-  const float sz = (z == 0 || cz1 == cz0) ? 0.f : ((z & 1) ? 0.25f : 0.75f);
-  const float sy = (y == 0 || cy1 == cy0) ? 0.f : ((y & 1) ? 0.25f : 0.75f);
-  const float sx = (x == 0 || cx1 == cx0) ? 0.f : ((x & 1) ? 0.25f : 0.75f);
-  float* dc = dfield + (long long)b * Dc * Hc * Wc * 3;
+  }      // live
+  if (!(HALF && FIELD)) return;
+  // Half resolution: u = 2 * sum of weight * coarse value over the (clamped) coarse corners of a voxel, and up to
+  // 64 fine voxels share a coarse one.  The workgroup first sums into its LDS copy of the coarse tile, then adds
+  // every tile entry to the global gradient once.
+  if (live && writer) {
+    const int cz0 = coarse_lo(z), cy0 = coarse_lo(y), cx0 = coarse_lo(x);
+    const int cz1 = min(cz0 + 1, Dc - 1), cy1 = min(cy0 + 1, Hc - 1), cx1 = min(cx0 + 1, Wc - 1);
+    const float sz = (z == 0 || cz1 == cz0) ? 0.f : ((z & 1) ? 0.25f : 0.75f);
+    const float sy = (y == 0 || cy1 == cy0) ? 0.f : ((y & 1) ? 0.25f : 0.75f);
+    const float sx = (x == 0 || cx1 == cx0) ? 0.f : ((x & 1) ? 0.25f : 0.75f);
 #pragma unroll
-  for (int c = 0; c < 8; ++c) {
-    const float w = 2.f * ((c & 4) ? sz : 1.f - sz) * ((c & 2) ? sy : 1.f - sy) * ((c & 1) ? sx : 1.f - sx);
-    if (w == 0.f) continue;
-    float* o = dc + (((long long)((c & 4) ? cz1 : cz0) * Hc + ((c & 2) ? cy1 : cy0)) * Wc + ((c & 1) ? cx1 : cx0)) * 3;
-    unsafeAtomicAdd(o, w * du[0]); unsafeAtomicAdd(o + 1, w * du[1]); unsafeAtomicAdd(o + 2, w * du[2]);
+    for (int c = 0; c < 8; ++c) {
+      const float w = 2.f * ((c & 4) ? sz : 1.f - sz) * ((c & 2) ? sy : 1.f - sy) * ((c & 1) ? sx : 1.f - sx);
+      if (w == 0.f) continue;
+      const int zi = ((c & 4) ? cz1 : cz0) - ct.oz, yi = ((c & 2) ? cy1 : cy0) - ct.oy, xi = ((c & 1) ? cx1 : cx0) - ct.ox;
+      float* o = dtile + ((zi * ct.ny + yi) * ct.nx + xi) * 3;
+#pragma unroll
+      for (int a = 0; a < 3; ++a)
+        __hip_atomic_fetch_add(o + a, w * du[a], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    }
+  }
+  __syncthreads();
+  float* dc = dfield + (long long)b * Dc * Hc * Wc * 3;
+  const int n = ct.nx * ct.ny * ct.nz;
+  for (int e = threadIdx.x; e < n; e += kThreads) {
+    const int ex = e % ct.nx, ey = (e / ct.nx) % ct.ny, ez = e / (ct.nx * ct.ny);
+    float* o = dc + (((long long)(ct.oz + ez) * Hc + ct.oy + ey) * Wc + ct.ox + ex) * 3;
+    unsafeAtomicAdd(o, dtile[e * 3]); unsafeAtomicAdd(o + 1, dtile[e * 3 + 1]); unsafeAtomicAdd(o + 2, dtile[e * 3 + 2]);
   }
 }
+
 
 template <class T, int VEC>
 hipError_t launch_bwd_t(const void* src, const float* field, const float* dout, float* dsrc, float* dfield, int B,
