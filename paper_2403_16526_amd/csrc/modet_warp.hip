@@ -293,73 +293,112 @@ warp_bwd_kernel(const T* __restrict__ src, const float* __restrict__ field, cons
     }
     __syncthreads();
   }
-  if (!live && !(HALF && FIELD)) return;      // (with a half-resolution field gradient everybody meets again below)
+  // (nobody leaves early: the scatter below moves values between neighbouring lanes, and with a half-resolution
+  // field gradient everybody meets again at a barrier)
   float du[3] = {0.f, 0.f, 0.f};
   bool writer = false;       // does this lane hold the voxel's whole sum?
   bool single = false;
-  if (live) {
-  const long long v = (((long long)b * D + z) * H + y) * W + x;
-  double u[3];
-  if (HALF) {
-    upsampled_disp(tile, ct, Dc, Hc, Wc, z, y, x, u);
-  } else {
-    u[0] = field[v * 3]; u[1] = field[v * 3 + 1]; u[2] = field[v * 3 + 2];
-  }
-  const double fz = floor(u[0]), fy = floor(u[1]), fx = floor(u[2]);
-  const float tz = (float)(u[0] - fz), ty = (float)(u[1] - fy), tx = (float)(u[2] - fx);
-  const int z0 = z + (int)fmin(fmax(fz, -1.0e6), 1.0e6);
-  const int y0 = y + (int)fmin(fmax(fy, -1.0e6), 1.0e6);
-  const int x0 = x + (int)fmin(fmax(fx, -1.0e6), 1.0e6);
+  int z0 = 0, y0 = 0, x0 = 0;
+  float tz = 0.f, ty = 0.f, tx = 0.f;
   float g[VEC];
-  Vec<float, VEC>::load(dout + v * C + chunk * VEC, g);
+#pragma unroll
+  for (int i = 0; i < VEC; ++i) g[i] = 0.f;
   const long long vol = (long long)b * D * H * W * C + chunk * VEC;
-  float val[8][VEC];
-  bool in[8];
-  long long off[8];
+  if (live) {
+    const long long v = (((long long)b * D + z) * H + y) * W + x;
+    double u[3];
+    if (HALF) {
+      upsampled_disp(tile, ct, Dc, Hc, Wc, z, y, x, u);
+    } else {
+      u[0] = field[v * 3]; u[1] = field[v * 3 + 1]; u[2] = field[v * 3 + 2];
+    }
+    const double fz = floor(u[0]), fy = floor(u[1]), fx = floor(u[2]);
+    tz = (float)(u[0] - fz); ty = (float)(u[1] - fy); tx = (float)(u[2] - fx);
+    z0 = z + (int)fmin(fmax(fz, -1.0e6), 1.0e6);
+    y0 = y + (int)fmin(fmax(fy, -1.0e6), 1.0e6);
+    x0 = x + (int)fmin(fmax(fx, -1.0e6), 1.0e6);
+    Vec<float, VEC>::load(dout + v * C + chunk * VEC, g);
+    if (FIELD) {
+      float val[8][VEC];
+      bool in[8];
 #pragma unroll
-  for (int c = 0; c < 8; ++c) {
-    const int zi = z0 + ((c >> 2) & 1), yi = y0 + ((c >> 1) & 1), xi = x0 + (c & 1);
-    in[c] = (unsigned)zi < (unsigned)D && (unsigned)yi < (unsigned)H && (unsigned)xi < (unsigned)W;
-    const int zc = min(max(zi, 0), D - 1), yc = min(max(yi, 0), H - 1), xc = min(max(xi, 0), W - 1);
-    off[c] = vol + (((long long)zc * H + yc) * W + xc) * C;
-    if (FIELD) Vec<T, VEC>::load(src + off[c], val[c]);      // all corner loads first, from clamped addresses
-  }
+      for (int c = 0; c < 8; ++c) {     // all corner loads first, from clamped addresses
+        const int zi = z0 + ((c >> 2) & 1), yi = y0 + ((c >> 1) & 1), xi = x0 + (c & 1);
+        in[c] = (unsigned)zi < (unsigned)D && (unsigned)yi < (unsigned)H && (unsigned)xi < (unsigned)W;
+        const int zc = min(max(zi, 0), D - 1), yc = min(max(yi, 0), H - 1), xc = min(max(xi, 0), W - 1);
+        Vec<T, VEC>::load(src + vol + (((long long)zc * H + yc) * W + xc) * C, val[c]);
+      }
 #pragma unroll
-  for (int c = 0; c < 8; ++c) {
-    const float wz = (c & 4) ? tz : 1.f - tz, wy = (c & 2) ? ty : 1.f - ty, wx = (c & 1) ? tx : 1.f - tx;
-    if (in[c]) {
-      const float w = wz * wy * wx;
+      for (int c = 0; c < 8; ++c) {
+        const float wz = (c & 4) ? tz : 1.f - tz, wy = (c & 2) ? ty : 1.f - ty, wx = (c & 1) ? tx : 1.f - tx;
+        if (in[c]) {
+          float dot = 0.f;
 #pragma unroll
-      for (int i = 0; i < VEC; ++i) unsafeAtomicAdd(dsrc + off[c] + i, w * g[i]);
-      if (FIELD) {
-        float dot = 0.f;
-#pragma unroll
-        for (int i = 0; i < VEC; ++i) dot = fmaf(g[i], val[c][i], dot);
-        du[0] = fmaf(((c & 4) ? wy : -wy) * wx, dot, du[0]);
-        du[1] = fmaf(((c & 2) ? wz : -wz) * wx, dot, du[1]);
-        du[2] = fmaf(((c & 1) ? wz : -wz) * wy, dot, du[2]);
+          for (int i = 0; i < VEC; ++i) dot = fmaf(g[i], val[c][i], dot);
+          du[0] = fmaf(((c & 4) ? wy : -wy) * wx, dot, du[0]);
+          du[1] = fmaf(((c & 2) ? wz : -wz) * wx, dot, du[1]);
+          du[2] = fmaf(((c & 1) ? wz : -wz) * wy, dot, du[2]);
+        }
+      }
+      writer = true;
+      if (bk.sc >= 0) {        // (uniform) the voxel's lanes are an aligned group of 2^sc lanes
+        for (int m = 1; m < (1 << bk.sc); m <<= 1) {
+          du[0] += __shfl_xor(du[0], m); du[1] += __shfl_xor(du[1], m); du[2] += __shfl_xor(du[2], m);
+        }
+        writer = chunk == 0;
+        single = true;
+      }
+      if (!HALF && writer) {
+        float* o = dfield + v * 3;
+        if (single) {          // the only writer of this voxel's entry
+          o[0] = du[0]; o[1] = du[1]; o[2] = du[2];
+        } else {
+          unsafeAtomicAdd(o, du[0]); unsafeAtomicAdd(o + 1, du[1]); unsafeAtomicAdd(o + 2, du[2]);
+        }
       }
     }
   }
-  if (FIELD) {
-    writer = true;
-    if (bk.sc >= 0) {        // (uniform) the voxel's lanes are an aligned group of 2^sc lanes
-      for (int m = 1; m < (1 << bk.sc); m <<= 1) {
-        du[0] += __shfl_xor(du[0], m); du[1] += __shfl_xor(du[1], m); du[2] += __shfl_xor(du[2], m);
+  // ---- the scatter: weight * dout to the eight corners.  The upper-x corner of a voxel is the lower-x corner
+  // of its x-neighbour whenever both have the same integer displacement, which a smooth field gives almost
+  // always: the neighbour's lane (2^sc lanes up, when the voxel's lanes are such an aligned group) then takes
+  // the contribution over and adds both with one atomic, which nearly halves the cache lines the atomic units
+  // have to work through.
+  const bool comb = bk.sc >= 0;                 // uniform
+  const int nch = comb ? 1 << bk.sc : 1;
+  const int lane = threadIdx.x & 63;
+  bool same_prev = false, next_same = false;
+  if (comb) {
+    const int pz = __shfl_up(z0, nch), py = __shfl_up(y0, nch), px = __shfl_up(x0, nch);
+    const int pl = __shfl_up((int)live, nch);
+    same_prev = live && pl != 0 && lane >= nch && lx > 0 && pz == z0 && py == y0 && px + 1 == x0;
+    next_same = __shfl_down((int)same_prev, nch) != 0 && lane + nch < 64;
+  }
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {                 // the four (z, y) corner rows
+    const float wzy = ((r & 2) ? tz : 1.f - tz) * ((r & 1) ? ty : 1.f - ty);
+    float lo[VEC], hi[VEC];
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) { lo[i] = wzy * (1.f - tx) * g[i]; hi[i] = wzy * tx * g[i]; }
+    if (comb) {
+#pragma unroll
+      for (int i = 0; i < VEC; ++i) {
+        const float from_prev = __shfl_up(hi[i], nch);
+        if (same_prev) lo[i] += from_prev;
       }
-      writer = chunk == 0;
-      single = true;
     }
-    if (!HALF && writer) {
-      float* o = dfield + v * 3;
-      if (single) {          // the only writer of this voxel's entry
-        o[0] = du[0]; o[1] = du[1]; o[2] = du[2];
-      } else {
-        unsafeAtomicAdd(o, du[0]); unsafeAtomicAdd(o + 1, du[1]); unsafeAtomicAdd(o + 2, du[2]);
+    const int zi = z0 + (r >> 1), yi = y0 + (r & 1);
+    if (live && (unsigned)zi < (unsigned)D && (unsigned)yi < (unsigned)H) {
+      float* row = dsrc + vol + ((long long)zi * H + yi) * W * C;
+      if ((unsigned)x0 < (unsigned)W) {
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) unsafeAtomicAdd(row + (long long)x0 * C + i, lo[i]);
+      }
+      if (!next_same && (unsigned)(x0 + 1) < (unsigned)W) {
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) unsafeAtomicAdd(row + (long long)(x0 + 1) * C + i, hi[i]);
       }
     }
   }
-  }      // live
   if (!(HALF && FIELD)) return;
   // Half resolution: u = 2 * sum of weight * coarse value over the (clamped) coarse corners of a voxel, and up to
   // 64 fine voxels share a coarse one.  The workgroup first sums into its LDS copy of the coarse tile, then adds
