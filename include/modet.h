@@ -1,19 +1,21 @@
 /* libmodet -- the ModeT motion-decomposition operator on AMD MI355X (gfx950).
  *
- * C ABI.  Every pointer named Q, K, bias, phi, attn, lse, dphi, dQ, dK, dbias, src, field,
- * out, workspace is a DEVICE pointer owned by the caller (for instance the storage of a
- * torch tensor).  The library never allocates, frees or retains memory and never
- * synchronises: work is enqueued on `stream` (a hipStream_t passed as void*; NULL is the
- * default stream) and the call returns at once.  Inputs and outputs must not alias.
- * All base pointers must be 16-byte aligned.
+ * C ABI.  Every pointer argument (Q, K, bias, phi, attn, lse, dphi, dQ, dK, dbias, src, field,
+ * out, dout, dsrc, dfield, outer, inner, v, tmp, workspace) is a DEVICE pointer owned by the
+ * caller (for instance the storage of a torch tensor).  The library never allocates, frees or
+ * retains memory and never synchronises: work is enqueued on `stream` (a hipStream_t passed as
+ * void*; NULL is the default stream) and the call returns at once.  Inputs and outputs must not
+ * alias unless a function says otherwise.  All base pointers must be 16-byte aligned.
  *
  * Layout (row-major, last index fastest):
- *   Q, K, dQ, dK, src, out : [B, D, H, W, C]      channels last; head s owns channels
+ *   Q, K, dQ, dK, src, out,
+ *   dout, dsrc             : [B, D, H, W, C]      channels last; head s owns channels
  *                                                 [s*d, (s+1)*d), d = C / heads
  *   phi, dphi              : [B, D, H, W, heads, 3]   components ordered (D, H, W), voxel units
  *   attn                   : [B, D, H, W, heads, k^3]
  *   lse                    : [B, D, H, W, heads]
  *   bias, dbias            : [heads, k^3]
+ *   displacement fields    : [B, D, H, W, 3]      fp32, voxel units, components ordered (D, H, W)
  *   window offset index    : j = ((a+r)*k + (b+r))*k + (c+r), offsets a,b,c in -r..r along
  *                            D,H,W, r = (k-1)/2
  *

@@ -1,29 +1,30 @@
-// LDS-tiled ModeT kernels for head size d = 8 (gfx950).
+// LDS-tiled ModeT kernels (gfx950): heads of 8 channels, of 6 (padded to 8 on chip) and of 12 (two half-heads).
 //
-// Paper: Section 3.3.1, Eq. 3 (neighbourhood scores + softmax) and Eq. 4-5 (attention-weighted
-// offset grid), and their derivatives with respect to Q and K.
+// Paper: Section 3.3.1, Eq. 3 (neighbourhood scores + softmax, with the bias B) and Eq. 4-5 (attention-weighted
+// offset grid), and their derivatives with respect to Q, K and B.
 //
-// Work decomposition (all three kernels)
-//   * The head axis is folded into W: a voxel row [W][heads][8] is a row of Wh = W*heads
-//     "fused columns" of 8 contiguous channels; the W-neighbour of fused column xs is xs +- heads.
-//   * A workgroup of 256 lanes owns a TX x TY = 32 x 8 patch of (fused column, H row) and marches
-//     along D over a chunk of planes.  One plane of the *other* operand (patch + halo, zero filled
-//     outside the volume, so the inner loops are branch free) lives in LDS at a time, double
-//     buffered; the next plane is fetched into registers while the current one is consumed.
-//   * Register blocking along D: a lane keeps the k planes of its own operand that can see the
-//     current LDS plane in flight, so every vector read from LDS is used for k windows.
-//   * forward : lane owns a query column, K planes in LDS, online softmax (running maximum), no
-//               logit or weight is ever stored.
-//   * dQ      : lane owns a query column, K planes in LDS, weights from w = exp(l - lse).
-//   * dK      : lane owns a key column, Q planes and per-query statistics (lse, g, g.phi) in LDS;
-//               it gathers over the queries that see the key, so no atomics and a fixed summation
-//               order (bit-reproducible).
-//   * Logits are accumulated in fp64 for fp32 inputs (template parameter LT): an fp32 sum of eight
-//     products leaves ~1e-6 of rounding on a logit of magnitude ~10, which the softmax turns into a
-//     1e-6 relative error of the weights.  An fp64 FMA costs two fp32 issue slots on this chip, so fp64
-//     is confined to the dot product, the subtraction of the softmax reference and the running softmax
-//     sums of the forward; everything else is fp32.  Logits are kept in log2 units (the in-flight
-//     operand is pre-multiplied by scale*log2(e)).
+// Work decomposition
+//   * The head axis is folded into W: a voxel row [W][heads][8] is a row of Wh = W*heads "fused columns" of 8
+//     contiguous channels; the W-neighbour of fused column xs is xs +- heads (the kernels' HS).
+//   * A group of 256 lanes owns a TX x TY = 32 x 8 patch of (fused column, H row) and marches along D over a
+//     chunk of planes.  One plane of the *other* operand (patch + halo, zero filled outside the volume, so the
+//     inner loops are branch free) lives in LDS at a time, double buffered; the next plane is fetched into
+//     registers while the current one is consumed.
+//   * Register blocking along D: a lane keeps the k planes of its own operand that can see the current LDS plane
+//     in flight ("roles"), so every vector read from LDS is used for k windows.
+//   * forward (FwdPolicy): lane owns a query column, K planes in LDS; softmax sums against one fixed reference per
+//     query (no running maximum, nothing rescaled); no logit or weight is ever stored.
+//   * backward: w = exp(l - lse) with the forward's lse.  k = 3 with one or two heads: bwd_fused_kernel, a
+//     512-lane workgroup whose query half (DqPolicy) computes every logit once and hands dl to its key half
+//     through LDS, which gathers dK; k = 3 with more heads: bwd_shared_kernel, the dQ and dK marches (DqPolicy,
+//     DkPolicy) side by side on shared staged planes; k = 5: march_pair_kernel, the two marches as neighbouring
+//     workgroups.  dK is always a gather over the queries that see a key: no atomics, fixed summation order.
+//   * The gradient of the bias is a by-product of the backward kernels (sums of dl, folded in fp64).
+//   * Logits are accumulated in fp64 for fp32 inputs (template parameter LT): an fp32 sum of eight products
+//     leaves ~1e-6 of rounding on a logit of magnitude ~10, which the softmax turns into a 1e-6 relative error of
+//     the weights.  An fp64 FMA issues at the rate of an unpacked fp32 one on this chip; fp64 is confined to the
+//     dot product, the subtraction of the softmax reference and the softmax sums of the forward, everything else
+//     is fp32.  Logits are kept in log2 units (the in-flight operand is pre-multiplied by scale*log2(e)).
 #pragma once
 #include "modet_common.hpp"
 #include <type_traits>
