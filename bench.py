@@ -191,6 +191,21 @@ def main():
     t_warp = e0.elapsed_time(e1) / 10
     warp_bytes = nvox * (2 * C * esz + 12)
 
+    # the warp's adjoint (scatter with atomics), source gradient alone and with the field gradient
+    dsrc = torch.empty((B, D, H, W, C), **f32)
+    dKw = torch.empty((B, D, H, W, C), **f32).normal_()
+    t_wb = []
+    for want in (False, True):
+        for _ in range(2):
+            modet.modet_warp_bwd(K, field, dKw, want_dfield=want, out=dsrc)
+        e0.record()
+        for _ in range(5):
+            modet.modet_warp_bwd(K, field, dKw, want_dfield=want, out=dsrc)
+        e1.record()
+        torch.cuda.synchronize()
+        t_wb.append(e0.elapsed_time(e1) / 5)
+    del dsrc, dKw
+
     # field composition and scaling-and-squaring at the same shape (also beside the metric)
     comp, tmp = torch.empty_like(field), torch.empty_like(field)
     for _ in range(3):
@@ -251,6 +266,8 @@ def main():
         "pairs_per_s": round(value * k ** 3, 1),
         "device_copy_gbs": round(copy_gbs, 1),
         "warp": {"ms": round(t_warp, 4), "gbs": round(warp_bytes / (t_warp * 1e-3) / 1e9, 1)},
+        "warp_bwd": {"ms": round(t_wb[0], 4), "gbs": round(warp_bytes / (t_wb[0] * 1e-3) / 1e9, 1),
+                     "ms_with_field_gradient": round(t_wb[1], 4)},
         "compose": {"ms": round(t_comp, 4), "gbs": round(nvox * 24 / (t_comp * 1e-3) / 1e9, 1),
                     "integrate_T7_ms": round(t_int, 4)},
         "input_gen_s": round(t_gen, 1),
