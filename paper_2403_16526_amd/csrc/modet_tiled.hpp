@@ -183,38 +183,6 @@ __device__ __forceinline__ double partner(double x) {
   const int hi = __builtin_amdgcn_mov_dpp(__double2hiint(x), 0xB1, 0xF, 0xF, true);
   return __hiloint2double(hi, lo);
 }
-// x + (x moved across lanes by a DPP control), lanes outside the row / bank masks add 0
-template <int CTRL, int ROW_MASK>
-__device__ __forceinline__ float dpp_add(float x) {
-  return x + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, ROW_MASK, 0xF, true));
-}
-// Sum of x over the wave's 64 lanes, valid in lane 63.  STEP = 1: an inclusive scan inside each row of 16 lanes
-// (shifts by 1, 2, 4, 8), then row 0's total into row 1 and row 2's into row 3 (broadcast of lane 15), then
-// lane 31's into rows 2 and 3.  STEP = 2 leaves out the shift by 1: the last two lanes of a row then hold the
-// sums of the row's even and of its odd lanes.
-template <int STEP>
-__device__ __forceinline__ float row_scan(float x) {
-  if (STEP == 1) x = dpp_add<0x111, 0xF>(x);      // row_shr:1
-  x = dpp_add<0x112, 0xF>(x);                     // row_shr:2
-  x = dpp_add<0x114, 0xF>(x);                     // row_shr:4
-  x = dpp_add<0x118, 0xF>(x);                     // row_shr:8
-  return x;
-}
-__device__ __forceinline__ float across_rows(float x) {
-  x = dpp_add<0x142, 0xA>(x);                     // row_bcast:15 into rows 1 and 3
-  x = dpp_add<0x143, 0xC>(x);                     // row_bcast:31 into rows 2 and 3
-  return x;
-}
-template <int STEP>
-__device__ __forceinline__ float wave_sum_to_last_lane(float x) { return across_rows(row_scan<STEP>(x)); }
-// sums over the even and over the odd lanes, both valid in lane 63
-__device__ __forceinline__ void wave_sums_by_parity(float x, float& even, float& odd) {
-  const float s = row_scan<2>(x);                 // lane 14 / 15 of a row: the row's even / odd lanes
-  odd = across_rows(s);
-  // move every row's lane 14 to its lane 15, then the same two steps
-  even = across_rows(__int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(s), 0x111, 0xF, 0xF, true)));
-}
-
 // a logit from this lane's partial sum
 template <class T, class LT>
 __device__ __forceinline__ LT whole_logit(LT part) {
@@ -677,17 +645,29 @@ struct DqPolicy {
   // One step: for every in-plane offset (b, c) the K vector is read once and every active role i (plane
   // offset a = R - i) gets its pair: w = exp2(logit - lse), dl = w * (g.o - g.phi), dQ += dl * K.  What else
   // happens to dl is the sink's business: sink.begin(b, c) runs before the dot products of an in-plane offset,
-  // sink.pair(i, b, c, dl) after each of them, sink.idle(i, b, c) for a role that is not active.
+  // sink.pair(i, b, c, dl) after each of them, sink.idle(i, b, c) for a role that is not active, sink.end_row(b)
+  // after the last in-plane offset of row b.
   struct NoSink {
+    static constexpr bool kRolledRows = false;
     __device__ __forceinline__ void begin(int, int) {}
     __device__ __forceinline__ void pair(int, int, int, float) {}
     __device__ __forceinline__ void idle(int, int, int) {}
+    __device__ __forceinline__ void end_row(int) {}
   };
   template <int PH, bool FULL, class Sink>
   static __device__ __forceinline__ void pairs(State (&st)[KW], const typename Lds<ET>::chunk* kb, int lbase,
                                                unsigned active, const LT* bl, Sink& sink) {
+    if constexpr (Sink::kRolledRows) {      // one copy of a row's code, run KW times (b is a run-time value then)
+#pragma unroll 1
+      for (int b = 0; b < KW; ++b) pairs_of_row<PH, FULL>(st, kb, lbase, active, bl, sink, b);
+    } else {
 #pragma unroll
-    for (int b = 0; b < KW; ++b)
+      for (int b = 0; b < KW; ++b) pairs_of_row<PH, FULL>(st, kb, lbase, active, bl, sink, b);
+    }
+  }
+  template <int PH, bool FULL, class Sink>
+  static __device__ __forceinline__ void pairs_of_row(State (&st)[KW], const typename Lds<ET>::chunk* kb, int lbase,
+                                                      unsigned active, const LT* bl, Sink& sink, int b) {
 #pragma unroll
       for (int c = 0; c < KW; ++c) {
         float kf[8];
@@ -714,6 +694,7 @@ struct DqPolicy {
             sink.idle(i, b, c);
           }
         }
+        if (c == KW - 1) sink.end_row(b);
       }
   }
   template <int PH, bool FULL>
@@ -727,6 +708,7 @@ struct DqPolicy {
   // write (nobody else touches the address; LDS atomics are an order of magnitude slower).  The sums of an
   // in-plane offset are read before its dot products and written after them.
   struct SumSink {
+    static constexpr bool kRolledRows = false;
     float* sums;
     float run[KW];
     __device__ __forceinline__ void begin(int b, int c) {
@@ -737,6 +719,7 @@ struct DqPolicy {
       sums[(((KW - 1 - i) * KW + b) * KW + c) * NT] = run[i] + dl;
     }
     __device__ __forceinline__ void idle(int, int, int) {}
+    __device__ __forceinline__ void end_row(int) {}
   };
   template <int PH, bool FULL>
   static __device__ __forceinline__ void step_sum(State (&st)[KW], const typename Lds<ET>::chunk* kb, int lbase,
@@ -745,40 +728,53 @@ struct DqPolicy {
     sink.sums = sums;
     pairs<PH, FULL>(st, kb, lbase, active, bl, sink);
   }
-  // The same step for a march that has no room for per-lane sums (k = 5: 125 offsets): every dl is summed across
-  // the wave right away with data-parallel-primitive moves (no LDS traffic, no waits, no branches), per head.  The
-  // wave's total of entry e = o * HS + head is kept in lane e % 64 of register e / 64 of `acc` (the total is read
-  // from lane 63 into a scalar and added under a one-lane mask).  `keep` is false for lanes that compute on a
-  // clamped column outside the volume.
-  static constexpr int kWaveAcc = SUMS ? (KW * KW * KW * HS + 63) / 64 : 1;
+  // The same step for a march that has no room for per-lane sums (k = 5: 125 offsets).  The wave transposes
+  // through its own LDS staging area: for one window row b every lane writes its KW * KW values of dl (role i,
+  // column c) to stage[(i * KW + c) * 64 + slot]; then lane 2e + part adds up one half (32 lanes' values, 8 vector
+  // reads rotated by e against bank conflicts) of entry e = i * KW + c into its accumulator of row b.  With two
+  // heads the lanes of a wave alternate heads and `slot` sorts them by head, so a half is a head; with one head
+  // the two halves are added across the lane pair.  Only the wave itself touches its staging area: the fences
+  // order its own LDS writes and reads.  `keep` is false for lanes that compute on a clamped column outside the
+  // volume.
   struct WaveSumSink {
-    float (&acc)[kWaveAcc];
-    int lane;
+    static constexpr bool kRolledRows = true;      // (unrolled over the rows as well, this variant spills)
+    float* acc;        // this lane's KW running sums, one per row b: acc[b * 64], in the wave's LDS area
+    float* stage;      // this wave's KW * KW rows of 64 floats
+    int lane, slot;
     bool keep;
-    static_assert(HS <= 2, "the wave sums are written for one or two heads");
-    __device__ __forceinline__ void add(int e, float total_in_last_lane) {
-      const float t = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(total_in_last_lane), 63));
-      acc[e / 64] += lane == e % 64 ? t : 0.f;
-    }
+    static_assert(HS <= 2 && 2 * KW * KW <= 64, "one or two heads; an adding lane per entry and half");
     __device__ __forceinline__ void begin(int, int) {}
-    __device__ __forceinline__ void pair(int i, int b, int c, float dl) {
-      const float v = keep ? dl : 0.f;
-      const int e = (((KW - 1 - i) * KW + b) * KW + c) * HS;
-      if (HS == 1) {
-        add(e, wave_sum_to_last_lane<1>(v));
-      } else {            // lanes alternate between the two heads
-        float even, odd;
-        wave_sums_by_parity(v, even, odd);
-        add(e, even);
-        add(e + 1, odd);
+    __device__ __forceinline__ void pair(int i, int, int c, float dl) { stage[(i * KW + c) * 64 + slot] = keep ? dl : 0.f; }
+    __device__ __forceinline__ void idle(int i, int, int c) { stage[(i * KW + c) * 64 + slot] = 0.f; }
+    __device__ __forceinline__ void end_row(int b) {
+      __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+      const int e = min(lane >> 1, KW * KW - 1);      // (lanes beyond the last entry repeat it; their sums are not used)
+      const float4* src = reinterpret_cast<const float4*>(stage + e * 64 + (lane & 1) * 32);
+      float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll 2
+      for (int j = 0; j < 8; ++j) {
+        const float4 v = src[(j + e) & 7];
+        t.x += v.x; t.y += v.y; t.z += v.z; t.w += v.w;
       }
+      float sum = (t.x + t.y) + (t.z + t.w);
+      if (HS == 1) sum += partner(sum);
+      acc[b * 64] += sum;
+      __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
     }
-    __device__ __forceinline__ void idle(int, int, int) {}
+    // bias entry (offset o, head) this lane's accumulator of row b belongs to, or -1
+    static __device__ __forceinline__ int entry(int lane, int b) {
+      const int e = lane >> 1, part = lane & 1;
+      if (e >= KW * KW || (HS == 1 && part != 0)) return -1;
+      const int o = ((KW - 1 - e / KW) * KW + b) * KW + e % KW;
+      return HS == 1 ? o : o * 2 + part;
+    }
   };
   template <int PH, bool FULL>
   static __device__ __forceinline__ void step_wavesum(State (&st)[KW], const typename Lds<ET>::chunk* kb, int lbase,
-                                                      unsigned active, const LT* bl, float (&acc)[kWaveAcc], bool keep) {
-    WaveSumSink sink = {acc, (int)(threadIdx.x & 63), keep};
+                                                      unsigned active, const LT* bl, float* wave_area, bool keep) {
+    const int lane = threadIdx.x & 63;
+    WaveSumSink sink = {wave_area + KW * KW * 64 + lane, wave_area, lane,
+                        HS == 1 ? lane : (lane & 1) * 32 + (lane >> 1), keep};
     pairs<PH, FULL>(st, kb, lbase, active, bl, sink);
   }
   // The same step, also handing dl of every (role, offset) to the key side:
@@ -786,12 +782,14 @@ struct DqPolicy {
   // active emit 0.
   template <int DLA>
   struct EmitSink {
+    static constexpr bool kRolledRows = false;
     float* out;      // dl_out + li
     __device__ __forceinline__ void begin(int, int) {}
     __device__ __forceinline__ void pair(int i, int b, int c, float dl) {
       out[(KW - 1 - i) * DLA + (b * KW + c) * NT] = dl;      // a + R = R - i + R = KW - 1 - i
     }
     __device__ __forceinline__ void idle(int i, int b, int c) { out[(KW - 1 - i) * DLA + (b * KW + c) * NT] = 0.f; }
+    __device__ __forceinline__ void end_row(int) {}
   };
   template <int PH, bool FULL, int DLA>
   static __device__ __forceinline__ void step_emit(State (&st)[KW], const typename Lds<ET>::chunk* kb, int lbase,
@@ -888,6 +886,8 @@ template <class Pol> struct SharedPlanes<Pol, false> {
   BiasTable<typename Pol::Logit, Pol::KW, Pol::HS, Pol::kBias> bias;
   // per wave: sums of dl per (window offset, head), for the bias gradient of a dQ march (WaveSumSink)
   float wsum[Pol::kWaveSums ? (NT / 64) * Pol::KW * Pol::KW * Pol::KW * Pol::HS : 1];
+  // per wave: KW * KW staging rows of 64 floats, then KW rows of per-lane running sums
+  alignas(16) float wstage[Pol::kWaveSums ? (NT / 64) * (Pol::KW * Pol::KW + Pol::KW) * 64 : 4];
 };
 template <class Pol> struct SharedPlanes<Pol, true> {
   typename Lds<typename Pol::ET>::chunk main[2][Lds<typename Pol::ET>::CH * Pol::P::NPOS];
@@ -902,15 +902,10 @@ __device__ __forceinline__ const typename Pol::Logit* lane_bias(const Sh& sh, in
   else return nullptr;
 }
 
-// per-lane registers of a march that sums dl across its waves (one dummy register otherwise)
-template <class Pol, bool ON = Pol::kWaveSums> struct WaveAcc { float v[1]; };
-template <class Pol> struct WaveAcc<Pol, true> { float v[Pol::kWaveAcc]; };
-
 template <class Pol, int PH, class Sh, class Stg, class SStg>
 __device__ __forceinline__ void march_body(typename Pol::State (&st)[Pol::KW], const TiledParams& p, const Tile& t,
                                            Sh& sh, int cur, int lbase, int s, typename Pol::Pre& pre,
-                                           bool have_next, bool commit_next, const Stg& stg, const SStg& sst,
-                                           WaveAcc<Pol>& wacc) {
+                                           bool have_next, bool commit_next, const Stg& stg, const SStg& sst) {
   constexpr int KW = Pol::KW, R = KW / 2;
   const unsigned active = active_roles<KW>(s, t.z0, t.z1);
   const float4* sa = nullptr;
@@ -918,11 +913,12 @@ __device__ __forceinline__ void march_body(typename Pol::State (&st)[Pol::KW], c
   if constexpr (Pol::kStats) { sa = sh.sa[cur]; sc = sh.sc[cur]; }
   const typename Pol::Logit* bl = lane_bias<Pol>(sh, t.xs);
   if constexpr (Pol::kWaveSums) {      // a dQ march that also sums its dl for the bias gradient
-    // (even lanes of a wave hold head 0, odd lanes head 1: tile origins are multiples of 32 columns)
     if (active == (1u << KW) - 1u)
-      Pol::template step_wavesum<PH, true>(st, sh.main[cur], lbase, active, bl, wacc.v, t.lane_ok);
+      Pol::template step_wavesum<PH, true>(st, sh.main[cur], lbase, active, bl,
+                                           sh.wstage + (threadIdx.x >> 6) * (KW * KW + KW) * 64, t.lane_ok);
     else
-      Pol::template step_wavesum<PH, false>(st, sh.main[cur], lbase, active, bl, wacc.v, t.lane_ok);
+      Pol::template step_wavesum<PH, false>(st, sh.main[cur], lbase, active, bl,
+                                            sh.wstage + (threadIdx.x >> 6) * (KW * KW + KW) * 64, t.lane_ok);
   } else {
     if (active == (1u << KW) - 1u) Pol::template step<PH, true>(st, sh.main[cur], sa, sc, lbase, active, bl);
     else Pol::template step<PH, false>(st, sh.main[cur], sa, sc, lbase, active, bl);
@@ -991,9 +987,11 @@ __device__ __forceinline__ void march(const TiledParams& p, unsigned id, void* s
     if constexpr (Pol::kStats) sst.zero_outside(sh.sa[j], sh.sc[j]);
   }
   if constexpr (Pol::kBias) fill_bias_table<T, typename Pol::Logit, KW, HS>(sh.bias.v, p.bias, threadIdx.x, NT);
-  WaveAcc<Pol> wacc;
+  if constexpr (Pol::kWaveSums) {      // every lane's running sums start at zero (its own slots: no barrier needed)
 #pragma unroll
-  for (int r = 0; r < (int)(sizeof(wacc.v) / sizeof(float)); ++r) wacc.v[r] = 0.f;
+    for (int b = 0; b < KW; ++b)
+      sh.wstage[(threadIdx.x >> 6) * (KW * KW + KW) * 64 + (KW * KW + b) * 64 + (threadIdx.x & 63)] = 0.f;
+  }
 
   typename Pol::State st[KW];
 #pragma unroll
@@ -1034,7 +1032,7 @@ __device__ __forceinline__ void march(const TiledParams& p, unsigned id, void* s
     const int cur = (s - s_first) & 1;
     const bool commit_next = s + 1 <= s_last;
     const bool have_next = s + R + 1 < t.z1;
-    march_body<Pol, PH>(st, p, t, sh, cur, lbase, s, pre, have_next, commit_next, stg, sst, wacc);
+    march_body<Pol, PH>(st, p, t, sh, cur, lbase, s, pre, have_next, commit_next, stg, sst);
     if (!ROT) {
       // rotate by moving: role i+1 becomes role i, the refilled slot 0 becomes role KW-1
       typename Pol::State tmp = st[0];
@@ -1060,9 +1058,11 @@ __device__ __forceinline__ void march(const TiledParams& p, unsigned id, void* s
   if constexpr (Pol::kWaveSums) {      // every wave's totals go to its row of the LDS table, then the rows are folded
     constexpr int K3 = KW * KW * KW;
 #pragma unroll
-    for (int r = 0; r < Pol::kWaveAcc; ++r) {
-      const int e = r * 64 + (threadIdx.x & 63);
-      if (e < K3 * HS) sh.wsum[(threadIdx.x >> 6) * K3 * HS + e] = wacc.v[r];
+    for (int b = 0; b < KW; ++b) {
+      const int e = Pol::WaveSumSink::entry(threadIdx.x & 63, b);
+      if (e >= 0)
+        sh.wsum[(threadIdx.x >> 6) * K3 * HS + e] =
+            sh.wstage[(threadIdx.x >> 6) * (KW * KW + KW) * 64 + (KW * KW + b) * 64 + (threadIdx.x & 63)];
     }
     __syncthreads();
     for (int i = threadIdx.x; i < K3 * HS; i += NT) {
