@@ -462,32 +462,38 @@ struct Disp { float z, y, x; };      // one voxel of a field: a single 12-byte l
 __global__ void __launch_bounds__(kThreads)
 compose_kernel(const float* __restrict__ outer, const float* __restrict__ inner, float* __restrict__ out, int B,
                int D, int H, int W, float s) {
-  const long long nvox = (long long)B * D * H * W;
-  const long long v = (long long)blockIdx.x * kThreads + threadIdx.x;
+  // (32-bit indices: the host has checked that the field has fewer than 2^31 elements)
+  const int nvox = B * D * H * W;
+  const int v = blockIdx.x * kThreads + threadIdx.x;
   if (v >= nvox) return;
-  long long t = v;
-  const int x = (int)(t % W); t /= W;
-  const int y = (int)(t % H); t /= H;
-  const int z = (int)(t % D);
-  const int b = (int)(t / D);
+  int t = v;
+  const int x = t % W; t /= W;
+  const int y = t % H; t /= H;
+  const int z = t % D;
+  const int b = t / D;
   const Disp iv = *reinterpret_cast<const Disp*>(inner + v * 3);
   const float i0 = iv.z, i1 = iv.y, i2 = iv.x;
-  const double u0 = (double)(s * i0), u1 = (double)(s * i1), u2 = (double)(s * i2);
-  // integer and fractional parts as in the warp kernel: the fraction of an fp32 displacement is exact
-  const double fz = floor(u0), fy = floor(u1), fx = floor(u2);
-  const float tz = (float)(u0 - fz), ty = (float)(u1 - fy), tx = (float)(u2 - fx);
-  const int z0 = z + (int)fmin(fmax(fz, -1.0e6), 1.0e6);
-  const int y0 = y + (int)fmin(fmax(fy, -1.0e6), 1.0e6);
-  const int x0 = x + (int)fmin(fmax(fx, -1.0e6), 1.0e6);
-  const float* ob = outer + (long long)b * D * H * W * 3;
+  const float u0 = s * i0, u1 = s * i1, u2 = s * i2;      // exact: s is a power of two
+  // integer and fractional parts as in the warp kernel; both are exact in fp32 for an fp32 displacement
+  const float fz = floorf(u0), fy = floorf(u1), fx = floorf(u2);
+  const float tz = u0 - fz, ty = u1 - fy, tx = u2 - fx;
+  const int z0 = z + (int)fminf(fmaxf(fz, -1.0e6f), 1.0e6f);
+  const int y0 = y + (int)fminf(fmaxf(fy, -1.0e6f), 1.0e6f);
+  const int x0 = x + (int)fminf(fmaxf(fx, -1.0e6f), 1.0e6f);
+  const float* ob = outer + b * (D * H * W * 3);
   float val[8][3];
   bool in[8];
+  // per axis: is the lower / upper corner inside, and its clamped index
+  const bool zin[2] = {(unsigned)z0 < (unsigned)D, (unsigned)(z0 + 1) < (unsigned)D};
+  const bool yin[2] = {(unsigned)y0 < (unsigned)H, (unsigned)(y0 + 1) < (unsigned)H};
+  const bool xin[2] = {(unsigned)x0 < (unsigned)W, (unsigned)(x0 + 1) < (unsigned)W};
+  const int zc[2] = {min(max(z0, 0), D - 1) * H, min(max(z0 + 1, 0), D - 1) * H};
+  const int yc[2] = {min(max(y0, 0), H - 1), min(max(y0 + 1, 0), H - 1)};
+  const int xc[2] = {min(max(x0, 0), W - 1), min(max(x0 + 1, 0), W - 1)};
 #pragma unroll
   for (int c = 0; c < 8; ++c) {     // all corner loads first, from clamped addresses
-    const int zi = z0 + ((c >> 2) & 1), yi = y0 + ((c >> 1) & 1), xi = x0 + (c & 1);
-    in[c] = (unsigned)zi < (unsigned)D && (unsigned)yi < (unsigned)H && (unsigned)xi < (unsigned)W;
-    const int zc = min(max(zi, 0), D - 1), yc = min(max(yi, 0), H - 1), xc = min(max(xi, 0), W - 1);
-    const Disp q = *reinterpret_cast<const Disp*>(ob + (((long long)zc * H + yc) * W + xc) * 3);
+    in[c] = zin[(c >> 2) & 1] && yin[(c >> 1) & 1] && xin[c & 1];
+    const Disp q = *reinterpret_cast<const Disp*>(ob + ((zc[(c >> 2) & 1] + yc[(c >> 1) & 1]) * W + xc[c & 1]) * 3);
     val[c][0] = q.z; val[c][1] = q.y; val[c][2] = q.x;
   }
   float acc[3] = {0.f, 0.f, 0.f};
