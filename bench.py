@@ -23,10 +23,22 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 PREWARM_MS = 60.0
 
-# HBM bytes per modet_bwd call (one kernel: the dQ and dK marches of a tile side by side) from rocprofv3 --pmc
-# FETCH_SIZE / WRITE_SIZE runs of this command, scaled by what the same counters read for the device copy
-# below (profiles/config3_fwd_bwd_warp_kernels.txt); None where not measured.
-MEASURED_TRAFFIC_BYTES = {3: 1175499489}
+PROFILE_FILE = os.path.join(ROOT, "profiles", "config3_fwd_bwd_warp_kernels.txt")
+
+
+def traffic_from_profile(kernel):
+    """HBM bytes per launch of `kernel` as the committed rocprofv3 --pmc summary records them (FETCH_SIZE +
+    WRITE_SIZE, scaled by what the same counters read for a plain copy): its line `hbm_bytes_per_launch <kernel>
+    <bytes>`.  None if the summary has no such line (the kernel that ran is not the one that was profiled)."""
+    try:
+        with open(PROFILE_FILE) as f:
+            for line in f:
+                w = line.split()
+                if len(w) == 3 and w[0] == "hbm_bytes_per_launch" and w[1] == kernel:
+                    return int(w[2])
+    except OSError:
+        pass
+    return None
 
 
 def main():
@@ -135,15 +147,16 @@ def main():
     bwd_bytes = nvox * (2 * C * esz + 12 * heads + 8 * C)
     hs = heads * (2 if C // heads == 12 else 1)       # fused columns per voxel (twelve channels: two half-heads)
     tiled = not args.generic and modet.modet_has_tiled_kernels(C, heads, k, in_dt) == 3
-    bwd_kernel = ("generic kernels" if not tiled else "bwd_fused_kernel" if k == 3 and hs <= 2 else
-                  "bwd_shared_kernel" if k == 3 else "march_pair_kernel")
+    bwd_kernel = ("generic kernels" if not tiled else "bwd_sym_kernel" if k == 3 and hs == 1 else
+                  "bwd_fused_kernel" if k == 3 and hs == 2 else "bwd_shared_kernel" if k == 3 else "march_pair_kernel")
     dom_bytes, dom_ms, dom_name = ((bwd_bytes, t_bwd, f"modet_bwd ({bwd_kernel})") if t_bwd >= t_fwd
                                   else (fwd_bytes, t_fwd, "modet_fwd"))
     achieved = dom_bytes / (dom_ms * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": dom_name, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": (MEASURED_TRAFFIC_BYTES.get(args.config)
-                            if (t_bwd >= t_fwd and not args.generic and not args.bias and not args.head_dim) else None),
+                "traffic": (traffic_from_profile(bwd_kernel)
+                            if (args.config == 3 and t_bwd >= t_fwd and not args.generic and not args.bias
+                                and not args.head_dim) else None),
                 "algorithmic_bytes": dom_bytes, "avg_launch_ms": round(dom_ms, 4)}
 
     # the same step against the vector-ALU roofline.  Algorithmic flops per window: k^3 pairs, each a d-term dot

@@ -28,20 +28,11 @@
 #pragma once
 #include "modet_common.hpp"
 #include <type_traits>
-#ifdef MODET_TUNING_ENV
-#include <stdlib.h>
-#endif
 
 namespace modet {
 namespace {
 
-#ifndef MODET_TX
-#define MODET_TX 32
-#endif
-#ifndef MODET_TY
-#define MODET_TY 8
-#endif
-constexpr int TX = MODET_TX, TY = MODET_TY, NT = TX * TY;
+constexpr int TX = 32, TY = 8, NT = TX * TY;
 constexpr float kLog2e = 1.4426950408889634f, kLn2 = 0.6931471805599453f;
 
 __device__ __forceinline__ float exp2_fast(float x) { return __builtin_amdgcn_exp2f(x); }
@@ -221,21 +212,39 @@ struct Stager {
   }
   // `plane` must point at a plane inside the tensor; ok = false: the wanted plane lies outside the volume
   // (zero padding) and the loaded values are discarded
+  __device__ __forceinline__ float4 load_slot(const E* plane, int i) const {
+    if constexpr (CH == 8) {
+      return Ld<E>::vec4(plane + goff[i]);
+    } else {
+      // six channels: the first half of a column is channels 0..3, the second channels 4, 5 and two zeros
+      // (the second load of a second half re-reads the same address: always valid, then discarded)
+      const bool second = (loff[i] >> 1) & 1;
+      const float2 a = Ld<E>::vec2(plane + goff[i]);
+      const float2 b = Ld<E>::vec2(plane + goff[i] + (second ? 0 : 2));
+      return make_float4(a.x, a.y, second ? 0.f : b.x, second ? 0.f : b.y);
+    }
+  }
   __device__ __forceinline__ void fetch(const E* plane, bool ok) {
 #pragma unroll
-    for (int i = 0; i < P::NL; ++i) {
-      if constexpr (CH == 8) {
-        v[i] = Ld<E>::vec4(plane + goff[i]);
-      } else {
-        // six channels: the first half of a column is channels 0..3, the second channels 4, 5 and two zeros
-        // (the second load of a second half re-reads the same address: always valid, then discarded)
-        const bool second = (loff[i] >> 1) & 1;
-        const float2 a = Ld<E>::vec2(plane + goff[i]);
-        const float2 b = Ld<E>::vec2(plane + goff[i] + (second ? 0 : 2));
-        v[i] = make_float4(a.x, a.y, second ? 0.f : b.x, second ? 0.f : b.y);
-      }
-    }
+    for (int i = 0; i < P::NL; ++i) v[i] = load_slot(plane, i);
     plane_ok = ok;
+  }
+  // a second plane staged with the same patch geometry keeps only its values: `vals` and `ok` live with the caller
+  __device__ __forceinline__ void fetch_into(float4 (&vals)[P::NL], const E* plane) const {
+#pragma unroll
+    for (int i = 0; i < P::NL; ++i) vals[i] = load_slot(plane, i);
+  }
+  __device__ __forceinline__ void commit_from(const float4 (&vals)[P::NL], bool ok, typename Lds<ET>::chunk* buf) const {
+    if (ok) {      // (uniform)
+#pragma unroll
+      for (int i = 0; i < P::NL; ++i)
+        if (loff[i] >= 0 && (loff[i] & 1)) Lds<ET>::put4(buf, P::NPOS, loff[i] >> 2, (loff[i] >> 1) & 1, vals[i]);
+    } else {
+#pragma unroll
+      for (int i = 0; i < P::NL; ++i)
+        if (loff[i] >= 0 && (loff[i] & 1))
+          Lds<ET>::put4(buf, P::NPOS, loff[i] >> 2, (loff[i] >> 1) & 1, make_float4(0.f, 0.f, 0.f, 0.f));
+    }
   }
   // Patch slots outside the volume (in H, W) never change: they are zeroed once per LDS buffer, and commit
   // writes the others only; a plane outside the volume (in D) is a uniform case, so nothing is selected per
@@ -519,8 +528,8 @@ struct FwdPolicy {
 #pragma unroll
     for (int c = 0; c < KW; ++c) {
       const float e = exp2_fast((float)l[c]);
-      rs += e;
-      if (c != R) ws = fmaf((float)(c - R), e, ws);
+      rs = c == 0 ? e : rs + e;
+      if (c != R) ws = (c == 0) ? (float)(c - R) * e : fmaf((float)(c - R), e, ws);
     }
     const LT rr = (LT)rs;
     plane += rr;
@@ -952,6 +961,20 @@ __device__ __forceinline__ int clamp_column(int xs, int Wh) {
   return Mem<T>::PAIR ? Wh - 2 + (xs & 1) : Wh - 1;
 }
 
+// Workgroups that share a CU compete for its vector units, and the hardware prefers the older wave: left alone,
+// the first workgroup on a CU runs at nearly full speed, the second one on what is left, and finishes the
+// last third of its march alone, when a single wave per SIMD cannot keep the vector unit busy.  Each wave
+// therefore lowers its own priority as it advances, in a sawtooth over four steps: whichever workgroup is (up to
+// three steps) behind wins the arbitration, the workgroups of a CU advance together and finish together.
+__device__ __forceinline__ void step_priority(int n) {
+  switch (n & 3) {
+    case 0: __builtin_amdgcn_s_setprio(3); break;
+    case 1: __builtin_amdgcn_s_setprio(2); break;
+    case 2: __builtin_amdgcn_s_setprio(1); break;
+    default: __builtin_amdgcn_s_setprio(0); break;
+  }
+}
+
 // One workgroup's march over its chunk.  id: logical tile index (after the XCD remap); smem: the workgroup's LDS.
 template <class Pol>
 __device__ __forceinline__ void march(const TiledParams& p, unsigned id, void* smem) {
@@ -959,11 +982,7 @@ __device__ __forceinline__ void march(const TiledParams& p, unsigned id, void* s
   typedef typename Pol::T T;
   typedef typename Pol::E E;
   constexpr int KW = Pol::KW, HS = Pol::HS, R = KW / 2;
-#ifdef MODET_NOROT
-  constexpr bool ROT = false;
-#else
   constexpr bool ROT = (KW == 3);
-#endif
   SharedPlanes<Pol, Pol::kStats>& sh = *reinterpret_cast<SharedPlanes<Pol, Pol::kStats>*>(smem);
 
   const Tile t = make_tile(p, id);
@@ -1032,6 +1051,7 @@ __device__ __forceinline__ void march(const TiledParams& p, unsigned id, void* s
     const int cur = (s - s_first) & 1;
     const bool commit_next = s + 1 <= s_last;
     const bool have_next = s + R + 1 < t.z1;
+    step_priority(s - s_first);
     march_body<Pol, PH>(st, p, t, sh, cur, lbase, s, pre, have_next, commit_next, stg, sst);
     if (!ROT) {
       // rotate by moving: role i+1 becomes role i, the refilled slot 0 becomes role KW-1
@@ -1537,17 +1557,38 @@ __device__ __forceinline__ void fused_key_half(TiledParams p, const Tile& t,
 #pragma unroll
     for (int c = 0; c < 8; ++c) acc[c] = 0.f;
     if (key_plane) {
-#pragma unroll 1                                     // (unrolled, all 27 vector reads get hoisted and spill)
-      for (int a = 0; a < 3; ++a) {                 // plane offset a - 1: query plane s - (a - 1)
-        const float4* qp = sh.q[qslot(1 - a)];
+      // 27 (dl, Q vector) pairs in nine groups of three (one window row each).  The reads of a group are issued
+      // one group ahead of its arithmetic and the order is pinned: left to itself the scheduler hoists all 27
+      // vector reads (and spills) when the loop is unrolled, and exposes the LDS latency once per plane offset
+      // when it is not.
+      const float4* qpl[3] = {sh.q[qslot(1)], sh.q[qslot(0)], sh.q[qslot(-1)]};   // query plane s - (a - 1)
+      float gd[2][3];
+      float4 gq[2][3][2];
+      auto read_group = [&](int g, int buf) __attribute__((always_inline)) {
+        const int a = g / 3, b = g % 3 - 1;
 #pragma unroll
-        for (int bc = 0; bc < 9; ++bc) {
-          const int b = bc / 3 - 1, c = bc % 3 - 1;
-          const float d = dl[a * F::DLA + gidx[bc]];
-          float qf[8];
-          Lds<float>::get8(qp, P::NPOS, (kr - b) * P::PC + kc - c * HS, qf);
-          axpy8(acc, d, qf);
+        for (int ci = 0; ci < 3; ++ci) {
+          const int c = ci - 1, pos = (kr - b) * P::PC + kc - c * HS;
+          gd[buf][ci] = dl[a * F::DLA + gidx[(b + 1) * 3 + ci]];
+          gq[buf][ci][0] = qpl[a][pos];
+          gq[buf][ci][1] = qpl[a][P::NPOS + pos];
         }
+      };
+      read_group(0, 0);
+#pragma unroll
+      for (int g = 0; g < 9; ++g) {
+        if (g + 1 < 9) read_group(g + 1, (g + 1) & 1);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int ci = 0; ci < 3; ++ci) {
+          const float d = gd[g & 1][ci];
+          const float4 u = gq[g & 1][ci][0], v = gq[g & 1][ci][1];
+          acc[0] = fmaf(d, u.x, acc[0]); acc[1] = fmaf(d, u.y, acc[1]);
+          acc[2] = fmaf(d, u.z, acc[2]); acc[3] = fmaf(d, u.w, acc[3]);
+          acc[4] = fmaf(d, v.x, acc[4]); acc[5] = fmaf(d, v.y, acc[5]);
+          acc[6] = fmaf(d, v.z, acc[6]); acc[7] = fmaf(d, v.w, acc[7]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
       }
     }
     if constexpr (BIAS) {
@@ -1638,15 +1679,321 @@ bwd_fused_kernel(TiledParams p, float* dQ, float* dK) {
     p.out = dQ;
     fused_query_half<T, LT, HS, BIAS>(p, t, sh, tid);
   } else {
+    // every SIMD holds one wave of each half; the key half's step is the longer one (the query half waits for it
+    // at the barrier), so its waves win the arbitration for the vector unit and the query wave fills the gaps
+    __builtin_amdgcn_s_setprio(3);
     p.out = dK;
     fused_key_half<T, LT, HS, BIAS>(p, t, sh, tid);
   }
 }
 
+// ---- backward with every logit computed once, one 256-lane workgroup per tile (k = 3, one head) -----------
+// The same arithmetic as bwd_fused_kernel, but the lanes that compute dl for a query column (phase A) afterwards
+// gather dK for the key of the same column (phase B), and two such workgroups share a CU.  In the 512-lane
+// kernel the query wave and the key wave of a SIMD meet at a barrier every step, so a step lasts as long as the
+// slower of the two, each of them alone on its SIMD for part of it, and a single wave cannot issue fast enough to
+// keep the vector unit busy.  Here the two waves of a SIMD belong to different workgroups and run freely against
+// each other: whenever one waits (barrier, LDS, memory) the other has arithmetic to issue.  What makes two
+// workgroups fit: one K plane (not two: the next one is committed in phase B, when nobody reads it), a ring of
+// three Q planes (plane s+1 is committed in phase A, when nobody gathers), one dl buffer: 79 KB.
+//   step s (K plane s in LDS; roles = query planes s-1, s, s+1):
+//     phase A  [refill newest role from registers] [commit Q plane s+1 and its ring statistics] [dl, dQ of 27
+//              pairs -> dl] [issue loads: own column of plane s+2, K plane s+1] [store dQ of plane s-1]   barrier
+//     phase R  [ring queries of this step -> dl]  (they read Q plane s+1, committed in phase A)            barrier
+//     phase B  [gather dK of plane s] [commit K plane s+1] [store dK] [issue loads: Q plane s+2]           barrier
+template <class T, class LT, int HS_, bool BIAS>
+struct SymBwd {
+  typedef FusedBwd<T, LT, HS_, BIAS> F;
+  typedef typename F::P P;
+  static constexpr int QR = 3;
+  struct Lds {
+    float4 k[2 * P::NPOS];
+    float4 q[QR][2 * P::NPOS];
+    float4 sa[QR][F::NRP];
+    float sc[QR][F::NRP];
+    float dl[F::DLN];
+    BiasTable<LT, 3, HS_, BIAS> bias;
+  };
+};
+
+template <class T, class LT, int HS, bool BIAS>
+__global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2)))
+bwd_sym_kernel(TiledParams p, float* dQ, float* dK) {
+  typedef SymBwd<T, LT, HS, BIAS> S;
+  typedef typename S::F F;
+  typedef typename F::Dq Dq;
+  typedef typename F::P P;
+  typedef typename Mem<T>::E E;
+  constexpr int KW = 3, NRP = F::NRP, NRQ = 3 * NRP, RPL = (NRQ + NT - 1) / NT;
+  __shared__ typename S::Lds sh;
+  const int tid = threadIdx.x;
+  const Tile t = make_tile(p, xcd_remap(blockIdx.x, gridDim.x));
+  const long long pw = (long long)p.H * p.Wh;
+  const long long wb = (long long)t.b * p.D * pw;
+  const E* Kb = (const E*)p.K + (long long)t.b * p.D * t.plane_elems;
+  const E* Qb = (const E*)p.Q + (long long)t.b * p.D * t.plane_elems;
+  const int cy = min(t.y, p.H - 1), cxs = clamp_column<T>(t.xs, p.Wh);
+  const E* Ob = Qb + ((long long)cy * p.Wh + cxs) * Mem<T>::CH;            // own query column
+  const long long ccol = wb + (long long)cy * p.Wh + cxs;
+  const int lbase = t.ty * P::PC + t.tx;
+  const int s_lo = t.z0 - 1, s_hi = t.z1;
+  const int zlo = max(t.z0 - 1, 0), zhi = min(t.z1 + 1, p.D);              // query planes whose dl is wanted
+
+  // ---- staging: the K plane in the stager's own registers, the Q plane (same patch geometry) in qv
+  Stager<KW, HS, T, float> stg;
+  stg.init(tid, t.y0, t.xs0, p.H, p.Wh);
+  stg.zero_outside(sh.k);
+#pragma unroll
+  for (int j = 0; j < S::QR; ++j) stg.zero_outside(sh.q[j]);
+  float4 qv[P::NL];
+  bool q_ok = false;
+  int rpr, rpc;
+  F::ring_rc(min(tid, NRP - 1), rpr, rpc);
+  const int rgy = t.y0 - 1 + rpr, rgx = t.xs0 - HS + rpc;
+  const bool ring_in = tid < NRP && rgy >= 0 && rgy < p.H && rgx >= 0 && rgx < p.Wh;
+  const long long ring_w = (long long)min(max(rgy, 0), p.H - 1) * p.Wh + min(max(rgx, 0), p.Wh - 1);
+  float r_lse, r_g[3], r_f[3];       // statistics of ring position `tid` of the Q plane fetched last
+  auto fetch_k = [&](int z) {
+    stg.fetch(Kb + (long long)clampi(z, 0, p.D - 1) * t.plane_elems, z >= 0 && z < p.D);
+  };
+  auto fetch_q = [&](int z) {
+    const int zc = clampi(z, 0, p.D - 1);
+    stg.fetch_into(qv, Qb + (long long)zc * t.plane_elems);
+    const long long w = (wb + (long long)zc * pw + ring_w) >> Win<T>::SH;
+    r_lse = p.lse_in[w];
+    r_g[0] = p.dphi[w * 3]; r_g[1] = p.dphi[w * 3 + 1]; r_g[2] = p.dphi[w * 3 + 2];
+    r_f[0] = p.phi_in[w * 3]; r_f[1] = p.phi_in[w * 3 + 1]; r_f[2] = p.phi_in[w * 3 + 2];
+    q_ok = z >= 0 && z < p.D;
+  };
+  auto commit_q = [&](int slot) {
+    stg.commit_from(qv, q_ok, sh.q[slot]);
+    if (tid < NRP) {
+      const bool ok = ring_in && q_ok;
+      const float g0 = ok ? r_g[0] : 0.f, g1 = ok ? r_g[1] : 0.f, g2 = ok ? r_g[2] : 0.f;
+      sh.sa[slot][tid] = make_float4(ok ? -r_lse * kLog2e * Win<T>::kShare : 0.f, g0, g1, g2);
+      sh.sc[slot][tid] = -(g0 * r_f[0] + g1 * r_f[1] + g2 * r_f[2]);
+    }
+  };
+  // Q slot of plane s - 1 + j in phase PH: (PH + j) % 3
+  fetch_q(s_lo - 1); commit_q(0);
+  fetch_q(s_lo); commit_q(1);
+  fetch_k(s_lo); stg.commit(sh.k);
+  fetch_q(s_lo + 1);
+
+  // ---- this lane's ring queries, packed: [0] = ring position | rq << 9 | ra << 16 | ring row << 18 | negative
+  // fixed offset component << 19 | valid(tt) << 20.. | used << 31;  [1] = key position of tt = 0, 1, 2 (10 bits each)
+  unsigned rdesc[RPL][2];
+#pragma unroll
+  for (int i = 0; i < RPL; ++i) {
+    const int e = tid + i * NT;
+    const bool used = e < NRQ;
+    const int ra = used ? e / NRP : 1, rq = used ? e - ra * NRP : 0;
+    int qr_, qc_;
+    F::ring_rc(rq, qr_, qc_);
+    const int ring_pos = qr_ * P::PC + qc_;
+    const bool rowq = qr_ == 0 || qr_ == P::PR - 1;
+    const bool neg = rowq ? qr_ != 0 : qc_ >= HS;      // row 0 looks down (b = +1), the left columns look right (c = +1)
+    unsigned da = (unsigned)ring_pos | (unsigned)rq << 9 | (unsigned)ra << 16 | (rowq ? 1u << 18 : 0u) |
+                  (neg ? 1u << 19 : 0u) | (used ? 1u << 31 : 0u), db = 0;
+#pragma unroll
+    for (int tt = 0; tt < 3; ++tt) {
+      int b, c;
+      const bool valid = F::ring_offset(qr_, qc_, tt, b, c);
+      const int kpos = valid ? (qr_ + b) * P::PC + qc_ + c * HS : ring_pos;
+      da |= valid ? 1u << (20 + tt) : 0u;
+      db |= (unsigned)kpos << (10 * tt);
+    }
+    rdesc[i][0] = da; rdesc[i][1] = db;
+  }
+  // ---- gather addresses: the query of offset (b, c) sits at patch position (kr - b, kc - c * HS)
+  const int kr = t.ty + 1, kc = t.tx + HS;
+  int gidx[9];
+#pragma unroll
+  for (int bc = 0; bc < 9; ++bc) {
+    const int b = bc / 3 - 1, c = bc % 3 - 1;
+    const int qr = kr - b, qc = kc - c * HS;
+    const bool inside = qr >= 1 && qr <= TY && qc >= HS && qc < HS + TX;
+    const bool row = qr == 0 || qr == P::PR - 1;
+    gidx[bc] = inside ? (bc * NT + (qr - 1) * TX + (qc - HS))
+                      : (9 * NT + F::ring_index(qr, qc) * 3 + (row ? c + 1 : b + 1));
+  }
+  const int db_row = tid >> 3, db_seg = tid & 7;      // bias gradient: see bwd_fused_kernel
+  const bool db_on = BIAS && p.dbias_acc != nullptr && db_row < 27;
+  double db_sum[4] = {0.0, 0.0, 0.0, 0.0};
+
+  // ---- the query roles
+  typename Dq::State st[KW];
+#pragma unroll
+  for (int i = 0; i < KW; ++i) Dq::reset(st[i]);
+  typename Dq::Pre pre;
+  auto prefetch = [&](int z) {
+    const int zc = clampi(z, 0, p.D - 1);
+    Dq::prefetch(p, Ob + (long long)zc * t.plane_elems, ccol + zc * pw, pre);
+  };
+  auto no_query = [&]() {      // a lane without a query: its dl must be zero for the keys next to it
+    if (!t.lane_ok) { pre.g0 = pre.g1 = pre.g2 = 0.f; pre.f0 = pre.f1 = pre.f2 = 0.f; }
+  };
+  if (s_lo >= zlo) {
+    prefetch(s_lo);
+    Dq::arrived(pre);
+    no_query();
+    Dq::refill(st[1], pre, p);
+  }
+  prefetch(s_lo + 1);
+  if constexpr (BIAS) fill_bias_table<T, LT, KW, HS>(sh.bias.v, p.bias, tid, NT);
+  const LT* bl = lane_bias<Dq>(sh, t.xs);
+  __syncthreads();
+
+  auto one_step = [&](auto PHc, int s) __attribute__((always_inline)) {
+    constexpr int PH = decltype(PHc)::value;
+    constexpr int Q0 = PH % 3, Q1 = (PH + 1) % 3, Q2 = (PH + 2) % 3;      // Q slots of the planes s - 1, s, s + 1
+    const bool fill_new = s + 1 >= zlo && s + 1 < zhi;
+    const unsigned active = active_roles<KW>(s, zlo, zhi);
+    const bool store_old = s - 1 >= t.z0 && s - 1 < t.z1 && t.lane_ok;
+    const bool key_plane = s >= t.z0 && s < t.z1;
+    step_priority(s - s_lo);
+    // ================= phase A
+    Dq::arrived(pre);
+    no_query();
+    if (fill_new) Dq::refill(st[(KW - 1 + PH) % KW], pre, p);
+    commit_q(Q2);      // Q plane s + 1 replaces plane s - 2
+    if (active == 7u) Dq::template step_emit<PH, true, F::DLA>(st, sh.k, lbase, active, sh.dl, tid, bl);
+    else Dq::template step_emit<PH, false, F::DLA>(st, sh.k, lbase, active, sh.dl, tid, bl);
+    prefetch(s + 2);
+    fetch_k(s + 1);
+    if (store_old) store_col_scaled<Mem<T>::CH>(dQ, t.col + (long long)(s - 1) * pw, st[PH % KW].acc, p.scale);
+    __syncthreads();
+    // ================= phase R: the pairs of the ring queries that point into the patch.  A lane's ring query
+    // (number e = tid + i * NT: plane offset index ra = e / NRP, query plane s + 1 - ra, ring position rq) and its
+    // three key positions are fixed for the whole march and packed into rdesc; all LDS reads are issued before
+    // the three dot products, which advance together.
+    if (key_plane) {
+#pragma unroll
+      for (int i = 0; i < RPL; ++i) {
+        unsigned da = rdesc[i][0], db = rdesc[i][1];
+        asm volatile("" : "+v"(da), "+v"(db));      // unpacked here, in every step: hoisted out of the loop, the
+        if (!(da >> 31)) continue;                   // addresses derived from them would occupy (and spill) registers
+        const int ring_pos = da & 511, rq = (da >> 9) & 127, ra = (da >> 16) & 3;
+        const bool rowq = (da >> 18) & 1;             // ring row: its offsets differ in c; ring column: in b
+        const float sgn = (da & (1u << 19)) ? -1.f : 1.f;   // the fixed component of the offset
+        const int sl = ra == 0 ? Q2 : (ra == 1 ? Q1 : Q0);
+        float qf[8], kf[3][8];
+        Lds<float>::get8(sh.q[sl], P::NPOS, ring_pos, qf);
+        const float4 a4 = sh.sa[sl][rq];
+        const float c4 = sh.sc[sl][rq];
+#pragma unroll
+        for (int tt = 0; tt < 3; ++tt) Lds<float>::get8(sh.k, P::NPOS, (db >> (10 * tt)) & 1023, kf[tt]);
+        LT qd[8];
+        widen8<LT, float>(qf, qd);
+        // t = g.o - g.phi with o = (ra - 1, b, c): u + (tt - 1) * v
+        const float base = fmaf((float)(ra - 1), a4.y, c4);
+        const float u = fmaf(sgn, rowq ? a4.z : a4.w, base), v = rowq ? a4.w : a4.z;
+        LT l[3];
+#pragma unroll
+        for (int tt = 0; tt < 3; ++tt) {
+          LT kd[8];
+          widen8<LT, float>(kf[tt], kd);
+          l[tt] = fma(dot8<LT>(qd, kd), (LT)p.qscale, (LT)a4.x);
+        }
+#pragma unroll
+        for (int tt = 0; tt < 3; ++tt) {
+          if constexpr (BIAS) {
+            const int b = rowq ? (sgn > 0.f ? 1 : -1) : tt - 1, c = rowq ? tt - 1 : (sgn > 0.f ? 1 : -1);
+            l[tt] += sh.bias.v[((ra * 3 + b + 1) * 3 + c + 1) * HS + (ring_pos % P::PC) % HS];
+          }
+          const LT lw = whole_logit<T, LT>(l[tt]);
+          const float tq = fmaf((float)(tt - 1), v, u);
+          const bool valid = (da >> (20 + tt)) & 1;
+          sh.dl[ra * F::DLA + 9 * NT + rq * 3 + tt] = valid ? exp2_fast((float)lw) * tq : 0.f;
+        }
+      }
+    }
+    __syncthreads();
+    // ================= phase B
+    float acc[8];
+#pragma unroll
+    for (int c = 0; c < 8; ++c) acc[c] = 0.f;
+    if (key_plane) {
+      // 27 (dl, Q vector) pairs in nine groups of three (one window row each); the reads of a group are issued
+      // one group ahead of its arithmetic and the order is pinned
+      const float4* qpl[3] = {sh.q[Q2], sh.q[Q1], sh.q[Q0]};      // a = 0, 1, 2: query plane s + 1 - a
+      float gd[2][3];
+      float4 gq[2][3][2];
+      auto read_group = [&](int g, int buf) __attribute__((always_inline)) {
+        const int a = g / 3, b = g % 3 - 1;
+#pragma unroll
+        for (int ci = 0; ci < 3; ++ci) {
+          const int c = ci - 1, pos = (kr - b) * P::PC + kc - c * HS;
+          gd[buf][ci] = sh.dl[a * F::DLA + gidx[(b + 1) * 3 + ci]];
+          gq[buf][ci][0] = qpl[a][pos];
+          gq[buf][ci][1] = qpl[a][P::NPOS + pos];
+        }
+      };
+      read_group(0, 0);
+#pragma unroll
+      for (int g = 0; g < 9; ++g) {
+        if (g + 1 < 9) read_group(g + 1, (g + 1) & 1);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int ci = 0; ci < 3; ++ci) {
+          const float d = gd[g & 1][ci];
+          const float4 u = gq[g & 1][ci][0], v = gq[g & 1][ci][1];
+          acc[0] = fmaf(d, u.x, acc[0]); acc[1] = fmaf(d, u.y, acc[1]);
+          acc[2] = fmaf(d, u.z, acc[2]); acc[3] = fmaf(d, u.w, acc[3]);
+          acc[4] = fmaf(d, v.x, acc[4]); acc[5] = fmaf(d, v.y, acc[5]);
+          acc[6] = fmaf(d, v.z, acc[6]); acc[7] = fmaf(d, v.w, acc[7]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+    if constexpr (BIAS) {
+      const int da = db_row / 9, zq = s + 1 - da;
+      if (db_on && zq >= t.z0 && zq < t.z1) {
+        const float4* src = reinterpret_cast<const float4*>(sh.dl + da * F::DLA + (db_row - da * 9) * NT + db_seg * 32);
+        float4 sum = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const float4 v = src[(i + db_row) & 7];
+          sum.x += v.x; sum.y += v.y; sum.z += v.z; sum.w += v.w;
+        }
+        db_sum[0] += (double)sum.x; db_sum[1] += (double)sum.y; db_sum[2] += (double)sum.z; db_sum[3] += (double)sum.w;
+      }
+    }
+    stg.commit(sh.k);      // K plane s + 1 (nobody reads the K plane in this phase)
+    if (key_plane && t.lane_ok) store_col_scaled<Mem<T>::CH>(dK, t.col + (long long)s * pw, acc, p.scale);
+    fetch_q(s + 2);
+    __syncthreads();
+  };
+  {
+    int s = s_lo;      // the three phases in sequence: the state never changes registers
+    while (true) {
+      one_step(std::integral_constant<int, 0>(), s); if (++s > s_hi) break;
+      one_step(std::integral_constant<int, 1>(), s); if (++s > s_hi) break;
+      one_step(std::integral_constant<int, 2>(), s); if (++s > s_hi) break;
+    }
+  }
+  if constexpr (BIAS) {
+    if (p.dbias_acc != nullptr) {
+      constexpr int SH = Win<T>::SH, NH = HS >> SH;
+      double hsum[NH];
+#pragma unroll
+      for (int h = 0; h < NH; ++h) {
+        double v = 0.0;
+#pragma unroll
+        for (int c = h << SH; c < 4; c += HS) v += db_sum[c];
+#pragma unroll
+        for (int m = 1; m < 8; m <<= 1) v += __shfl_xor(v, m);
+        hsum[h] = v;
+      }
+      if (db_on && db_seg == 0) {
+#pragma unroll
+        for (int h = 0; h < NH; ++h) atomicAdd(p.dbias_acc + h * 27 + db_row, hsum[h]);
+      }
+    }
+  }
+}
+
 // ---- launch ------------------------------------------------------------------------------------------
-#ifndef MODET_WAVES
-#define MODET_WAVES 2
-#endif
 
 int compute_units() {
   static int n = 0;
@@ -1692,9 +2039,6 @@ TiledParams make_params(const Geo& g, int wgs_per_cu, int wgs_per_tile = 1) {
   p.ntx = (p.Wh + TX - 1) / TX;
   p.nty = (g.H + TY - 1) / TY;
   int zc = chunk_length((long long)p.ntx * p.nty * g.B * wgs_per_tile, g.D, g.k, wgs_per_cu);
-#ifdef MODET_TUNING_ENV
-  if (const char* e = getenv("MODET_ZC")) zc = atoi(e);
-#endif
   if (zc > g.D) zc = g.D;
   if (zc < 1) zc = 1;
   p.ZC = zc;
@@ -1709,7 +2053,7 @@ inline unsigned nblocks(const TiledParams& p) { return (unsigned)((long long)p.n
 
 // waves per SIMD the register allocator is asked to make room for: the fp64 state of the fp32-input
 // kernels and the five in-flight planes of k = 5 fit two, the all-fp32 state of k = 3 fits three
-template <class LT, int KW> struct Waves { static constexpr int value = MODET_WAVES; };
+template <class LT, int KW> struct Waves { static constexpr int value = 2; };
 template <> struct Waves<float, 3> { static constexpr int value = 3; };
 
 // workgroups of one kernel instantiation that are resident on a CU (registers and LDS decide)

@@ -26,6 +26,7 @@ def unfold_modet(Q, K, heads, k, scale, bias=None):
     attn = torch.softmax(logits, dim=-1)
     V = torch.tensor(list(itertools.product(range(-r, r + 1), repeat=3)), dtype=Q.dtype)
     phi = attn @ V
+    unfold_modet.lse = torch.logsumexp(logits, dim=-1).permute(0, 2, 3, 4, 1)      # [B, D, H, W, heads]
     return phi.permute(0, 2, 3, 4, 1, 5), attn.permute(0, 2, 3, 4, 1, 5)
 
 
@@ -50,9 +51,11 @@ def test_p11_unfold_forward_backward(B, D, H, W, C, heads, k, dtype, with_bias):
     tphi, tattn = unfold_modet(tq, tk, heads, k, scale, tb)
     (tphi * torch.tensor(g.astype(np.float64))).sum().backward()
 
-    phi, attn = oracle.modet_fwd(Q, K, heads, k, bias=bias, dtype=dtype, want_attn=True)
+    phi, attn, lse = oracle.modet_fwd(Q, K, heads, k, bias=bias, dtype=dtype, want_attn=True, want_lse=True)
     np.testing.assert_allclose(phi, tphi.detach().numpy(), atol=1e-12)
     np.testing.assert_allclose(attn, tattn.detach().numpy(), atol=1e-12)
+    # the log-normaliser against the library's logsumexp of the unfolded logits (natural log)
+    np.testing.assert_allclose(lse, unfold_modet.lse.detach().numpy(), atol=1e-12)
     dQ, dK, db = oracle.modet_bwd(Q, K, g, heads, k, bias=bias, dtype=dtype, form="scatter", want_dbias=True)
     np.testing.assert_allclose(dQ, tq.grad.numpy(), atol=1e-12)
     np.testing.assert_allclose(dK, tk.grad.numpy(), atol=1e-12)

@@ -32,9 +32,11 @@ def test_p1_invariants(k, heads, C):
 # ---- P2: Q = 0 -> uniform attention over all k^3 (padded ones included), phi = 0 ----------
 def test_p2_zero_query_uniform():
     K = rnd(3, (1, 4, 5, 6, 8))
-    phi, attn = oracle.modet_fwd(np.zeros_like(K), K, 2, 3, dtype="f64", want_attn=True)
+    phi, attn, lse = oracle.modet_fwd(np.zeros_like(K), K, 2, 3, dtype="f64", want_attn=True, want_lse=True)
     np.testing.assert_allclose(attn, 1.0 / 27, atol=1e-15)
     np.testing.assert_allclose(phi, 0.0, atol=1e-15)
+    # 27 logits of zero: the log-normaliser is log 27 at every voxel, borders included
+    np.testing.assert_allclose(lse, np.log(27.0), rtol=0, atol=1e-14)
 
 
 # ---- P3: k = 1 ------------------------------------------------------------------------------
@@ -67,8 +69,13 @@ def test_p5_border_closed_form(t):
     K = np.broadcast_to(u, (1, 6, 6, 6, C)).copy()
     Q = t * K
     a = scale * t * float(u @ u)
-    phi = oracle.modet_fwd(Q, K, 1, 3, scale=scale, dtype="f64")
+    phi, lse = oracle.modet_fwd(Q, K, 1, 3, scale=scale, dtype="f64", want_lse=True)
     ea = np.exp(a)
+    # the log-normaliser counts the padded neighbours with logit 0: ln(n_in e^a + n_out)
+    np.testing.assert_allclose(lse[0, 0, 0, 0, 0], np.log(8 * ea + 19), rtol=1e-13)
+    np.testing.assert_allclose(lse[0, 0, 3, 2, 0], np.log(18 * ea + 9), rtol=1e-13)
+    np.testing.assert_allclose(lse[0, 0, 0, 3, 0], np.log(12 * ea + 15), rtol=1e-13)
+    np.testing.assert_allclose(lse[0, 2, 3, 3, 0], np.log(27 * ea), rtol=1e-13)      # interior: a + ln 27
     corner = 4 * (ea - 1) / (8 * ea + 19)          # 8 in-bounds neighbours, 19 padded
     np.testing.assert_allclose(phi[0, 0, 0, 0, 0], [corner] * 3, rtol=1e-13, atol=1e-15)
     np.testing.assert_allclose(phi[0, 5, 5, 5, 0], [-corner] * 3, rtol=1e-13, atol=1e-15)
@@ -77,6 +84,20 @@ def test_p5_border_closed_form(t):
     np.testing.assert_allclose(phi[0, 2, 5, 3, 0], [0, -face, 0], rtol=1e-13, atol=1e-15)
     edge = 6 * (ea - 1) / (12 * ea + 15)           # edge along W at (0,0,x): 12 in, 15 out
     np.testing.assert_allclose(phi[0, 0, 0, 3, 0], [edge, edge, 0], rtol=1e-13, atol=1e-15)
+
+
+def test_lse_large_logits_do_not_overflow():
+    u = np.array([1.0, 2.0, -1.0, 0.5])
+    K = np.broadcast_to(u, (1, 5, 5, 5, 4)).copy()
+    a = 800.0
+    Q = K * (a / float(u @ u))
+    phi, lse = oracle.modet_fwd(Q, K, 1, 3, scale=1.0, dtype="f64", want_lse=True)
+    np.testing.assert_allclose(lse[0, 2, 2, 2, 0], a + np.log(27.0), rtol=1e-14)
+    np.testing.assert_allclose(lse[0, 0, 0, 0, 0], a + np.log(8.0), rtol=1e-14)      # 19 padded weights underflow
+    Qn = -Q                                                                            # padded keys (logit 0) dominate
+    phi, lse = oracle.modet_fwd(Qn, K, 1, 3, scale=1.0, dtype="f64", want_lse=True)
+    np.testing.assert_allclose(lse[0, 0, 0, 0, 0], np.log(19.0), rtol=1e-14)
+    np.testing.assert_allclose(lse[0, 2, 2, 2, 0], -a + np.log(27.0), rtol=1e-14)
 
 
 # ---- P6: shift test: sign, axis order and offset enumeration -------------------------------
@@ -108,9 +129,10 @@ def test_p7_single_key_two_level(o):
     Q = np.full((1, D, H, W, 1), qv)
     K = np.zeros((1, D, H, W, 1))
     K[0, 3 + o[0], 3 + o[1], 3 + o[2], 0] = kv
-    phi = oracle.modet_fwd(Q, K, 1, 3, scale=scale, dtype="f64")
+    phi, lse = oracle.modet_fwd(Q, K, 1, 3, scale=scale, dtype="f64", want_lse=True)
     ea = np.exp(scale * qv * kv)
     np.testing.assert_allclose(phi[0, 3, 3, 3, 0], np.array(o) * (ea - 1) / (ea + 26), rtol=1e-13, atol=1e-15)
+    np.testing.assert_allclose(lse[0, 3, 3, 3, 0], np.log(ea + 26), rtol=1e-13)
     # (the 26 other neighbours share weight 1/(ea+26) each and their offsets sum to -o)
 
 
