@@ -51,7 +51,8 @@ enum {
  * part in the softmax with logit bias[s,o] (or 0).  w = softmax_o(l);
  * phi[p, s, :] = sum_o w_o * o  (the constant offset grid V of Eq. 4 is never materialised).
  *
- *   Q, K   in   in_dtype (fp32, or bf16 bit patterns; accumulation is fp32 either way)
+ *   Q, K   in   in_dtype (fp32, or bf16 bit patterns).  fp32 inputs: the dot products and the softmax sums
+ *               are accumulated in fp64, everything else in fp32; bf16 inputs: fp32 throughout
  *   bias   in   nullable; NULL means all zeros (the paper's initial state of B)
  *   phi    out  fp32, fully written
  *   attn   out  nullable; the softmax weights w (fp32)
@@ -92,6 +93,24 @@ int modet_bwd(const void* Q, const void* K, const float* bias, const float* dphi
 enum { MODET_WS_HAVE_STATS = 1, MODET_WS_WANT_DBIAS = 2 };
 size_t modet_bwd_workspace_bytes(int B, int D, int H, int W, int C, int heads, int k,
                                  modet_dtype in_dtype, int flags);
+
+/* modet_bwd for callers that cannot allocate or pass device scratch: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  The same computation as modet_bwd, with the workspace taken from a
+ * device array built into the library instead of the caller: MODET_STATIC_SCRATCH_BYTES bytes per GPU the
+ * library is used on, held until the process ends.  The call allocates nothing and frees nothing.
+ *
+ *   A call whose modet_bwd_workspace_bytes(...) exceeds MODET_STATIC_SCRATCH_BYTES returns MODET_ERR_WORKSPACE
+ *   (8 MiB cover the bias gradient of any shape, and the recomputed statistics of up to 524288 windows; with
+ *   phi and lse passed in, only the bias gradient needs scratch).
+ *   All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (different streams or
+ *   threads) race on it and must be serialised by the caller.  Nothing is carried from one call to the next.
+ *   Every other argument, and every error code, as in modet_bwd.
+ */
+#define MODET_STATIC_SCRATCH_BYTES (8u << 20)
+int modet_bwd_static(const void* Q, const void* K, const float* bias, const float* dphi,
+                     const float* phi, const float* lse, float* dQ, float* dK, float* dbias,
+                     int B, int D, int H, int W, int C, int heads, int k, float scale,
+                     modet_dtype in_dtype, void* stream);
 
 /* Trilinear feature warp between pyramid levels: paper Section 3.1 (the moving feature map
  * of the next level is deformed by the upsampled total field before it enters ModeT).
@@ -163,9 +182,9 @@ int modet_integrate_velocity(const float* v, float* out, float* tmp,
 int modet_set_kernel_path(int path);
 
 /* Arithmetic of the LDS-tiled kernels for fp32 inputs.  0 (default) = logits accumulated in fp64: meets
- * 1e-5 relative / 1e-6 absolute against an fp64 evaluation of Eq. 3-4.  1 = logits accumulated in fp32:
- * about twice as fast, but a logit of magnitude ~10 then carries ~1e-6 of rounding and gradients can miss
- * that tolerance by a small factor.  bf16 inputs always use fp32.  Returns the previous value.
+ * 1e-5 relative / 1e-6 absolute against an fp64 evaluation of Eq. 3-4.  1 = logits accumulated in fp32,
+ * kept for comparison: a logit of magnitude ~10 then carries ~1e-6 of rounding and gradients can miss that
+ * tolerance by a small factor.  bf16 inputs always use fp32.  Returns the previous value.
  * Process-wide, not thread safe. */
 int modet_set_math_mode(int mode);
 

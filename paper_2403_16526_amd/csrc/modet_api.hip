@@ -4,8 +4,15 @@
 #include "modet_common.hpp"
 
 #include <math.h>
+#include <mutex>
 
 using namespace modet;
+
+// Scratch of modet_bwd_static: device memory of the library's own, one copy per GPU the library is loaded on,
+// held until the process ends.  Host code must never pass this name to a kernel or a HIP call (in host code it
+// is a stand-in, not a device address): scratch_pointer() asks the runtime for the array's address on the
+// current device, once per device, and everything else uses that pointer.
+static __device__ __align__(256) unsigned char scratch[MODET_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -37,6 +44,23 @@ Geo make_geo(int B, int D, int H, int W, int C, int heads, int k, float scale) {
 }
 
 inline size_t round16(size_t n) { return (n + 15) & ~(size_t)15; }
+
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices] = {};
+std::mutex g_scratch_mutex;
+
+// address of `scratch` on the current device (looked up on the first call for that device), or NULL
+void* scratch_pointer() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) return nullptr;
+    g_scratch_ptr[dev] = ptr;
+  }
+  return g_scratch_ptr[dev];
+}
 
 }  // namespace
 
@@ -118,6 +142,32 @@ int modet_bwd(const void* Q, const void* K, const float* bias, const float* dphi
     if (e != hipSuccess) return MODET_ERR_LAUNCH;
   }
   return MODET_OK;
+}
+
+int modet_bwd_static(const void* Q, const void* K, const float* bias, const float* dphi,
+                     const float* phi, const float* lse, float* dQ, float* dK, float* dbias,
+                     int B, int D, int H, int W, int C, int heads, int k, float scale,
+                     modet_dtype in_dtype, void* stream) {
+  // the same validation order as modet_bwd up to the workspace, all of it before any HIP call
+  if (!Q || !K || !dphi || !dQ || !dK) return MODET_ERR_NULL;
+  if ((phi == nullptr) != (lse == nullptr)) return MODET_ERR_NULL;
+  int rc = check_op_shape(B, D, H, W, C, heads, k, (int)in_dtype);
+  if (rc != MODET_OK) return rc;
+  if (misaligned(Q) || misaligned(K) || misaligned(bias) || misaligned(dphi) || misaligned(phi) ||
+      misaligned(lse) || misaligned(dQ) || misaligned(dK) || misaligned(dbias))
+    return MODET_ERR_ALIGN;
+  const int flags = (phi ? MODET_WS_HAVE_STATS : 0) | (dbias ? MODET_WS_WANT_DBIAS : 0);
+  const size_t need = modet_bwd_workspace_bytes(B, D, H, W, C, heads, k, in_dtype, flags);
+  if (need > (size_t)MODET_STATIC_SCRATCH_BYTES) return MODET_ERR_WORKSPACE;      // beyond the built-in scratch
+  void* ws = nullptr;
+  if (need > 0) {
+    ws = scratch_pointer();
+    if (!ws) return MODET_ERR_LAUNCH;
+  }
+  // everything modet_bwd keeps in its workspace is written before it is read (the statistics by the forward
+  // kernel, the bias gradient's sums by a fill kernel), so the last call's contents do not matter
+  return modet_bwd(Q, K, bias, dphi, phi, lse, dQ, dK, dbias, B, D, H, W, C, heads, k, scale, in_dtype, ws,
+                   need, stream);
 }
 
 int modet_warp(const void* src, const float* field, void* out,

@@ -18,7 +18,7 @@ LIB_PATH = os.environ.get("MODET_LIBRARY") or os.path.join(_HERE, "libmodet.so")
 MODET_F32, MODET_BF16 = 0, 1
 MODET_OK = 0
 
-EXPORTS = ("modet_fwd", "modet_bwd", "modet_bwd_workspace_bytes", "modet_warp", "modet_warp_bwd", "modet_compose",
+EXPORTS = ("modet_fwd", "modet_bwd", "modet_bwd_static", "modet_bwd_workspace_bytes", "modet_warp", "modet_warp_bwd", "modet_compose",
            "modet_integrate_velocity", "modet_set_kernel_path", "modet_set_math_mode",
            "modet_has_tiled_kernels", "modet_status_string", "modet_version")
 
@@ -32,6 +32,8 @@ _lib.modet_fwd.argtypes = [_vp] * 6 + [_ci] * 7 + [_cf, _ci, _vp]
 _lib.modet_fwd.restype = _ci
 _lib.modet_bwd.argtypes = [_vp] * 9 + [_ci] * 7 + [_cf, _ci, _vp, _sz, _vp]
 _lib.modet_bwd.restype = _ci
+_lib.modet_bwd_static.argtypes = [_vp] * 9 + [_ci] * 7 + [_cf, _ci, _vp]
+_lib.modet_bwd_static.restype = _ci
 _lib.modet_bwd_workspace_bytes.argtypes = [_ci] * 7 + [_ci, _ci]
 _lib.modet_bwd_workspace_bytes.restype = _sz
 _lib.modet_warp.argtypes = [_vp] * 3 + [_ci] * 5 + [_ci, _ci, _vp]
@@ -158,6 +160,21 @@ def modet_bwd(Q, K, dphi, heads: int, k: int, scale: float = 0.0, bias=None, phi
                           _ptr(dbias), B, D, H, W, C, heads, k, float(scale), _in_dtype(Q), _ptr(workspace),
                           wbytes, _stream()))
     return (dQ, dK, dbias) if want_dbias else (dQ, dK)
+
+
+MODET_STATIC_SCRATCH_BYTES = 8 << 20
+
+
+def modet_bwd_static(Q, K, dphi, heads: int, k: int, out, scale: float = 0.0, bias=None, phi=None, lse=None,
+                     dbias=None):
+    """modet_bwd with the library's built-in scratch: nothing is allocated, here or in the library.  `out` =
+    (dQ, dK) and, when the bias gradient is wanted, `dbias` [heads, k^3] are the caller's tensors."""
+    _dev(Q, K, dphi, bias, phi, lse, dbias, *out)
+    B, D, H, W, C = Q.shape
+    dQ, dK = out
+    _check(_lib.modet_bwd_static(_ptr(Q), _ptr(K), _ptr(bias), _ptr(dphi), _ptr(phi), _ptr(lse), _ptr(dQ), _ptr(dK),
+                                 _ptr(dbias), B, D, H, W, C, heads, k, float(scale), _in_dtype(Q), _stream()))
+    return (dQ, dK, dbias) if dbias is not None else (dQ, dK)
 
 
 def modet_warp(src, field, field_half_res: bool = False, out=None):
