@@ -41,13 +41,124 @@ def traffic_from_profile(kernel):
     return None
 
 
+def bench_pyramid(args, np, torch, modet, synth):
+    """Config 4: the five-level coarse-to-fine loop for a 160x192x224 pair (Section 3.1); a step is one
+    iteration over all levels (warp, forward, composition, backward, update), `--steps` of them are timed (50
+    by default: the number of fine-tuning iterations per pair of Section 4.4)."""
+    from paper_2403_16526_amd.pyramid import PyramidLoop
+    t0 = time.time()
+    pyr = synth.make_pyramid()
+    t_gen = time.time() - t0
+    levels = [dict(Q=torch.from_numpy(l["Q"]).cuda(), K=torch.from_numpy(l["K"]).cuda(), heads=l["heads"]) for l in pyr]
+    loop = PyramidLoop(levels, eta=1.0)
+    t0 = time.perf_counter()
+    while (time.perf_counter() - t0) * 1e3 < PREWARM_MS:
+        loop.iteration()
+        torch.cuda.synchronize()
+    for _ in range(args.warmup):
+        loop.iteration()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        loop.iteration()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_iter = wall * 1e3 / args.steps
+
+    # the split: the same loop with HIP events around every library call (a run of its own: the events perturb it)
+    spans = {}
+
+    def timer(l, name, fn):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        out = fn()
+        e1.record()
+        spans.setdefault((l, name), []).append((e0, e1))
+        return out
+
+    loop.timer = timer
+    nsplit = 10
+    e_a, e_b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e_a.record()
+    for _ in range(nsplit):
+        loop.iteration()
+    e_b.record()
+    torch.cuda.synchronize()
+    loop.timer = None
+    split_iter_ms = e_a.elapsed_time(e_b) / nsplit
+    us = {k: 1e3 * sum(a.elapsed_time(b) for a, b in v) / nsplit for k, v in spans.items()}
+    per_level, lib_us = [], 0.0
+    nvn_total, alg_bytes, alg_bytes_survey = 0, 0, 0
+    for l, lv in enumerate(pyr):
+        n, C, heads = lv["D"] * lv["H"] * lv["W"], lv["C"], lv["heads"]
+        nvn_total += n * heads
+        fwd_b, bwd_b = n * (8 * C + 12 * heads), n * (8 * C + 12 * heads + 8 * C)
+        # warp: source and result once, the coarse field once (1/8 of 12 bytes per fine voxel); composition: the
+        # residual field, the coarse field, the result
+        warp_b = n * (8 * C) + n * 12 // 8 if l else 0
+        comp_b = n * 24 + n * 12 // 8 if l else 0
+        alg_bytes += fwd_b + bwd_b + warp_b + comp_b
+        alg_bytes_survey += fwd_b + bwd_b + (n * (8 * C + 12) if l else 0)
+        row = {"level": l + 1, "grid": f"{lv['D']}x{lv['H']}x{lv['W']}", "C": C, "heads": heads}
+        for name in ("warp", "fwd", "compose", "bwd"):
+            if (l, name) in us:
+                row[name + "_us"] = round(us[(l, name)], 1)
+                lib_us += us[(l, name)]
+        per_level.append(row)
+    top = pyr[-1]
+    ntop = top["D"] * top["H"] * top["W"]
+    dom_bytes = ntop * (8 * top["C"] + 12 * top["heads"] + 8 * top["C"])
+    dom_ms = us[(len(pyr) - 1, "bwd")] * 1e-3
+    achieved = dom_bytes / (dom_ms * 1e-3) / 1e9
+    roofline = {"bound": "hbm", "kernel": "modet_bwd of level 5 (bwd_sym_kernel)", "achieved": round(achieved, 1),
+                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "algorithmic_bytes": dom_bytes, "avg_launch_ms": round(dom_ms, 4)}
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        from oracle.pyramid_loop import OraclePyramidLoop
+        ol = OraclePyramidLoop([dict(Q=l["Q"].copy(), K=l["K"], heads=l["heads"]) for l in pyr], eta=1.0)
+        t0 = time.perf_counter()
+        nit = 2
+        for _ in range(nit):
+            ol.iteration()
+        dt = (time.perf_counter() - t0) / nit
+        cpu = {"value": round(nvn_total / dt, 1), "unit": "voxel-neighbourhoods/s", "cores": oracle.threads(),
+               "kind": "oracle",
+               "sample": f"{nit} of the {synth.PYRAMID_ITERS} iterations of the oracle-side loop over all five levels, "
+                         f"{dt:.2f} s per iteration ({dt * synth.PYRAMID_ITERS:.0f} s extrapolated to the whole loop)"}
+    line = {
+        "metric": "ModeT fwd+bwd voxel-neighbourhoods/sec and achieved HBM GB/s (% of peak), 1 GPU",
+        "value": round(nvn_total / (ms_per_iter * 1e-3), 1), "unit": "voxel-neighbourhoods/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_iter, 5), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "config 4: five-level pairwise-optimisation loop for a 160x192x224 pair, C=64,32,32,16,8 "
+                               "heads=8,4,4,2,1 k=3 f32; one step = one iteration over all levels (warp by the "
+                               "upsampled field, fwd, composition, bwd, update)",
+                   "untimed_prewarm_ms": PREWARM_MS, "logits": "fp64"},
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "loop_ms_total": round(ms_per_iter * args.steps, 3),
+        "per_level": per_level,
+        "libmodet_us_per_iteration": round(lib_us, 1),
+        "glue_share": round(1.0 - lib_us * 1e-3 / split_iter_ms, 4),
+        "iteration_ms_with_events": round(split_iter_ms, 4),
+        "bytes_per_iteration": alg_bytes,
+        "bytes_per_iteration_full_res_field": alg_bytes_survey,
+        "hbm_gbs": round(alg_bytes / (ms_per_iter * 1e-3) / 1e9, 1),
+        "hbm_frac": round(alg_bytes / (ms_per_iter * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+        "input_gen_s": round(t_gen, 1),
+    }
+    print(json.dumps(line))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     # the timed region is long enough to average over the box's jitter
-    ap.add_argument("--steps", type=int, default=300)
-    ap.add_argument("--warmup", type=int, default=100)
-    ap.add_argument("--config", type=int, default=3, choices=[1, 2, 3, 5])
+    ap.add_argument("--steps", type=int, default=None, help="default: 300 (config 4: its 50 iterations)")
+    ap.add_argument("--warmup", type=int, default=None, help="default: 100 (config 4: 5)")
+    ap.add_argument("--config", type=int, default=3, choices=[1, 2, 3, 4, 5])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--generic", action="store_true", help="force the generic kernels")
     ap.add_argument("--fast-logits", action="store_true",
@@ -70,6 +181,12 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     torch.cuda.set_device(0)
+    if args.config == 4:
+        args.steps = synth.PYRAMID_ITERS if args.steps is None else args.steps
+        args.warmup = 5 if args.warmup is None else args.warmup
+        return bench_pyramid(args, np, torch, modet, synth)
+    args.steps = 300 if args.steps is None else args.steps
+    args.warmup = 100 if args.warmup is None else args.warmup
     cfg = synth.CONFIGS[args.config]
     t0 = time.time()
     over = {"C": cfg["heads"] * args.head_dim} if args.head_dim else {}

@@ -156,11 +156,15 @@ int modet_warp_bwd(const void* src, const float* field, const float* dout, float
  *   out[b, p, :] = inner[b, p, :] + trilinear(outer[b], p + inner[b, p, :]),
  * the displacement of "move by inner, then by outer"; same sampling rules as modet_warp (voxel
  * units, components ordered (D, H, W), zero outside the volume).
- *   outer, inner  in   [B, D, H, W, 3] fp32; they may be the same buffer
+ *   outer_half_res == 0:  outer is [B, D, H, W, 3]; outer and inner may be the same buffer.
+ *   outer_half_res == 1:  outer is the coarser level's total field [B, D/2, H/2, W/2, 3] (D, H, W even); the
+ *       field that is sampled is its 2x upsampling with values doubled, exactly as in modet_warp with
+ *       field_half_res == 1, evaluated on the fly (it is never written to memory).
+ *   inner         in   [B, D, H, W, 3] fp32
  *   out           out  [B, D, H, W, 3] fp32; must not alias an input
  */
 int modet_compose(const float* outer, const float* inner, float* out,
-                  int B, int D, int H, int W, void* stream);
+                  int B, int D, int H, int W, int outer_half_res, void* stream);
 
 /* Integration of a stationary velocity field by scaling and squaring: paper Section 3.3.2, Eq. 6
  * (the optional diffeomorphic layer of the registration head).

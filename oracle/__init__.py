@@ -31,13 +31,18 @@ def lib():
         _lib = ctypes.CDLL(LIB)
         for name in ("oracle_modet_fwd", "oracle_modet_bwd_scatter", "oracle_modet_bwd_gather",
                      "oracle_modet_fwd_at", "oracle_modet_bwd_at", "oracle_warp", "oracle_warp_bwd",
-                     "oracle_upsample2x", "oracle_threads"):
+                     "oracle_upsample2x", "oracle_threads", "oracle_set_threads"):
             getattr(_lib, name).restype = _c_int
     return _lib
 
 
 def threads() -> int:
     return int(lib().oracle_threads())
+
+
+def set_threads(n: int) -> int:
+    """threads of the oracle's parallel loops from now on; returns the previous number."""
+    return int(lib().oracle_set_threads(int(n)))
 
 
 def _ptr(a):
@@ -179,10 +184,13 @@ def upsample2x(coarse):
     return fine
 
 
-def compose(outer, inner):
+def compose(outer, inner, outer_half_res=False):
     """Displacement of "move by inner, then by outer" (Section 3.1): inner + outer sampled at p + inner(p);
-    fields [B,D,H,W,3] (taken as fp32), float64 result."""
+    fields [B,D,H,W,3] (taken as fp32), float64 result.  outer_half_res: outer is the coarser level's field
+    [B,D/2,H/2,W/2,3] and is upsampled (2x, values doubled) first, without rounding in between."""
     inner32 = np.ascontiguousarray(inner, dtype=np.float32)
+    if outer_half_res:
+        return inner32.astype(np.float64) + warp(upsample2x(outer), inner32, dtype="f64")
     return inner32.astype(np.float64) + warp(outer, inner32)
 
 

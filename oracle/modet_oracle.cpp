@@ -487,4 +487,16 @@ int oracle_threads(void) {
 #endif
 }
 
+// number of threads the parallel loops use from now on (for timing the oracle on one core); returns the old value
+int oracle_set_threads(int n) {
+#ifdef _OPENMP
+  const int old = omp_get_max_threads();
+  if (n >= 1) omp_set_num_threads(n);
+  return old;
+#else
+  (void)n;
+  return 1;
+#endif
+}
+
 }  // extern "C"

@@ -203,12 +203,15 @@ int modet_warp_bwd(const void* src, const float* field, const float* dout, float
   return e == hipSuccess ? MODET_OK : MODET_ERR_LAUNCH;
 }
 
-int modet_compose(const float* outer, const float* inner, float* out, int B, int D, int H, int W, void* stream) {
+int modet_compose(const float* outer, const float* inner, float* out, int B, int D, int H, int W,
+                  int outer_half_res, void* stream) {
   if (!outer || !inner || !out) return MODET_ERR_NULL;
   if (B < 1 || D < 1 || H < 1 || W < 1) return MODET_ERR_SHAPE;
+  if (outer_half_res != 0 && outer_half_res != 1) return MODET_ERR_SHAPE;
+  if (outer_half_res && ((D | H | W) & 1)) return MODET_ERR_SHAPE;
   if ((long long)B * D * H * W * 3 >= (1LL << 31)) return MODET_ERR_UNSUPPORTED;
   if (misaligned(outer) || misaligned(inner) || misaligned(out)) return MODET_ERR_ALIGN;
-  hipError_t e = launch_compose(outer, inner, out, B, D, H, W, 1.0f, (hipStream_t)stream);
+  hipError_t e = launch_compose(outer, inner, out, B, D, H, W, 1.0f, outer_half_res, (hipStream_t)stream);
   return e == hipSuccess ? MODET_OK : MODET_ERR_LAUNCH;
 }
 
@@ -231,7 +234,7 @@ int modet_integrate_velocity(const float* v, float* out, float* tmp, int B, int 
   for (int t = 1; t <= T; ++t) {
     float* dst = ((T - t) & 1) ? tmp : out;
     const float s = t == 1 ? ldexpf(1.0f, -T) : 1.0f;
-    if (launch_compose(src, src, dst, B, D, H, W, s, st) != hipSuccess) return MODET_ERR_LAUNCH;
+    if (launch_compose(src, src, dst, B, D, H, W, s, 0, st) != hipSuccess) return MODET_ERR_LAUNCH;
     src = dst;
   }
   return MODET_OK;

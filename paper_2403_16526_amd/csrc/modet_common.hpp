@@ -44,14 +44,15 @@ hipError_t launch_warp(const void* src, const float* field, void* out, int B, in
 // gradients of sum(dout * warp(src, field)): dsrc [B, D, H, W, C] fp32, dfield (nullable) in the shape of field
 hipError_t launch_warp_bwd(const void* src, const float* field, const float* dout, float* dsrc, float* dfield, int B,
                            int D, int H, int W, int C, int half, int dtype, hipStream_t st);
-// out = s * (inner + trilinear(outer, p + s * inner)); fields [B, D, H, W, 3] fp32
+// out = s * (inner + trilinear(outer, p + s * inner)); fields [B, D, H, W, 3] fp32.  outer_half_res (with s = 1):
+// outer is [B, D/2, H/2, W/2, 3] and is upsampled 2x (values doubled) on the fly
 hipError_t launch_compose(const float* outer, const float* inner, float* out, int B, int D, int H, int W, float s,
-                          hipStream_t st);
+                          int outer_half_res, hipStream_t st);
 
-// LDS-tiled kernels (head size 8)
+// LDS-tiled kernels (heads of 8, 6 or 12 channels)
 bool tiled_fwd_supported(int d, int heads, int k, int dtype);
 bool tiled_bwd_supported(int d, int heads, int k, int dtype);
-// fast_logits: fp32 instead of fp64 dot products for fp32 inputs (about twice as fast, logits good to ~1e-6 only)
+// fast_logits: fp32 instead of fp64 dot products for fp32 inputs (logits good to ~1e-6 only)
 hipError_t launch_fwd_tiled(const Geo& g, int dtype, bool fast_logits, const void* Q, const void* K,
                             const float* bias, float* phi, float* lse, hipStream_t st);
 struct BwdTensors {

@@ -508,13 +508,83 @@ compose_kernel(const float* __restrict__ outer, const float* __restrict__ inner,
   *reinterpret_cast<Disp*>(out + v * 3) = r;
 }
 
+// The same with the outer field given at half resolution [B, D/2, H/2, W/2, 3]: the value of the 2x upsampled
+// field (values doubled) at each of the eight fine corners around p + inner(p) is itself a trilinear mix of
+// coarse voxels, and per axis the two fine corners together touch at most three consecutive coarse voxels.  The
+// two interpolations are folded into one table of three weights per axis (fp64: the factors are exact, the
+// result is rounded once) over a 3 x 3 x 3 coarse neighbourhood, so the upsampled field is never materialised.
+// Fine corners outside the volume contribute nothing (zero padding of the fine field); inside, the upsampling
+// clamps its coarse coordinates like the warp's.
+__device__ __forceinline__ void axis_table(int i0, float t, int N, int& base, double (&w)[3]) {
+  const int Nc = N >> 1;
+  w[0] = w[1] = w[2] = 0.0;
+  base = -1;
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const int i = i0 + j;
+    if ((unsigned)i >= (unsigned)N) continue;                    // this fine corner is outside: weight 0
+    const double cw = j ? (double)t : 1.0 - (double)t;
+    const int lo = coarse_lo(i), hi = min(lo + 1, Nc - 1);
+    const double f = (i == 0 || hi == lo) ? 0.0 : ((i & 1) ? 0.25 : 0.75);
+    if (base < 0) base = lo;
+    w[lo - base] += cw * (1.0 - f);
+    w[hi - base] += cw * f;
+  }
+  if (base < 0) base = 0;
+}
+
+__global__ void __launch_bounds__(kThreads)
+compose_up_kernel(const float* __restrict__ outer_c, const float* __restrict__ inner, float* __restrict__ out, int B,
+                  int D, int H, int W) {
+  const int nvox = B * D * H * W;
+  const int v = blockIdx.x * kThreads + threadIdx.x;
+  if (v >= nvox) return;
+  int t = v;
+  const int x = t % W; t /= W;
+  const int y = t % H; t /= H;
+  const int z = t % D;
+  const int b = t / D;
+  const Disp iv = *reinterpret_cast<const Disp*>(inner + v * 3);
+  const float fz = floorf(iv.z), fy = floorf(iv.y), fx = floorf(iv.x);
+  const float tz = iv.z - fz, ty = iv.y - fy, tx = iv.x - fx;
+  const int z0 = z + (int)fminf(fmaxf(fz, -1.0e6f), 1.0e6f);
+  const int y0 = y + (int)fminf(fmaxf(fy, -1.0e6f), 1.0e6f);
+  const int x0 = x + (int)fminf(fmaxf(fx, -1.0e6f), 1.0e6f);
+  int bz, by, bx;
+  double wz[3], wy[3], wx[3];
+  axis_table(z0, tz, D, bz, wz);
+  axis_table(y0, ty, H, by, wy);
+  axis_table(x0, tx, W, bx, wx);
+  const int Dc = D >> 1, Hc = H >> 1, Wc = W >> 1;
+  const float* ob = outer_c + b * (Dc * Hc * Wc * 3);
+  Disp val[27];
+#pragma unroll
+  for (int c = 0; c < 27; ++c) {      // all loads first, from clamped addresses (a clamped one has weight 0)
+    const int zi = min(bz + c / 9, Dc - 1), yi = min(by + (c / 3) % 3, Hc - 1), xi = min(bx + c % 3, Wc - 1);
+    val[c] = *reinterpret_cast<const Disp*>(ob + ((zi * Hc + yi) * Wc + xi) * 3);
+  }
+  double acc[3] = {0.0, 0.0, 0.0};
+#pragma unroll
+  for (int c = 0; c < 27; ++c) {
+    const double w = wz[c / 9] * wy[(c / 3) % 3] * wx[c % 3];
+    acc[0] = fma(w, (double)val[c].z, acc[0]);
+    acc[1] = fma(w, (double)val[c].y, acc[1]);
+    acc[2] = fma(w, (double)val[c].x, acc[2]);
+  }
+  Disp r;
+  r.z = (float)((double)iv.z + 2.0 * acc[0]); r.y = (float)((double)iv.y + 2.0 * acc[1]);
+  r.x = (float)((double)iv.x + 2.0 * acc[2]);
+  *reinterpret_cast<Disp*>(out + v * 3) = r;
+}
+
 }  // namespace
 
 hipError_t launch_compose(const float* outer, const float* inner, float* out, int B, int D, int H, int W, float s,
-                          hipStream_t st) {
+                          int outer_half_res, hipStream_t st) {
   const long long nvox = (long long)B * D * H * W;
-  hipLaunchKernelGGL(compose_kernel, dim3((unsigned)((nvox + kThreads - 1) / kThreads)), dim3(kThreads), 0, st, outer,
-                     inner, out, B, D, H, W, s);
+  const dim3 grid((unsigned)((nvox + kThreads - 1) / kThreads)), block(kThreads);
+  if (outer_half_res) hipLaunchKernelGGL(compose_up_kernel, grid, block, 0, st, outer, inner, out, B, D, H, W);
+  else hipLaunchKernelGGL(compose_kernel, grid, block, 0, st, outer, inner, out, B, D, H, W, s);
   return hipGetLastError();
 }
 

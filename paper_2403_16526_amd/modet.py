@@ -40,7 +40,7 @@ _lib.modet_warp.argtypes = [_vp] * 3 + [_ci] * 5 + [_ci, _ci, _vp]
 _lib.modet_warp_bwd.restype = _ci
 _lib.modet_warp_bwd.argtypes = [_vp] * 5 + [_ci] * 5 + [_ci, _ci, _vp]
 _lib.modet_compose.restype = _ci
-_lib.modet_compose.argtypes = [_vp] * 3 + [_ci] * 4 + [_vp]
+_lib.modet_compose.argtypes = [_vp] * 3 + [_ci] * 5 + [_vp]
 _lib.modet_integrate_velocity.restype = _ci
 _lib.modet_integrate_velocity.argtypes = [_vp] * 3 + [_ci] * 5 + [_vp]
 _lib.modet_warp.restype = _ci
@@ -200,13 +200,14 @@ def modet_warp_bwd(src, field, dout, field_half_res: bool = False, want_dfield: 
     return (dsrc, dfield) if want_dfield else dsrc
 
 
-def modet_compose(outer, inner, out=None):
-    """out[b,p,:] = inner[b,p,:] + trilinear(outer[b], p + inner[b,p,:]); fields [B,D,H,W,3] fp32."""
+def modet_compose(outer, inner, outer_half_res: bool = False, out=None):
+    """out[b,p,:] = inner[b,p,:] + trilinear(outer[b], p + inner[b,p,:]); fields [B,D,H,W,3] fp32.  With
+    outer_half_res, outer is [B,D/2,H/2,W/2,3] and stands for its 2x upsampling (values doubled)."""
     _dev(outer, inner)
     B, D, H, W, _ = inner.shape
     if out is None:
         out = torch.empty_like(inner)
-    _check(_lib.modet_compose(_ptr(outer), _ptr(inner), _ptr(out), B, D, H, W, _stream()))
+    _check(_lib.modet_compose(_ptr(outer), _ptr(inner), _ptr(out), B, D, H, W, int(bool(outer_half_res)), _stream()))
     return out
 
 

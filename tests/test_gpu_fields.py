@@ -33,6 +33,18 @@ def test_compose_matches_oracle(modet, shape):
     assert_close(out.cpu().numpy(), oracle.compose(inner, inner), "f32", f"self-compose {shape}")
 
 
+@pytest.mark.parametrize("shape", [(1, 16, 16, 16), (2, 10, 18, 70), (1, 6, 12, 130), (1, 2, 2, 2), (1, 2, 4, 2),
+                                   (1, 34, 20, 66)], ids=lambda s: "x".join(map(str, s)))
+def test_compose_with_half_resolution_outer_field(modet, shape):
+    """the coarser level's field as the outer field: upsampled 2x inside the kernel (odd / ragged coarse extents,
+    samples that leave the volume, a volume of one coarse voxel)."""
+    B, D, H, W = shape
+    coarse = synth.smooth_real_field(27, B, D // 2, H // 2, W // 2, 1.5)
+    inner = synth.smooth_real_field(28, B, D, H, W, 1.7)
+    out = modet.modet_compose(up(coarse), up(inner), outer_half_res=True)
+    assert_close(out.cpu().numpy(), oracle.compose(coarse, inner, outer_half_res=True), "f32", f"compose-up {shape}")
+
+
 @pytest.mark.parametrize("T", [0, 1, 2, 5, 7])
 @pytest.mark.parametrize("shape", [(1, 16, 16, 16), (2, 9, 19, 70), (1, 2, 3, 1)], ids=lambda s: "x".join(map(str, s)))
 def test_integrate_velocity_matches_oracle(modet, shape, T):
@@ -65,3 +77,6 @@ def test_compose_and_integrate_full_volume(modet):
     assert_close(out.cpu().numpy(), oracle.compose(outer, inner), "f32", "compose")
     phi = modet.modet_integrate_velocity(up(inner), 7)
     assert_close(phi.cpu().numpy(), oracle.integrate_velocity(inner, 7), "f32", "integrate T=7", scale=7)
+    coarse = synth.smooth_real_field(29, B, D // 2, H // 2, W // 2, 1.0)
+    out = modet.modet_compose(up(coarse), up(inner), outer_half_res=True)
+    assert_close(out.cpu().numpy(), oracle.compose(coarse, inner, outer_half_res=True), "f32", "compose-up")

@@ -22,7 +22,7 @@ def lib():
     L.modet_bwd.argtypes = [vp] * 9 + [ci] * 7 + [cf, ci, vp, sz, vp]
     L.modet_bwd_static.argtypes = [vp] * 9 + [ci] * 7 + [cf, ci, vp]
     L.modet_warp.argtypes = [vp] * 3 + [ci] * 5 + [ci, ci, vp]
-    L.modet_compose.argtypes = [vp] * 3 + [ci] * 4 + [vp]
+    L.modet_compose.argtypes = [vp] * 3 + [ci] * 5 + [vp]
     L.modet_warp_bwd.argtypes = [vp] * 5 + [ci] * 5 + [ci, ci, vp]
     L.modet_integrate_velocity.argtypes = [vp] * 3 + [ci] * 5 + [vp]
     L.modet_bwd_workspace_bytes.argtypes = [ci] * 9
@@ -126,9 +126,10 @@ def test_warp_bwd_rejects_bad_arguments(lib):
 
 
 def test_field_functions_reject_bad_arguments(lib):
-    comp = lambda a=P, b=P, o=P, B=1, D=4, H=4, W=4: lib.modet_compose(a, b, o, B, D, H, W, None)
+    comp = lambda a=P, b=P, o=P, B=1, D=4, H=4, W=4, half=0: lib.modet_compose(a, b, o, B, D, H, W, half, None)
     assert comp(a=None) == E_NULL and comp(b=None) == E_NULL and comp(o=None) == E_NULL
     assert comp(H=0) == E_SHAPE and comp(o=ODD) == E_ALIGN
+    assert comp(half=2) == E_SHAPE and comp(half=1, W=5) == E_SHAPE
     assert comp(B=64, D=512, H=512, W=512) == E_UNSUP
     integ = lambda v=P, o=P, t=P, B=1, D=4, H=4, W=4, T=3: lib.modet_integrate_velocity(v, o, t, B, D, H, W, T, None)
     assert integ(v=None) == E_NULL and integ(o=None) == E_NULL

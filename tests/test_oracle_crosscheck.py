@@ -176,3 +176,23 @@ def test_displaced_keys_peak_at_the_field():
     exp = (u[..., 0] + 1) * 9 + (u[..., 1] + 1) * 3 + (u[..., 2] + 1)
     inner = (slice(None), slice(2, -2), slice(2, -2), slice(2, -2))
     assert (am[inner] == exp[inner]).mean() > 0.6
+
+
+def test_compose_with_half_resolution_outer_field_matches_library_pipeline():
+    """composition with the coarser level's field (Section 3.1): the library interpolator (2x, half-voxel centres,
+    values doubled) followed by the library sampler at p + inner(p), both in fp64, against the oracle."""
+    B, D, H, W = 2, 10, 12, 14
+    coarse = synth.smooth_real_field(41, B, D // 2, H // 2, W // 2, 1.5)
+    inner = synth.smooth_real_field(42, B, D, H, W, 1.7)          # some samples leave the volume
+    fine = 2.0 * F.interpolate(torch.tensor(coarse.astype(np.float64)).permute(0, 4, 1, 2, 3), scale_factor=2,
+                               mode="trilinear", align_corners=False).permute(0, 2, 3, 4, 1)
+    ti = torch.tensor(inner.astype(np.float64))
+    ref = ti + grid_sample_warp(fine, ti)
+    out = oracle.compose(coarse, inner, outer_half_res=True)
+    np.testing.assert_allclose(out, ref.numpy(), atol=1e-12)
+    # a constant coarse field c upsamples to 2c everywhere: out = inner + 2c wherever all corners are inside
+    c = np.array([0.25, -0.5, 0.125], np.float32)
+    out = oracle.compose(np.broadcast_to(c, coarse.shape).copy(), inner, outer_half_res=True)
+    q = inner.astype(np.float64) + np.stack(np.meshgrid(np.arange(D), np.arange(H), np.arange(W), indexing="ij"), -1)
+    m = np.all((q >= 0) & (q <= np.array([D - 1, H - 1, W - 1])), axis=-1)
+    np.testing.assert_allclose(out[m], (inner.astype(np.float64) + 2.0 * c)[m], atol=1e-13)
