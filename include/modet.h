@@ -31,6 +31,7 @@
 extern "C" {
 #endif
 
+/* element types of Q, K, src, out: passed as int (`in_dtype`, `dtype`); any other value is MODET_ERR_UNSUPPORTED */
 typedef enum { MODET_F32 = 0, MODET_BF16 = 1 } modet_dtype;
 
 enum {
@@ -62,7 +63,7 @@ enum {
  */
 int modet_fwd(const void* Q, const void* K, const float* bias, float* phi, float* attn, float* lse,
               int B, int D, int H, int W, int C, int heads, int k, float scale,
-              modet_dtype in_dtype, void* stream);
+              int in_dtype, void* stream);
 
 /* Backward pass of Eq. 3-4 with respect to Q and K (and optionally B): the gradients the
  * pairwise-optimisation loop of Section 3.1 / Eq. 1 needs every iteration.  With g = dphi:
@@ -84,7 +85,7 @@ int modet_fwd(const void* Q, const void* K, const float* bias, float* phi, float
 int modet_bwd(const void* Q, const void* K, const float* bias, const float* dphi,
               const float* phi, const float* lse, float* dQ, float* dK, float* dbias,
               int B, int D, int H, int W, int C, int heads, int k, float scale,
-              modet_dtype in_dtype, void* workspace, size_t workspace_bytes, void* stream);
+              int in_dtype, void* workspace, size_t workspace_bytes, void* stream);
 
 /* Bytes of scratch modet_bwd needs.  flags: MODET_WS_HAVE_STATS = phi and lse will be passed in
  * (otherwise they are recomputed into the workspace, 16 bytes per window), MODET_WS_WANT_DBIAS =
@@ -92,7 +93,7 @@ int modet_bwd(const void* Q, const void* K, const float* bias, const float* dphi
  * itself reports the error). */
 enum { MODET_WS_HAVE_STATS = 1, MODET_WS_WANT_DBIAS = 2 };
 size_t modet_bwd_workspace_bytes(int B, int D, int H, int W, int C, int heads, int k,
-                                 modet_dtype in_dtype, int flags);
+                                 int in_dtype, int flags);
 
 /* modet_bwd for callers that cannot allocate or pass device scratch: code under HIP graph capture, tight serving
  * loops, harnesses that forbid hipMalloc.  The same computation as modet_bwd, with the workspace taken from a
@@ -110,7 +111,7 @@ size_t modet_bwd_workspace_bytes(int B, int D, int H, int W, int C, int heads, i
 int modet_bwd_static(const void* Q, const void* K, const float* bias, const float* dphi,
                      const float* phi, const float* lse, float* dQ, float* dK, float* dbias,
                      int B, int D, int H, int W, int C, int heads, int k, float scale,
-                     modet_dtype in_dtype, void* stream);
+                     int in_dtype, void* stream);
 
 /* Trilinear feature warp between pyramid levels: paper Section 3.1 (the moving feature map
  * of the next level is deformed by the upsampled total field before it enters ModeT).
@@ -127,7 +128,7 @@ int modet_bwd_static(const void* Q, const void* K, const float* bias, const floa
  */
 int modet_warp(const void* src, const float* field, void* out,
                int B, int D, int H, int W, int C, int field_half_res,
-               modet_dtype dtype, void* stream);
+               int dtype, void* stream);
 
 /* Adjoint of modet_warp: the gradients of L = sum(dout * warp(src, field)), which carry a gradient with
  * respect to the warped moving features (modet_bwd's dK) back to the un-warped features and to the field
@@ -148,7 +149,7 @@ int modet_warp(const void* src, const float* field, void* out,
  */
 int modet_warp_bwd(const void* src, const float* field, const float* dout, float* dsrc, float* dfield,
                    int B, int D, int H, int W, int C, int field_half_res,
-                   modet_dtype dtype, void* stream);
+                   int dtype, void* stream);
 
 /* Composition of two displacement fields: paper Section 3.1 (the total field of a pyramid level is
  * the level's residual field composed with the upsampled total field of the level below).
@@ -194,7 +195,7 @@ int modet_set_math_mode(int mode);
 
 /* Bit 0: modet_fwd, bit 1: modet_bwd run on the LDS-tiled kernels for this (head size, heads, k,
  * dtype) under path 0 (with or without bias; not when the attention weights are requested). */
-int modet_has_tiled_kernels(int C, int heads, int k, modet_dtype in_dtype);
+int modet_has_tiled_kernels(int C, int heads, int k, int in_dtype);
 
 const char* modet_status_string(int status);
 int modet_version(void);

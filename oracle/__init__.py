@@ -27,8 +27,7 @@ _i64 = ctypes.c_int64
 def lib():
     global _lib
     if _lib is None:
-        build(force=False)
-        _lib = ctypes.CDLL(LIB)
+        _lib = ctypes.CDLL(build(force=False))
         for name in ("oracle_modet_fwd", "oracle_modet_bwd_scatter", "oracle_modet_bwd_gather",
                      "oracle_modet_fwd_at", "oracle_modet_bwd_at", "oracle_warp", "oracle_warp_bwd",
                      "oracle_upsample2x", "oracle_threads", "oracle_set_threads"):

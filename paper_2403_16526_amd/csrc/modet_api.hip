@@ -68,7 +68,7 @@ extern "C" {
 
 int modet_fwd(const void* Q, const void* K, const float* bias, float* phi, float* attn, float* lse,
               int B, int D, int H, int W, int C, int heads, int k, float scale,
-              modet_dtype in_dtype, void* stream) {
+              int in_dtype, void* stream) {
   if (!Q || !K || !phi) return MODET_ERR_NULL;
   int rc = check_op_shape(B, D, H, W, C, heads, k, (int)in_dtype);
   if (rc != MODET_OK) return rc;
@@ -85,7 +85,7 @@ int modet_fwd(const void* Q, const void* K, const float* bias, float* phi, float
 }
 
 size_t modet_bwd_workspace_bytes(int B, int D, int H, int W, int C, int heads, int k,
-                                 modet_dtype in_dtype, int flags) {
+                                 int in_dtype, int flags) {
   if (check_op_shape(B, D, H, W, C, heads, k, (int)in_dtype) != MODET_OK) return 0;
   size_t n = 0;
   if (!(flags & MODET_WS_HAVE_STATS)) {
@@ -99,7 +99,7 @@ size_t modet_bwd_workspace_bytes(int B, int D, int H, int W, int C, int heads, i
 int modet_bwd(const void* Q, const void* K, const float* bias, const float* dphi,
               const float* phi, const float* lse, float* dQ, float* dK, float* dbias,
               int B, int D, int H, int W, int C, int heads, int k, float scale,
-              modet_dtype in_dtype, void* workspace, size_t workspace_bytes, void* stream) {
+              int in_dtype, void* workspace, size_t workspace_bytes, void* stream) {
   if (!Q || !K || !dphi || !dQ || !dK) return MODET_ERR_NULL;
   if ((phi == nullptr) != (lse == nullptr)) return MODET_ERR_NULL;
   int rc = check_op_shape(B, D, H, W, C, heads, k, (int)in_dtype);
@@ -147,7 +147,7 @@ int modet_bwd(const void* Q, const void* K, const float* bias, const float* dphi
 int modet_bwd_static(const void* Q, const void* K, const float* bias, const float* dphi,
                      const float* phi, const float* lse, float* dQ, float* dK, float* dbias,
                      int B, int D, int H, int W, int C, int heads, int k, float scale,
-                     modet_dtype in_dtype, void* stream) {
+                     int in_dtype, void* stream) {
   // the same validation order as modet_bwd up to the workspace, all of it before any HIP call
   if (!Q || !K || !dphi || !dQ || !dK) return MODET_ERR_NULL;
   if ((phi == nullptr) != (lse == nullptr)) return MODET_ERR_NULL;
@@ -172,7 +172,7 @@ int modet_bwd_static(const void* Q, const void* K, const float* bias, const floa
 
 int modet_warp(const void* src, const float* field, void* out,
                int B, int D, int H, int W, int C, int field_half_res,
-               modet_dtype dtype, void* stream) {
+               int dtype, void* stream) {
   if (!src || !field || !out) return MODET_ERR_NULL;
   if (B < 1 || D < 1 || H < 1 || W < 1 || C < 1) return MODET_ERR_SHAPE;
   if (field_half_res != 0 && field_half_res != 1) return MODET_ERR_SHAPE;
@@ -187,7 +187,7 @@ int modet_warp(const void* src, const float* field, void* out,
 }
 
 int modet_warp_bwd(const void* src, const float* field, const float* dout, float* dsrc, float* dfield,
-                   int B, int D, int H, int W, int C, int field_half_res, modet_dtype dtype, void* stream) {
+                   int B, int D, int H, int W, int C, int field_half_res, int dtype, void* stream) {
   if (!field || !dout || !dsrc || (dfield && !src)) return MODET_ERR_NULL;
   if (B < 1 || D < 1 || H < 1 || W < 1 || C < 1) return MODET_ERR_SHAPE;
   if (field_half_res != 0 && field_half_res != 1) return MODET_ERR_SHAPE;
@@ -252,7 +252,7 @@ int modet_set_math_mode(int mode) {
   return old;
 }
 
-int modet_has_tiled_kernels(int C, int heads, int k, modet_dtype in_dtype) {
+int modet_has_tiled_kernels(int C, int heads, int k, int in_dtype) {
   if (C < 1 || heads < 1 || C % heads != 0) return 0;
   return (tiled_fwd_supported(C / heads, heads, k, (int)in_dtype) ? 1 : 0) |
          (tiled_bwd_supported(C / heads, heads, k, (int)in_dtype) ? 2 : 0);

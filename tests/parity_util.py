@@ -24,6 +24,32 @@ def assert_close(gpu, ref, dtype="f32", what="", scale=1.0):
     return w
 
 
+def assert_dbias_close(got, ref, nterms, dtype="f32", what=""):
+    """The bias gradient sums dl over all windows of a head (nterms of either sign).  Both sides get the same
+    input bits, so the difference is rounding of the terms, which adds up like a random walk: relative 1e-5 of
+    the largest entry plus c * sqrt(nterms), c = the rounding of one term (fp32 inputs: fp64 logits, ~1e-7 per
+    term of magnitude <~ 1; bf16 inputs: fp32 logits of magnitude ~10, ~1e-6).  Returns the largest error."""
+    got, ref = np.asarray(got, np.float64), np.asarray(ref, np.float64)
+    c = 2e-7 if dtype == "f32" else 2e-6
+    tol = 1e-5 * np.abs(ref).max() + c * np.sqrt(nterms) + 1e-6
+    err = float(np.abs(got - ref).max())
+    assert err <= tol, f"{what}: dbias error {err:.3g} > {tol:.3g} (max |ref| {np.abs(ref).max():.3g}, {nterms} terms)"
+    return err
+
+
+# bf16-input cases: the inputs are the same bits on both sides and the kernels compute in fp32, so besides the
+# stated bf16 tolerance (rtol 2e-2) the results must also agree at fp32 level: ten times the fp32 tolerance leaves
+# room for fp32 logits of magnitude ~10 (1e-6 of rounding each), nothing more
+BF16_FP32_LEVEL = 10.0
+
+
+def assert_close_bf16_tight(gpu, ref, what="", scale=1.0):
+    t = TOL["f32"]
+    w = worst(gpu, ref, t["rtol"] * scale * BF16_FP32_LEVEL, t["atol"] * scale * BF16_FP32_LEVEL)
+    assert w <= 1.0, f"{what}: {w * BF16_FP32_LEVEL:.3g} x the fp32 tolerance (bf16 inputs, fp32 arithmetic)"
+    return w
+
+
 def up(a, dtype="f32"):
     """numpy -> GPU tensor; bf16 inputs arrive as uint16 bit patterns."""
     if a is None:

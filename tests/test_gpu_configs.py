@@ -6,7 +6,7 @@ import torch
 
 import oracle
 from paper_2403_16526_amd import synth
-from parity_util import assert_close, sample_windows, up
+from parity_util import assert_close, assert_close_bf16_tight, assert_dbias_close, sample_windows, up
 
 pytestmark = [pytest.mark.gpu, pytest.mark.timeout(900)]
 
@@ -102,6 +102,42 @@ def test_config5_bf16_k5_sampled(modet):
     # properties that hold at any size
     assert torch.isfinite(phi).all() and torch.isfinite(dQ).all() and torch.isfinite(dK).all()
     assert phi.abs().max().item() <= 2.0 + 1e-5
+
+
+def test_config5_full_slabs_at_both_faces(modet):
+    """config 5, batch item 1: every element of the 12 planes at each D face of the full-size run.  The oracle
+    runs on the 16-plane sub-volume those outputs depend on: k = 5 reaches two planes, and dK of a key reaches
+    four (the queries two planes away, whose softmax spans two more)."""
+    c = synth.make_config(5)
+    B, D, H, W, C, heads, k = (c[n] for n in ("B", "D", "H", "W", "C", "heads", "k"))
+    phi, lse, dQ, dK = gpu_fwd_bwd(modet, c)
+    n, halo = 12, 4
+    for lo, hi, keep in ((0, n + halo, slice(0, n)), (D - n - halo, D, slice(halo, n + halo))):
+        Qs, Ks, gs = (c[name][1:2, lo:hi].copy() for name in ("Q", "K", "dphi"))
+        ref_phi, ref_lse = oracle.modet_fwd(Qs, Ks, heads, k, dtype="bf16", want_lse=True)
+        ref_dQ, ref_dK = oracle.modet_bwd(Qs, Ks, gs, heads, k, dtype="bf16", form="gather")
+        for name, got, ref in (("phi", phi, ref_phi), ("lse", lse, ref_lse), ("dQ", dQ, ref_dQ), ("dK", dK, ref_dK)):
+            g_ = got[1:2, lo:hi][:, keep].cpu().numpy()
+            r_ = ref[:, keep]
+            assert_close(g_, r_, "bf16", f"config 5 slab {lo}:{hi} {name}")
+            assert_close_bf16_tight(g_, r_, f"config 5 slab {lo}:{hi} {name}", scale=k ** 3 / 27.0)
+
+
+def test_config5_shape_bias_gradient(modet):
+    """the k = 5 bias gradient (summed wave by wave inside the dQ march) at config 5's in-plane extents: a
+    24-plane volume of the same batch, H, W, channels and heads, with a bias, every entry against the oracle."""
+    c = synth.make_config(5, D=24)
+    B, D, H, W, C, heads, k = (c[n] for n in ("B", "D", "H", "W", "C", "heads", "k"))
+    bias = (0.5 * synth.normal(synth.BASE_SEED + 5, 9, (heads, k ** 3))).astype(np.float32)
+    Q, K, g = up(c["Q"], "bf16"), up(c["K"], "bf16"), up(c["dphi"])
+    phi, lse = modet.modet_fwd(Q, K, heads, k, bias=up(bias), want_lse=True)
+    dQ, dK, db = modet.modet_bwd(Q, K, g, heads, k, bias=up(bias), phi=phi, lse=lse, want_dbias=True)
+    ref_dQ, ref_dK, ref_db = oracle.modet_bwd(c["Q"], c["K"], c["dphi"], heads, k, bias=bias, dtype="bf16",
+                                              form="scatter", want_dbias=True)
+    assert_close_bf16_tight(dQ.cpu().numpy(), ref_dQ, "dQ", scale=k ** 3 / 27.0)
+    assert_close_bf16_tight(dK.cpu().numpy(), ref_dK, "dK", scale=k ** 3 / 27.0)
+    err = assert_dbias_close(db.cpu().numpy(), ref_db, B * D * H * W, "bf16", "config-5 shape")
+    print(f"k=5 dbias: max |ref| {np.abs(ref_db).max():.4g}, max abs error {err:.3g}")
 
 
 def test_warp_config3_shape_full_volume(modet):

@@ -6,7 +6,7 @@ import torch
 
 import oracle
 from paper_2403_16526_amd import synth
-from parity_util import assert_close, up
+from parity_util import assert_close, assert_close_bf16_tight, assert_dbias_close, up
 
 pytestmark = pytest.mark.gpu
 
@@ -56,6 +56,13 @@ SMALL = [
     (1, 30, 9, 40, 8, 1, 5, "bf16"),        # k = 5 with chunk seams (bias gradient summed wave by wave)
     (2, 23, 10, 35, 16, 2, 5, "bf16"),
     (1, 5, 6, 7, 24, 3, 3, "f32"),          # three heads: no tiled variant, generic kernels under both paths
+    # the head counts of the paper's large model (Section 4.4: 32 / 16 / 8 heads of 12 channels) and of its small
+    # one (8 heads of 6), and 16 / 32 heads of 8 channels
+    (1, 5, 6, 9, 384, 32, 3, "f32"),
+    (1, 6, 7, 11, 192, 16, 3, "bf16"),
+    (1, 9, 8, 13, 96, 8, 3, "f32"),
+    (1, 6, 5, 12, 128, 16, 3, "f32"),
+    (1, 4, 6, 10, 256, 32, 3, "bf16"),
 ]
 
 
@@ -92,8 +99,12 @@ def run_case(modet, shape, path, with_bias=False, stats="pass"):
     assert_close(dK.cpu().numpy(), ref_dK, dtype, "dK " + tag, scale=gs)
     assert_close(dQ2.cpu().numpy(), ref_dQ, dtype, "dQ (no dbias) " + tag, scale=gs)
     assert_close(dK2.cpu().numpy(), ref_dK, dtype, "dK (no dbias) " + tag, scale=gs)
-    # dbias is a sum over all voxels: its rounding grows with the number of terms
-    assert_close(db.cpu().numpy(), ref_db, dtype, "dbias " + tag, scale=10.0 * gs)
+    if dtype == "bf16":      # fp32 arithmetic on identical input bits: the result is good to fp32 level, not to 2e-2
+        for name, got, ref in (("phi", phi, ref_phi), ("dQ", dQ, ref_dQ), ("dK", dK, ref_dK), ("dQ (no dbias)", dQ2, ref_dQ),
+                               ("dK (no dbias)", dK2, ref_dK), ("lse", lse, ref_lse)):
+            assert_close_bf16_tight(got.cpu().numpy(), ref, f"{name} {tag}", scale=gs)
+    # dbias sums dl over all windows of a head
+    assert_dbias_close(db.cpu().numpy(), ref_db, B * D * H * W, dtype, "dbias " + tag)
 
 
 @pytest.mark.parametrize("shape", SMALL, ids=lambda s: "x".join(map(str, s)))
@@ -238,6 +249,7 @@ def test_errors_surface_as_exceptions(modet):
 @pytest.mark.parametrize("B,D,H,W,C,dtype,half", [
     (1, 6, 7, 9, 8, "f32", False), (2, 8, 10, 12, 8, "f32", True), (1, 5, 9, 33, 32, "f32", False),
     (1, 6, 8, 10, 3, "f32", False), (1, 6, 8, 10, 3, "f32", True), (1, 8, 6, 14, 16, "bf16", True),
+    (1, 9, 11, 70, 1, "f32", False), (2, 8, 10, 34, 1, "f32", True),      # one channel: the final image warp
     (1, 4, 5, 70, 16, "bf16", False), (1, 1, 1, 1, 4, "f32", False), (1, 2, 2, 2, 4, "f32", True),
     # channel counts of the paper's head sizes (6 and 12 per head) and odd ones: narrower vectors per lane
     (1, 6, 7, 19, 6, "f32", False), (1, 6, 8, 18, 6, "bf16", True), (2, 5, 7, 9, 12, "bf16", False),

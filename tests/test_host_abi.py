@@ -7,7 +7,7 @@ import re
 import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-LIB = os.path.join(ROOT, "paper_2403_16526_amd", "libmodet.so")
+LIB = os.environ.get("MODET_LIBRARY") or os.path.join(ROOT, "paper_2403_16526_amd", "libmodet.so")
 HDR = os.path.join(ROOT, "include", "modet.h")
 
 OK, E_NULL, E_SHAPE, E_UNSUP, E_ALIGN, E_WS, E_LAUNCH = 0, -1, -2, -3, -4, -5, -6
