@@ -71,8 +71,11 @@ int modet_fwd(const void* Q, const void* K, const float* bias, float* phi, float
  *   dQ[p, s]  = scale * sum_o dl_o(p,s) * K[p+o, s]          (in-bounds p+o only)
  *   dK[q, s]  = scale * sum_o dl_o(q-o, s) * Q[q-o, s]        (in-bounds q-o only)
  *   dbias[s,o] = sum_p dl_o(p,s)
- * Softmax weights are recomputed from Q and K, never stored.
+ * Softmax weights are recomputed from Q and K, never stored.  When the attention weights of Eq. 3 were
+ * themselves an output (modet_fwd's attn) and carry an upstream gradient dattn, the loss is
+ * sum(dphi * phi) + sum(dattn * attn) and  dl_o = w_o * (g.o + dattn_o - g.phi - sum_j w_j dattn_j).
  *
+ *   dattn      in   nullable, [B, D, H, W, heads, k^3] fp32; such a call runs on the generic kernels
  *   phi, lse   in   nullable, both or neither: the outputs of modet_fwd for the same inputs.
  *                   When NULL the library recomputes them into `workspace`.
  *   dQ, dK     out  fp32, fully overwritten (no zeroing by the caller needed)
@@ -82,16 +85,16 @@ int modet_fwd(const void* Q, const void* K, const float* bias, float* phi, float
  *                   flags that describe this call, 16-byte aligned; may be NULL when that
  *                   size is 0
  */
-int modet_bwd(const void* Q, const void* K, const float* bias, const float* dphi,
+int modet_bwd(const void* Q, const void* K, const float* bias, const float* dphi, const float* dattn,
               const float* phi, const float* lse, float* dQ, float* dK, float* dbias,
               int B, int D, int H, int W, int C, int heads, int k, float scale,
               int in_dtype, void* workspace, size_t workspace_bytes, void* stream);
 
 /* Bytes of scratch modet_bwd needs.  flags: MODET_WS_HAVE_STATS = phi and lse will be passed in
  * (otherwise they are recomputed into the workspace, 16 bytes per window), MODET_WS_WANT_DBIAS =
- * dbias will be requested (8 bytes per bias entry).  Returns 0 for invalid shapes (modet_bwd
- * itself reports the error). */
-enum { MODET_WS_HAVE_STATS = 1, MODET_WS_WANT_DBIAS = 2 };
+ * dbias will be requested (8 bytes per bias entry), MODET_WS_HAVE_DATTN = dattn will be passed in
+ * (4 bytes per window).  Returns 0 for invalid shapes (modet_bwd itself reports the error). */
+enum { MODET_WS_HAVE_STATS = 1, MODET_WS_WANT_DBIAS = 2, MODET_WS_HAVE_DATTN = 4 };
 size_t modet_bwd_workspace_bytes(int B, int D, int H, int W, int C, int heads, int k,
                                  int in_dtype, int flags);
 
@@ -108,7 +111,7 @@ size_t modet_bwd_workspace_bytes(int B, int D, int H, int W, int C, int heads, i
  *   Every other argument, and every error code, as in modet_bwd.
  */
 #define MODET_STATIC_SCRATCH_BYTES (8u << 20)
-int modet_bwd_static(const void* Q, const void* K, const float* bias, const float* dphi,
+int modet_bwd_static(const void* Q, const void* K, const float* bias, const float* dphi, const float* dattn,
                      const float* phi, const float* lse, float* dQ, float* dK, float* dbias,
                      int B, int D, int H, int W, int C, int heads, int k, float scale,
                      int in_dtype, void* stream);

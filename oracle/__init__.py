@@ -82,24 +82,27 @@ def modet_fwd(Q, K, heads, k, scale=None, bias=None, dtype="f32", want_attn=Fals
     return out if len(out) > 1 else phi
 
 
-def modet_bwd(Q, K, dphi, heads, k, scale=None, bias=None, dtype="f32", form="gather", want_dbias=False):
-    """dQ, dK [B,D,H,W,C] (float64) of L = sum(dphi * phi); form = "scatter" | "gather"."""
+def modet_bwd(Q, K, dphi, heads, k, scale=None, bias=None, dtype="f32", form="gather", want_dbias=False, dattn=None):
+    """dQ, dK [B,D,H,W,C] (float64) of L = sum(dphi * phi) (+ sum(dattn * attn) when the attention weights are an
+    output with upstream gradient dattn [B,D,H,W,heads,k^3]); form = "scatter" | "gather"."""
     Q, K = _prep(Q, K, dtype)
     B, D, H, W, C = Q.shape
     bias = _bias(bias)
     g = np.ascontiguousarray(dphi, dtype=np.float64)
     assert g.shape == (B, D, H, W, heads, 3)
+    da = None if dattn is None else np.ascontiguousarray(dattn, dtype=np.float64)
+    assert da is None or da.shape == (B, D, H, W, heads, k ** 3)
     dQ = np.empty(Q.shape, dtype=np.float64)
     dK = np.empty(Q.shape, dtype=np.float64)
     sc = _c_dbl(_scale(scale, C, heads))
     if form == "scatter":
         db = np.empty((heads, k ** 3), dtype=np.float64)
-        rc = lib().oracle_modet_bwd_scatter(_ptr(Q), _ptr(K), _ptr(bias), _ptr(g), B, D, H, W, C, heads, k, sc,
+        rc = lib().oracle_modet_bwd_scatter(_ptr(Q), _ptr(K), _ptr(bias), _ptr(g), _ptr(da), B, D, H, W, C, heads, k, sc,
                                             _DT[dtype], _ptr(dQ), _ptr(dK), _ptr(db))
         assert rc == 0
         return (dQ, dK, db) if want_dbias else (dQ, dK)
     assert not want_dbias
-    rc = lib().oracle_modet_bwd_gather(_ptr(Q), _ptr(K), _ptr(bias), _ptr(g), B, D, H, W, C, heads, k, sc,
+    rc = lib().oracle_modet_bwd_gather(_ptr(Q), _ptr(K), _ptr(bias), _ptr(g), _ptr(da), B, D, H, W, C, heads, k, sc,
                                        _DT[dtype], _ptr(dQ), _ptr(dK))
     assert rc == 0
     return dQ, dK

@@ -102,16 +102,19 @@ void weighted_offsets(const Geo& g, const double* w, double* phi) {
       }
 }
 
-// derivative of L = sum g.phi with respect to the logits of one window:
-// dl[j] = w[j] * (g.V[j] - g.phi)   (softmax Jacobian applied to t[j] = g.V[j]).
-void dlogits(const Geo& g, const double* w, const double* phi, const double* gr, double* dl) {
-  double gphi = gr[0] * phi[0] + gr[1] * phi[1] + gr[2] * phi[2];
+// derivative of L = sum g.phi (+ sum da.w when the attention weights of Eq. 3 are an output with upstream
+// gradient da) with respect to the logits of one window: the softmax Jacobian applied to
+// t[j] = g.V[j] (+ da[j]):  dl[j] = w[j] * (t[j] - sum_i w[i] t[i]),  and sum_i w[i] g.V[i] = g.phi.
+void dlogits(const Geo& g, const double* w, const double* phi, const double* gr, const double* da, double* dl) {
+  double mean = gr[0] * phi[0] + gr[1] * phi[1] + gr[2] * phi[2];
+  if (da)
+    for (int j = 0; j < g.k3; ++j) mean += w[j] * da[j];
   int j = 0;
   for (int a = -g.r; a <= g.r; ++a)
     for (int bb = -g.r; bb <= g.r; ++bb)
       for (int c = -g.r; c <= g.r; ++c, ++j) {
-        double t = gr[0] * a + gr[1] * bb + gr[2] * c;
-        dl[j] = w[j] * (t - gphi);
+        double t = gr[0] * a + gr[1] * bb + gr[2] * c + (da ? da[j] : 0.0);
+        dl[j] = w[j] * (t - mean);
       }
 }
 
@@ -140,7 +143,7 @@ void fwd_impl(const Geo& g, const T* Q, const T* K, const double* bias, double s
 // literal, serial: every (query, neighbour) pair adds into dQ[query] and dK[neighbour].
 template <class T>
 void bwd_scatter_impl(const Geo& g, const T* Q, const T* K, const double* bias, double scale,
-                      const double* dphi, double* dQ, double* dK, double* dbias) {
+                      const double* dphi, const double* dattn, double* dQ, double* dK, double* dbias) {
   int64_t n = (int64_t)g.B * g.D * g.H * g.W * g.C;
   for (int64_t i = 0; i < n; ++i) dQ[i] = dK[i] = 0.0;
   if (dbias) for (int i = 0; i < g.heads * g.k3; ++i) dbias[i] = 0.0;
@@ -155,7 +158,8 @@ void bwd_scatter_impl(const Geo& g, const T* Q, const T* K, const double* bias, 
             logits(g, Q, K, bias, scale, b, z, y, x, s, l.data());
             softmax(l.data(), g.k3, w.data());
             weighted_offsets(g, w.data(), phi);
-            dlogits(g, w.data(), phi, dphi + (p * g.heads + s) * 3, dl.data());
+            dlogits(g, w.data(), phi, dphi + (p * g.heads + s) * 3,
+                    dattn ? dattn + (p * g.heads + s) * g.k3 : nullptr, dl.data());
             int j = 0;
             for (int a = -g.r; a <= g.r; ++a)
               for (int bb = -g.r; bb <= g.r; ++bb)
@@ -175,7 +179,7 @@ void bwd_scatter_impl(const Geo& g, const T* Q, const T* K, const double* bias, 
 // second derivation: first dl for every window, then each output element collects its terms.
 template <class T>
 void bwd_gather_impl(const Geo& g, const T* Q, const T* K, const double* bias, double scale,
-                     const double* dphi, double* dQ, double* dK) {
+                     const double* dphi, const double* dattn, double* dQ, double* dK) {
   int64_t nvn = (int64_t)g.B * g.D * g.H * g.W * g.heads;
   std::vector<double> DL((size_t)nvn * g.k3);
 #pragma omp parallel
@@ -192,7 +196,7 @@ void bwd_gather_impl(const Geo& g, const T* Q, const T* K, const double* bias, d
               logits(g, Q, K, bias, scale, b, z, y, x, s, l.data());
               softmax(l.data(), g.k3, w.data());
               weighted_offsets(g, w.data(), phi);
-              dlogits(g, w.data(), phi, dphi + vn * 3, DL.data() + vn * g.k3);
+              dlogits(g, w.data(), phi, dphi + vn * 3, dattn ? dattn + vn * g.k3 : nullptr, DL.data() + vn * g.k3);
             }
 #pragma omp for collapse(2) schedule(static)
     for (int b = 0; b < g.B; ++b)
@@ -266,7 +270,7 @@ void bwd_at_impl(const Geo& g, const T* Q, const T* K, const double* bias, doubl
       logits(g, Q, K, bias, scale, b, z, y, x, s, l.data());
       softmax(l.data(), g.k3, w.data());
       weighted_offsets(g, w.data(), phi);
-      dlogits(g, w.data(), phi, dphi + idx[i] * 3, dl.data());
+      dlogits(g, w.data(), phi, dphi + idx[i] * 3, nullptr, dl.data());
       for (int ch = 0; ch < g.d; ++ch) dQ[i * g.d + ch] = dK[i * g.d + ch] = 0.0;
       int j = 0;
       for (int a = -g.r; a <= g.r; ++a)
@@ -286,7 +290,7 @@ void bwd_at_impl(const Geo& g, const T* Q, const T* K, const double* bias, doubl
             logits(g, Q, K, bias, scale, b, pz, py, px, s, l.data());
             softmax(l.data(), g.k3, w.data());
             weighted_offsets(g, w.data(), phi);
-            dlogits(g, w.data(), phi, dphi + (pv * g.heads + s) * 3, dl.data());
+            dlogits(g, w.data(), phi, dphi + (pv * g.heads + s) * 3, nullptr, dl.data());
             for (int ch = 0; ch < g.d; ++ch)
               dK[i * g.d + ch] += scale * dl[j] * widen(Q[pv * g.C + s * g.d + ch]);
           }
@@ -429,18 +433,19 @@ int oracle_modet_fwd(const void* Q, const void* K, const double* bias, int B, in
   DISPATCH(dtype, fwd_impl<T>(g, (const T*)Q, (const T*)K, bias, scale, phi, attn, lse));
 }
 
-int oracle_modet_bwd_scatter(const void* Q, const void* K, const double* bias, const double* dphi, int B, int D,
-                             int H, int W, int C, int heads, int k, double scale, int dtype, double* dQ,
-                             double* dK, double* dbias) {
+// dattn (nullable): upstream gradient of the attention weights [B, D, H, W, heads, k^3]
+int oracle_modet_bwd_scatter(const void* Q, const void* K, const double* bias, const double* dphi,
+                             const double* dattn, int B, int D, int H, int W, int C, int heads, int k, double scale,
+                             int dtype, double* dQ, double* dK, double* dbias) {
   Geo g = make_geo(B, D, H, W, C, heads, k);
-  DISPATCH(dtype, bwd_scatter_impl<T>(g, (const T*)Q, (const T*)K, bias, scale, dphi, dQ, dK, dbias));
+  DISPATCH(dtype, bwd_scatter_impl<T>(g, (const T*)Q, (const T*)K, bias, scale, dphi, dattn, dQ, dK, dbias));
 }
 
-int oracle_modet_bwd_gather(const void* Q, const void* K, const double* bias, const double* dphi, int B, int D,
-                            int H, int W, int C, int heads, int k, double scale, int dtype, double* dQ,
-                            double* dK) {
+int oracle_modet_bwd_gather(const void* Q, const void* K, const double* bias, const double* dphi,
+                            const double* dattn, int B, int D, int H, int W, int C, int heads, int k, double scale,
+                            int dtype, double* dQ, double* dK) {
   Geo g = make_geo(B, D, H, W, C, heads, k);
-  DISPATCH(dtype, bwd_gather_impl<T>(g, (const T*)Q, (const T*)K, bias, scale, dphi, dQ, dK));
+  DISPATCH(dtype, bwd_gather_impl<T>(g, (const T*)Q, (const T*)K, bias, scale, dphi, dattn, dQ, dK));
 }
 
 int oracle_modet_fwd_at(const void* Q, const void* K, const double* bias, int B, int D, int H, int W, int C,

@@ -93,10 +93,11 @@ size_t modet_bwd_workspace_bytes(int B, int D, int H, int W, int C, int heads, i
     n += round16(nvn * 3 * sizeof(float)) + round16(nvn * sizeof(float));   // phi, lse
   }
   if (flags & MODET_WS_WANT_DBIAS) n += round16((size_t)heads * k * k * k * sizeof(double));   // fp64 sums
+  if (flags & MODET_WS_HAVE_DATTN) n += round16((size_t)B * D * H * W * heads * sizeof(float));  // sum_o w_o dattn_o
   return n;
 }
 
-int modet_bwd(const void* Q, const void* K, const float* bias, const float* dphi,
+int modet_bwd(const void* Q, const void* K, const float* bias, const float* dphi, const float* dattn,
               const float* phi, const float* lse, float* dQ, float* dK, float* dbias,
               int B, int D, int H, int W, int C, int heads, int k, float scale,
               int in_dtype, void* workspace, size_t workspace_bytes, void* stream) {
@@ -104,16 +105,18 @@ int modet_bwd(const void* Q, const void* K, const float* bias, const float* dphi
   if ((phi == nullptr) != (lse == nullptr)) return MODET_ERR_NULL;
   int rc = check_op_shape(B, D, H, W, C, heads, k, (int)in_dtype);
   if (rc != MODET_OK) return rc;
-  if (misaligned(Q) || misaligned(K) || misaligned(bias) || misaligned(dphi) || misaligned(phi) ||
+  if (misaligned(Q) || misaligned(K) || misaligned(bias) || misaligned(dphi) || misaligned(dattn) || misaligned(phi) ||
       misaligned(lse) || misaligned(dQ) || misaligned(dK) || misaligned(dbias) || misaligned(workspace))
     return MODET_ERR_ALIGN;
-  const int flags = (phi ? MODET_WS_HAVE_STATS : 0) | (dbias ? MODET_WS_WANT_DBIAS : 0);
+  const int flags = (phi ? MODET_WS_HAVE_STATS : 0) | (dbias ? MODET_WS_WANT_DBIAS : 0) |
+                    (dattn ? MODET_WS_HAVE_DATTN : 0);
   const size_t need = modet_bwd_workspace_bytes(B, D, H, W, C, heads, k, in_dtype, flags);
   if (need > 0 && (!workspace || workspace_bytes < need)) return MODET_ERR_WORKSPACE;
   const Geo g = make_geo(B, D, H, W, C, heads, k, scale);
   hipStream_t st = (hipStream_t)stream;
   const bool tiled_f = g_kernel_path == 0 && tiled_fwd_supported(g.d, heads, k, (int)in_dtype);
-  const bool tiled_b = g_kernel_path == 0 && tiled_bwd_supported(g.d, heads, k, (int)in_dtype);
+  // (the gradient that arrives through the attention weights is handled by the generic kernels only)
+  const bool tiled_b = g_kernel_path == 0 && !dattn && tiled_bwd_supported(g.d, heads, k, (int)in_dtype);
   hipError_t e = hipSuccess;
   char* ws = (char*)workspace;
   if (!phi) {   // statistics pass: the forward kernel writes phi and lse into the workspace
@@ -127,24 +130,26 @@ int modet_bwd(const void* Q, const void* K, const float* bias, const float* dphi
     lse = wlse;
   }
   double* acc = dbias ? (double*)ws : nullptr;     // fp64 sums of the bias gradient
+  if (dbias) ws += round16((size_t)g.heads * g.k3 * sizeof(double));
+  float* adot = dattn ? (float*)ws : nullptr;      // sum_o w_o dattn_o per window
   if (acc && launch_dbias_begin(g, acc, st) != hipSuccess) return MODET_ERR_LAUNCH;
   bool dbias_done = false;
   if (tiled_b) {
     const BwdTensors io = {Q, K, bias, dphi, phi, lse, dQ, dK, acc};
     e = launch_bwd_tiled(g, (int)in_dtype, g_math_mode == 1, io, st, &dbias_done);
   } else {
-    e = launch_bwd_generic(g, (int)in_dtype, Q, K, bias, dphi, phi, lse, dQ, dK, st);
+    e = launch_bwd_generic(g, (int)in_dtype, Q, K, bias, dphi, phi, lse, dattn, adot, dQ, dK, st);
   }
   if (e != hipSuccess) return MODET_ERR_LAUNCH;
   if (acc) {
-    if (!dbias_done) e = launch_dbias_generic(g, (int)in_dtype, Q, K, bias, dphi, phi, lse, acc, st);
+    if (!dbias_done) e = launch_dbias_generic(g, (int)in_dtype, Q, K, bias, dphi, phi, lse, dattn, adot, acc, st);
     if (e == hipSuccess) e = launch_dbias_end(g, acc, dbias, st);
     if (e != hipSuccess) return MODET_ERR_LAUNCH;
   }
   return MODET_OK;
 }
 
-int modet_bwd_static(const void* Q, const void* K, const float* bias, const float* dphi,
+int modet_bwd_static(const void* Q, const void* K, const float* bias, const float* dphi, const float* dattn,
                      const float* phi, const float* lse, float* dQ, float* dK, float* dbias,
                      int B, int D, int H, int W, int C, int heads, int k, float scale,
                      int in_dtype, void* stream) {
@@ -153,10 +158,11 @@ int modet_bwd_static(const void* Q, const void* K, const float* bias, const floa
   if ((phi == nullptr) != (lse == nullptr)) return MODET_ERR_NULL;
   int rc = check_op_shape(B, D, H, W, C, heads, k, (int)in_dtype);
   if (rc != MODET_OK) return rc;
-  if (misaligned(Q) || misaligned(K) || misaligned(bias) || misaligned(dphi) || misaligned(phi) ||
+  if (misaligned(Q) || misaligned(K) || misaligned(bias) || misaligned(dphi) || misaligned(dattn) || misaligned(phi) ||
       misaligned(lse) || misaligned(dQ) || misaligned(dK) || misaligned(dbias))
     return MODET_ERR_ALIGN;
-  const int flags = (phi ? MODET_WS_HAVE_STATS : 0) | (dbias ? MODET_WS_WANT_DBIAS : 0);
+  const int flags = (phi ? MODET_WS_HAVE_STATS : 0) | (dbias ? MODET_WS_WANT_DBIAS : 0) |
+                    (dattn ? MODET_WS_HAVE_DATTN : 0);
   const size_t need = modet_bwd_workspace_bytes(B, D, H, W, C, heads, k, in_dtype, flags);
   if (need > (size_t)MODET_STATIC_SCRATCH_BYTES) return MODET_ERR_WORKSPACE;      // beyond the built-in scratch
   void* ws = nullptr;
@@ -166,7 +172,7 @@ int modet_bwd_static(const void* Q, const void* K, const float* bias, const floa
   }
   // everything modet_bwd keeps in its workspace is written before it is read (the statistics by the forward
   // kernel, the bias gradient's sums by a fill kernel), so the last call's contents do not matter
-  return modet_bwd(Q, K, bias, dphi, phi, lse, dQ, dK, dbias, B, D, H, W, C, heads, k, scale, in_dtype, ws,
+  return modet_bwd(Q, K, bias, dphi, dattn, phi, lse, dQ, dK, dbias, B, D, H, W, C, heads, k, scale, in_dtype, ws,
                    need, stream);
 }
 

@@ -30,14 +30,16 @@ __device__ __forceinline__ bf16_t f2bf(float f) {
 // generic kernels: any head size, k in {1,3,5,7}, fp32 / bf16 inputs
 hipError_t launch_fwd_generic(const Geo& g, int dtype, const void* Q, const void* K, const float* bias,
                               float* phi, float* attn, float* lse, hipStream_t st);
+// dattn (nullable): upstream gradient of the attention weights; adot: one float per window of scratch for it
 hipError_t launch_bwd_generic(const Geo& g, int dtype, const void* Q, const void* K, const float* bias,
-                              const float* dphi, const float* phi, const float* lse, float* dQ, float* dK,
-                              hipStream_t st);
+                              const float* dphi, const float* phi, const float* lse, const float* dattn,
+                              float* adot, float* dQ, float* dK, hipStream_t st);
 // Gradient of the bias.  The sums over all voxels are accumulated in fp64 in `acc` ([heads, k^3] doubles of the
 // caller's workspace): _begin zeroes it, any number of kernels add to it, _end rounds it into dbias.
 hipError_t launch_dbias_begin(const Geo& g, double* acc, hipStream_t st);
 hipError_t launch_dbias_generic(const Geo& g, int dtype, const void* Q, const void* K, const float* bias,
-                                const float* dphi, const float* phi, const float* lse, double* acc, hipStream_t st);
+                                const float* dphi, const float* phi, const float* lse, const float* dattn,
+                                const float* adot, double* acc, hipStream_t st);
 hipError_t launch_dbias_end(const Geo& g, const double* acc, float* dbias, hipStream_t st);
 hipError_t launch_warp(const void* src, const float* field, void* out, int B, int D, int H, int W, int C,
                        int half, int dtype, hipStream_t st);

@@ -30,9 +30,9 @@ _lib = ctypes.CDLL(LIB_PATH)
 _vp, _ci, _cf, _sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_size_t
 _lib.modet_fwd.argtypes = [_vp] * 6 + [_ci] * 7 + [_cf, _ci, _vp]
 _lib.modet_fwd.restype = _ci
-_lib.modet_bwd.argtypes = [_vp] * 9 + [_ci] * 7 + [_cf, _ci, _vp, _sz, _vp]
+_lib.modet_bwd.argtypes = [_vp] * 10 + [_ci] * 7 + [_cf, _ci, _vp, _sz, _vp]
 _lib.modet_bwd.restype = _ci
-_lib.modet_bwd_static.argtypes = [_vp] * 9 + [_ci] * 7 + [_cf, _ci, _vp]
+_lib.modet_bwd_static.argtypes = [_vp] * 10 + [_ci] * 7 + [_cf, _ci, _vp]
 _lib.modet_bwd_static.restype = _ci
 _lib.modet_bwd_workspace_bytes.argtypes = [_ci] * 7 + [_ci, _ci]
 _lib.modet_bwd_workspace_bytes.restype = _sz
@@ -135,28 +135,32 @@ def modet_fwd(Q, K, heads: int, k: int, scale: float = 0.0, bias=None, want_attn
     return out if len(out) > 1 else phi
 
 
-MODET_WS_HAVE_STATS, MODET_WS_WANT_DBIAS = 1, 2
+MODET_WS_HAVE_STATS, MODET_WS_WANT_DBIAS, MODET_WS_HAVE_DATTN = 1, 2, 4
 
 
-def modet_bwd_workspace_bytes(B, D, H, W, C, heads, k, dtype=MODET_F32, have_stats=False, want_dbias=False) -> int:
-    flags = (MODET_WS_HAVE_STATS if have_stats else 0) | (MODET_WS_WANT_DBIAS if want_dbias else 0)
+def modet_bwd_workspace_bytes(B, D, H, W, C, heads, k, dtype=MODET_F32, have_stats=False, want_dbias=False,
+                              have_dattn=False) -> int:
+    flags = ((MODET_WS_HAVE_STATS if have_stats else 0) | (MODET_WS_WANT_DBIAS if want_dbias else 0) |
+             (MODET_WS_HAVE_DATTN if have_dattn else 0))
     return int(_lib.modet_bwd_workspace_bytes(B, D, H, W, C, heads, k, dtype, flags))
 
 
 def modet_bwd(Q, K, dphi, heads: int, k: int, scale: float = 0.0, bias=None, phi=None, lse=None,
-              want_dbias=False, out=None, workspace=None):
-    """dQ, dK [B,D,H,W,C] fp32 (+ dbias [heads,k^3]).  `phi`, `lse` are modet_fwd's outputs (optional).
+              want_dbias=False, out=None, workspace=None, dattn=None):
+    """dQ, dK [B,D,H,W,C] fp32 (+ dbias [heads,k^3]).  `phi`, `lse` are modet_fwd's outputs (optional); `dattn`
+    [B,D,H,W,heads,k^3] is the upstream gradient of the attention weights when they were an output too.
     `out` = (dQ, dK) and `workspace` (uint8 tensor) may be preallocated for use in timed loops."""
-    _dev(Q, K, dphi, bias, phi, lse)
+    _dev(Q, K, dphi, bias, phi, lse, dattn)
     B, D, H, W, C = Q.shape
     f32 = dict(device=Q.device, dtype=torch.float32)
     dQ, dK = out if out is not None else (torch.empty(Q.shape, **f32), torch.empty(Q.shape, **f32))
     dbias = torch.empty((heads, k ** 3), **f32) if want_dbias else None
-    need = modet_bwd_workspace_bytes(B, D, H, W, C, heads, k, _in_dtype(Q), phi is not None, want_dbias)
+    need = modet_bwd_workspace_bytes(B, D, H, W, C, heads, k, _in_dtype(Q), phi is not None, want_dbias,
+                                     dattn is not None)
     if workspace is None and need:
         workspace = torch.empty(need, device=Q.device, dtype=torch.uint8)
     wbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
-    _check(_lib.modet_bwd(_ptr(Q), _ptr(K), _ptr(bias), _ptr(dphi), _ptr(phi), _ptr(lse), _ptr(dQ), _ptr(dK),
+    _check(_lib.modet_bwd(_ptr(Q), _ptr(K), _ptr(bias), _ptr(dphi), _ptr(dattn), _ptr(phi), _ptr(lse), _ptr(dQ), _ptr(dK),
                           _ptr(dbias), B, D, H, W, C, heads, k, float(scale), _in_dtype(Q), _ptr(workspace),
                           wbytes, _stream()))
     return (dQ, dK, dbias) if want_dbias else (dQ, dK)
@@ -166,13 +170,14 @@ MODET_STATIC_SCRATCH_BYTES = 8 << 20
 
 
 def modet_bwd_static(Q, K, dphi, heads: int, k: int, out, scale: float = 0.0, bias=None, phi=None, lse=None,
-                     dbias=None):
+                     dbias=None, dattn=None):
     """modet_bwd with the library's built-in scratch: nothing is allocated, here or in the library.  `out` =
     (dQ, dK) and, when the bias gradient is wanted, `dbias` [heads, k^3] are the caller's tensors."""
-    _dev(Q, K, dphi, bias, phi, lse, dbias, *out)
+    _dev(Q, K, dphi, bias, phi, lse, dbias, dattn, *out)
     B, D, H, W, C = Q.shape
     dQ, dK = out
-    _check(_lib.modet_bwd_static(_ptr(Q), _ptr(K), _ptr(bias), _ptr(dphi), _ptr(phi), _ptr(lse), _ptr(dQ), _ptr(dK),
+    _check(_lib.modet_bwd_static(_ptr(Q), _ptr(K), _ptr(bias), _ptr(dphi), _ptr(dattn), _ptr(phi), _ptr(lse), _ptr(dQ),
+                                 _ptr(dK),
                                  _ptr(dbias), B, D, H, W, C, heads, k, float(scale), _in_dtype(Q), _stream()))
     return (dQ, dK, dbias) if dbias is not None else (dQ, dK)
 

@@ -132,6 +132,38 @@ def test_bias_with_statistics_passed_in(modet, shape):
     run_case(modet, shape, 0, with_bias=True, stats="pass")
 
 
+@pytest.mark.parametrize("shape", [SMALL[1], SMALL[3], SMALL[6], SMALL[12], SMALL[8], SMALL[9], SMALL[32]],
+                         ids=lambda s: "x".join(map(str, s)))
+def test_gradient_through_the_attention_weights(modet, shape):
+    """the weights of Eq. 3 as a second output with an upstream gradient of their own: dQ, dK and the bias gradient
+    of sum(dphi * phi) + sum(dattn * attn), with the forward's statistics passed in and recomputed."""
+    B, D, H, W, C, heads, k, dtype = shape
+    keys = "displaced" if min(D, H, W) >= 4 else "iid"
+    c = synth.make_case(B, D, H, W, C, heads, k, dtype=dtype, keys=keys, m=(k - 1) // 2, seed=2000 + D * H + W)
+    bias = (0.5 * synth.normal(79, 0, (heads, k ** 3))).astype(np.float32)
+    da = synth.normal(80, 0, (B, D, H, W, heads, k ** 3))
+    ref_dQ, ref_dK, ref_db = oracle.modet_bwd(c["Q"], c["K"], c["dphi"], heads, k, bias=bias, dtype=dtype,
+                                              form="scatter", want_dbias=True, dattn=da)
+    Q, K, g = up(c["Q"], dtype), up(c["K"], dtype), up(c["dphi"])
+    phi, lse = modet.modet_fwd(Q, K, heads, k, bias=up(bias), want_lse=True)
+    gs = max(1.0, k ** 3 / 27.0)
+    for given in (dict(phi=phi, lse=lse), {}):
+        dQ, dK, db = modet.modet_bwd(Q, K, g, heads, k, bias=up(bias), want_dbias=True, dattn=up(da), **given)
+        tag = f"{shape} stats {'passed' if given else 'recomputed'}"
+        assert_close(dQ.cpu().numpy(), ref_dQ, dtype, "dQ " + tag, scale=gs)
+        assert_close(dK.cpu().numpy(), ref_dK, dtype, "dK " + tag, scale=gs)
+        if dtype == "bf16":
+            assert_close_bf16_tight(dQ.cpu().numpy(), ref_dQ, "dQ " + tag, scale=gs)
+            assert_close_bf16_tight(dK.cpu().numpy(), ref_dK, "dK " + tag, scale=gs)
+        assert_dbias_close(db.cpu().numpy(), ref_db, B * D * H * W, dtype, "dbias " + tag)
+    # a gradient that is constant over each window changes nothing (the weights of a window sum to one)
+    dQ0, dK0 = modet.modet_bwd(Q, K, g, heads, k, bias=up(bias), phi=phi, lse=lse)
+    dQ1, dK1 = modet.modet_bwd(Q, K, g, heads, k, bias=up(bias), phi=phi, lse=lse,
+                               dattn=torch.full(da.shape, 0.25, device="cuda"))
+    assert_close(dQ1.cpu().numpy(), dQ0.cpu().numpy().astype(np.float64), dtype, "constant dattn dQ", scale=gs)
+    assert_close(dK1.cpu().numpy(), dK0.cpu().numpy().astype(np.float64), dtype, "constant dattn dK", scale=gs)
+
+
 def test_explicit_scale_and_peaked_attention(modet):
     """large scale: attention is one-hot on the planted integer offset (sign / axis order on the GPU)."""
     B, D, H, W, heads, d, k = 1, 8, 9, 70, 1, 8, 3

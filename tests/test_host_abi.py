@@ -19,8 +19,8 @@ def lib():
     L = ctypes.CDLL(LIB)
     vp, ci, cf, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_size_t
     L.modet_fwd.argtypes = [vp] * 6 + [ci] * 7 + [cf, ci, vp]
-    L.modet_bwd.argtypes = [vp] * 9 + [ci] * 7 + [cf, ci, vp, sz, vp]
-    L.modet_bwd_static.argtypes = [vp] * 9 + [ci] * 7 + [cf, ci, vp]
+    L.modet_bwd.argtypes = [vp] * 10 + [ci] * 7 + [cf, ci, vp, sz, vp]
+    L.modet_bwd_static.argtypes = [vp] * 10 + [ci] * 7 + [cf, ci, vp]
     L.modet_warp.argtypes = [vp] * 3 + [ci] * 5 + [ci, ci, vp]
     L.modet_compose.argtypes = [vp] * 3 + [ci] * 5 + [vp]
     L.modet_warp_bwd.argtypes = [vp] * 5 + [ci] * 5 + [ci, ci, vp]
@@ -61,8 +61,8 @@ def fwd(lib, Q=P, K=P, bias=None, phi=P, attn=None, lse=None, B=1, D=4, H=4, W=4
 
 
 def bwd(lib, Q=P, K=P, bias=None, g=P, phi=None, lse=None, dQ=P, dK=P, db=None, B=1, D=4, H=4, W=4, C=8, heads=1,
-        k=3, dt=0, ws=None, wsb=0):
-    return lib.modet_bwd(Q, K, bias, g, phi, lse, dQ, dK, db, B, D, H, W, C, heads, k, 0.0, dt, ws, wsb, None)
+        k=3, dt=0, ws=None, wsb=0, da=None):
+    return lib.modet_bwd(Q, K, bias, g, da, phi, lse, dQ, dK, db, B, D, H, W, C, heads, k, 0.0, dt, ws, wsb, None)
 
 
 def test_fwd_rejects_bad_arguments(lib):
@@ -90,12 +90,16 @@ def test_bwd_rejects_bad_arguments(lib):
     assert lib.modet_bwd_workspace_bytes(1, 4, 4, 4, 8, 1, 3, 0, 2) == need + 224
     assert bwd(lib, phi=P, lse=P, db=P) == E_WS and bwd(lib, phi=P, lse=P, db=P, ws=P, wsb=223) == E_WS
     assert bwd(lib, db=P, ws=P, wsb=need + 223) == E_WS
+    # flag 4: an upstream gradient of the attention weights is passed in -- one float per window
+    assert lib.modet_bwd_workspace_bytes(1, 4, 4, 4, 8, 1, 3, 0, 5) == 256
+    assert bwd(lib, phi=P, lse=P, da=P) == E_WS and bwd(lib, phi=P, lse=P, da=P, ws=P, wsb=255) == E_WS
+    assert bwd(lib, phi=P, lse=P, da=ODD, ws=P, wsb=256) == E_ALIGN
 
 
 def test_bwd_static_rejects_bad_arguments(lib):
     def sb(Q=P, K=P, bias=None, g=P, phi=None, lse=None, dQ=P, dK=P, db=None, B=1, D=4, H=4, W=4, C=8, heads=1, k=3,
            dt=0):
-        return lib.modet_bwd_static(Q, K, bias, g, phi, lse, dQ, dK, db, B, D, H, W, C, heads, k, 0.0, dt, None)
+        return lib.modet_bwd_static(Q, K, bias, g, None, phi, lse, dQ, dK, db, B, D, H, W, C, heads, k, 0.0, dt, None)
     assert sb(g=None) == E_NULL and sb(dK=None) == E_NULL and sb(phi=P) == E_NULL
     assert sb(W=0) == E_SHAPE and sb(k=4) == E_SHAPE and sb(k=9) == E_UNSUP and sb(dQ=ODD) == E_ALIGN
     # the built-in scratch is 8 MiB: statistics of 524288 windows (16 bytes each) fit, one window more does not,

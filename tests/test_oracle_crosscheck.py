@@ -64,6 +64,18 @@ def test_p11_unfold_forward_backward(B, D, H, W, C, heads, k, dtype, with_bias):
     dQg, dKg = oracle.modet_bwd(Q, K, g, heads, k, bias=bias, dtype=dtype, form="gather")
     np.testing.assert_allclose(dQg, tq.grad.numpy(), atol=1e-12)
     np.testing.assert_allclose(dKg, tk.grad.numpy(), atol=1e-12)
+    # the attention weights as a second output with an upstream gradient of their own (autograd of the same graph)
+    ga = synth.normal(33, 0, (B, D, H, W, heads, k ** 3), dtype=np.float64)
+    for t in (tq, tk, tb):
+        if t is not None:
+            t.grad = None
+    tphi, tattn = unfold_modet(tq, tk, heads, k, scale, tb)
+    ((tphi * torch.tensor(g.astype(np.float64))).sum() + (tattn * torch.tensor(ga)).sum()).backward()
+    dQ, dK, db = oracle.modet_bwd(Q, K, g, heads, k, bias=bias, dtype=dtype, form="scatter", want_dbias=True, dattn=ga)
+    np.testing.assert_allclose(dQ, tq.grad.numpy(), atol=1e-12)
+    np.testing.assert_allclose(dK, tk.grad.numpy(), atol=1e-12)
+    if with_bias:
+        np.testing.assert_allclose(db, tb.grad.numpy(), atol=1e-11)
 
 
 def test_explicit_scale_is_eq3_as_printed():

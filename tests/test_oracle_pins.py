@@ -210,6 +210,48 @@ def test_p9_finite_differences(k, with_bias):
     assert abs(lhs - rhs) <= 1e-7 * max(1.0, abs(rhs))
 
 
+def test_p9_finite_differences_with_attention_as_an_output():
+    """L = sum(g * phi) + sum(ga * attn): the weights of Eq. 3 as a second output with their own upstream
+    gradient.  Central differences in fp64 on Q, K and the bias, and the adjoint identity."""
+    B, D, H, W, C, heads, k = 1, 3, 4, 5, 4, 2, 3
+    Q, K = rnd(40, (B, D, H, W, C)), rnd(41, (B, D, H, W, C))
+    g, ga = rnd(42, (B, D, H, W, heads, 3)), rnd(43, (B, D, H, W, heads, k ** 3))
+    bias = 0.4 * rnd(44, (heads, k ** 3))
+
+    def loss(q, kk, bb=bias):
+        phi, attn = oracle.modet_fwd(q, kk, heads, k, bias=bb, dtype="f64", want_attn=True)
+        return float((phi * g).sum() + (attn * ga).sum())
+
+    for form in ("scatter", "gather"):
+        out = oracle.modet_bwd(Q, K, g, heads, k, bias=bias, dtype="f64", form=form, dattn=ga,
+                               want_dbias=form == "scatter")
+        if form == "scatter":
+            dQ, dK, db = out
+        else:
+            np.testing.assert_allclose(out[0], dQ, atol=1e-12)
+            np.testing.assert_allclose(out[1], dK, atol=1e-12)
+    h = 1e-6
+    rs = np.random.RandomState(1)
+    for _ in range(30):
+        i = tuple(rs.randint(0, s) for s in Q.shape)
+        for arr, grad, which in ((Q, dQ, 0), (K, dK, 1)):
+            ap, am = arr.copy(), arr.copy()
+            ap[i] += h
+            am[i] -= h
+            fd = (loss(ap, K) - loss(am, K)) / (2 * h) if which == 0 else (loss(Q, ap) - loss(Q, am)) / (2 * h)
+            assert abs(fd - grad[i]) <= 1e-7 * max(1.0, abs(grad[i])), (i, which, fd, grad[i])
+    for _ in range(15):
+        i = (rs.randint(heads), rs.randint(k ** 3))
+        bp, bm = bias.copy(), bias.copy()
+        bp[i] += h
+        bm[i] -= h
+        fd = (loss(Q, K, bp) - loss(Q, K, bm)) / (2 * h)
+        assert abs(fd - db[i]) <= 1e-7 * max(1.0, abs(db[i]))
+    # with g = 0 and ga constant over a window the loss is constant (the weights sum to one): zero gradients
+    z = oracle.modet_bwd(Q, K, np.zeros_like(g), heads, k, bias=bias, dtype="f64", dattn=np.full_like(ga, 0.7))
+    assert np.abs(z[0]).max() < 1e-14 and np.abs(z[1]).max() < 1e-14
+
+
 # ---- P10: the two derivations of the backward agree -----------------------------------------
 @pytest.mark.parametrize("k,dtype", [(3, "f64"), (5, "f32"), (3, "bf16")])
 def test_p10_scatter_equals_gather(k, dtype):
