@@ -45,7 +45,13 @@ struct TiledParams {
   double* dbias_acc;                                              // backward, optional: [heads, k^3] sums of dl
   float* phi; float* lse;                                         // forward outputs
   float* out;                                                     // dQ or dK
-  int B, D, H, Wh;          // Wh = W * heads fused columns
+  int B, D, H, Wh;          // Wh = W * HS fused columns of one head group (what a launch's tiles cover)
+  // Head groups: a kernel handles at most 8 fused columns per voxel (its HS).  With more (16 or 32 heads, or more
+  // than 4 heads of twelve channels) the columns of a voxel are split into ngrp groups of HS = 1 << hs_shift, a
+  // group is one more grid axis, and only the addresses know: local column xl of group g is global column
+  // (xl >> hs_shift) * HSg + g * HS + (xl & (HS - 1)) of a row of Whg = W * HSg columns.  Heads never interact,
+  // so nothing else changes.  One group: HSg = HS, Whg = Wh, the mapping is the identity.
+  int Whg, HSg, hs_shift, ngrp;
   int ch;                   // channels per fused column in memory (8, or 6: see Mem)
   int ZC, ntx, nty, nzc;    // planes per chunk; tiles along Wh, H; chunks along D
   float qscale;             // scale * log2(e)
@@ -61,25 +67,32 @@ __device__ __forceinline__ unsigned xcd_remap(unsigned id, unsigned n) {
 
 struct Tile {
   int b, z0, z1, y0, xs0, tx, ty, xs, y;
+  int gofs;                // first global column (inside a voxel) of this workgroup's head group
   bool lane_ok;
-  long long plane_elems;   // H * Wh * channels per column
-  long long col;           // window index of (b, z=0, y, xs): + z*H*Wh
+  long long plane_elems;   // H * Whg * channels per column
+  long long col;           // global column index of (b, z=0, y, xs): + z*H*Whg
 };
+
+// local fused column of a head group -> global fused column of the row
+__device__ __forceinline__ int gcol(const TiledParams& p, int gofs, int xl) {
+  return (xl >> p.hs_shift) * p.HSg + gofs + (xl & ((1 << p.hs_shift) - 1));
+}
 
 __device__ __forceinline__ Tile make_tile(const TiledParams& p, unsigned id, int lane = -1) {
   Tile t;
   if (lane < 0) lane = threadIdx.x;
   const int txi = id % p.ntx; id /= p.ntx;
   const int tyi = id % p.nty; id /= p.nty;
-  const int zc = id % p.nzc;
-  t.b = id / p.nzc;
+  const int zc = id % p.nzc; id /= p.nzc;
+  t.b = id % p.B;
+  t.gofs = (id / p.B) << p.hs_shift;
   t.tx = lane % TX; t.ty = lane / TX;
   t.xs0 = txi * TX; t.y0 = tyi * TY;
   t.z0 = zc * p.ZC; t.z1 = min(p.D, t.z0 + p.ZC);
   t.xs = t.xs0 + t.tx; t.y = t.y0 + t.ty;
   t.lane_ok = t.xs < p.Wh && t.y < p.H;
-  t.plane_elems = (long long)p.H * p.Wh * p.ch;
-  t.col = (long long)t.b * p.D * p.H * p.Wh + (long long)t.y * p.Wh + t.xs;
+  t.plane_elems = (long long)p.H * p.Whg * p.ch;
+  t.col = (long long)t.b * p.D * p.H * p.Whg + (long long)t.y * p.Whg + gcol(p, t.gofs, min(t.xs, p.Wh - 1));
   return t;
 }
 
@@ -195,7 +208,7 @@ struct Stager {
   float4 v[P::NL];
   bool plane_ok;
 
-  __device__ __forceinline__ void init(int tid, int y0, int xs0, int H, int Wh) {
+  __device__ __forceinline__ void init(int tid, int y0, int xs0, int H, int Wh, const TiledParams& p, int gofs) {
 #pragma unroll
     for (int i = 0; i < P::NL; ++i) {
       const int e = tid + i * NT;
@@ -205,7 +218,7 @@ struct Stager {
       const bool used = e < P::NV;
       const bool in = used && gy >= 0 && gy < H && gx >= 0 && gx < Wh;
       const int cy = min(max(gy, 0), H - 1), cx = min(max(gx, 0), Wh - 1);
-      goff[i] = (cy * Wh + cx) * CH + hv * 4;
+      goff[i] = (cy * p.Whg + gcol(p, gofs, cx)) * CH + hv * 4;
       loff[i] = used ? (pos << 2 | hv << 1 | (in ? 1 : 0)) : -1;
     }
     plane_ok = false;
@@ -281,7 +294,8 @@ struct StatStager {
   int sh;            // column index -> window index (1 for half-head columns)
   float nshare;      // -log2(e) * the share of lse a lane's partial logit starts from
 
-  __device__ __forceinline__ void init(int tid, int y0, int xs0, int H, int Wh, int sh_ = 0) {
+  __device__ __forceinline__ void init(int tid, int y0, int xs0, int H, int Wh, const TiledParams& p, int gofs,
+                                       int sh_ = 0) {
     sh = sh_;
     nshare = sh_ ? -0.5f * kLog2e : -kLog2e;
 #pragma unroll
@@ -292,7 +306,7 @@ struct StatStager {
       const bool used = pos < P::NPOS;
       const bool in = used && gy >= 0 && gy < H && gx >= 0 && gx < Wh;
       const int cy = min(max(gy, 0), H - 1), cx = min(max(gx, 0), Wh - 1);
-      goff[i] = cy * Wh + cx;
+      goff[i] = cy * p.Whg + gcol(p, gofs, cx);
       loff[i] = used ? (pos << 1 | (in ? 1 : 0)) : -1;
     }
     plane_ok = false;
@@ -402,10 +416,10 @@ __device__ __forceinline__ void store_col_scaled(float* out, long long w, const 
 // A lane's head is its fused column modulo HS, so it reads through bt + head at the compile-time offset o * HS,
 // o = ((a+R)*KW + b+R)*KW + c+R.  A NULL bias is all zeros (its gradient may still be wanted).
 template <class T, class LT, int KW, int HS>
-__device__ __forceinline__ void fill_bias_table(LT* bt, const float* bias, int tid, int nthreads) {
+__device__ __forceinline__ void fill_bias_table(LT* bt, const float* bias, int tid, int nthreads, int gofs = 0) {
   constexpr int K3 = KW * KW * KW;
   for (int i = tid; i < K3 * HS; i += nthreads) {
-    const int j = i / HS, h = (i - j * HS) >> Win<T>::SH;
+    const int j = i / HS, h = (gofs + i - j * HS) >> Win<T>::SH;      // (gofs: first column of the head group)
     bt[i] = bias ? (LT)bias[h * K3 + j] * (LT)kLog2e * (LT)Win<T>::kShare : (LT)0;
   }
 }
@@ -442,7 +456,7 @@ template <int KW, int HS, class T>
 __device__ void fwd_query_two_pass(const TiledParams& p, long long w) {
   constexpr int R = KW / 2;
   long long r = w;
-  const int xs = (int)(r % p.Wh); r /= p.Wh;
+  const int xs = (int)(r % p.Whg); r /= p.Whg;      // (global columns: w is a global column index)
   const int y = (int)(r % p.H); r /= p.H;
   const int z = (int)(r % p.D);
   typedef typename Mem<T>::E E;
@@ -455,15 +469,15 @@ __device__ void fwd_query_two_pass(const TiledParams& p, long long w) {
 #pragma unroll 1
     for (int j = 0; j < KW * KW * KW; ++j) {
       const int a = j / (KW * KW) - R, bb = (j / KW) % KW - R, cc = j % KW - R;
-      const int zz = z + a, yy = y + bb, xx = xs + cc * HS;
+      const int zz = z + a, yy = y + bb, xx = xs + cc * p.HSg;
       double l = 0.0;      // a neighbour outside the volume is a zero key
-      if (zz >= 0 && zz < p.D && yy >= 0 && yy < p.H && xx >= 0 && xx < p.Wh) {
-        const E* Kp = (const E*)p.K + (w + ((long long)a * p.H + bb) * p.Wh + cc * HS) * CH;
+      if (zz >= 0 && zz < p.D && yy >= 0 && yy < p.H && xx >= 0 && xx < p.Whg) {
+        const E* Kp = (const E*)p.K + (w + ((long long)a * p.H + bb) * p.Whg + cc * p.HSg) * CH;
 #pragma unroll 1
         for (int c = 0; c < CHW; ++c) l = fma((double)Ld<E>::one(Qp + c), (double)Ld<E>::one(Kp + c), l);
         l *= (double)p.qscale;
       }
-      if (p.bias) l += (double)p.bias[((xs % HS) >> SH) * (KW * KW * KW) + j] * (double)kLog2e;
+      if (p.bias) l += (double)p.bias[((xs % p.HSg) >> SH) * (KW * KW * KW) + j] * (double)kLog2e;
       if (pass == 0) {
         mx = fmax(mx, l);
       } else {
@@ -942,12 +956,12 @@ __device__ __forceinline__ void march_body(typename Pol::State (&st)[Pol::KW], c
   // top of the next step, when the refill below is skipped) would wait for the stores as well.
   Pol::arrived(pre);
   typename Pol::State& done = st[PH % KW];     // role 0 is complete: it has seen planes z-R .. z+R
-  if ((active & 1u) && t.lane_ok) Pol::store(done, p, t.col + (long long)(s - R) * p.H * p.Wh);
+  if ((active & 1u) && t.lane_ok) Pol::store(done, p, t.col + (long long)(s - R) * p.H * p.Whg);
   if (have_next) Pol::refill(done, pre, p);     // the freed slot takes the plane s + R + 1
 }
 
 struct NoStats {
-  __device__ __forceinline__ void init(int, int, int, int, int, int = 0) {}
+  __device__ __forceinline__ void init(int, int, int, int, int, const TiledParams&, int, int = 0) {}
   __device__ __forceinline__ void fetch(const TiledParams&, long long, bool) {}
   __device__ __forceinline__ void zero_outside(float4*, float*) const {}
 };
@@ -988,24 +1002,24 @@ __device__ __forceinline__ void march(const TiledParams& p, unsigned id, void* s
   const Tile t = make_tile(p, id);
   const E* Lb = Pol::lds_operand(p) + (long long)t.b * p.D * t.plane_elems;
   // lanes outside the volume compute on a clamped (valid) column and never store
-  const int cy = min(t.y, p.H - 1), cxs = clamp_column<T>(t.xs, p.Wh);
+  const int cy = min(t.y, p.H - 1), cxs = gcol(p, t.gofs, clamp_column<T>(t.xs, p.Wh));
   const E* Ob = Pol::own_operand(p) + (long long)t.b * p.D * t.plane_elems +
-                ((long long)cy * p.Wh + cxs) * Mem<T>::CH;
-  const long long ccol = (long long)t.b * p.D * p.H * p.Wh + (long long)cy * p.Wh + cxs;
-  const long long pw = (long long)p.H * p.Wh;
+                ((long long)cy * p.Whg + cxs) * Mem<T>::CH;
+  const long long ccol = (long long)t.b * p.D * p.H * p.Whg + (long long)cy * p.Whg + cxs;
+  const long long pw = (long long)p.H * p.Whg;
   const long long wb = (long long)t.b * p.D * pw;    // window index of (b, 0, 0, 0)
   const int lbase = t.ty * P::PC + t.tx;             // patch position of the window corner of this lane
 
   Stager<KW, HS, T, typename Pol::ET> stg;
-  stg.init(threadIdx.x, t.y0, t.xs0, p.H, p.Wh);
+  stg.init(threadIdx.x, t.y0, t.xs0, p.H, p.Wh, p, t.gofs);
   typename std::conditional<Pol::kStats, StatStager<KW, HS>, NoStats>::type sst;
-  sst.init(threadIdx.x, t.y0, t.xs0, p.H, p.Wh, Win<T>::SH);
+  sst.init(threadIdx.x, t.y0, t.xs0, p.H, p.Wh, p, t.gofs, Win<T>::SH);
 #pragma unroll
   for (int j = 0; j < 2; ++j) {
     stg.zero_outside(sh.main[j]);
     if constexpr (Pol::kStats) sst.zero_outside(sh.sa[j], sh.sc[j]);
   }
-  if constexpr (Pol::kBias) fill_bias_table<T, typename Pol::Logit, KW, HS>(sh.bias.v, p.bias, threadIdx.x, NT);
+  if constexpr (Pol::kBias) fill_bias_table<T, typename Pol::Logit, KW, HS>(sh.bias.v, p.bias, threadIdx.x, NT, t.gofs);
   if constexpr (Pol::kWaveSums) {      // every lane's running sums start at zero (its own slots: no barrier needed)
 #pragma unroll
     for (int b = 0; b < KW; ++b)
@@ -1126,7 +1140,7 @@ march_pair_kernel(TiledParams p, float* outA, float* outB) {
 // only the even one counts), the 8 segments are folded across lanes, and one lane per offset issues the atomics.
 // Called by NT lanes, tid = 0..NT-1, all of them.
 template <class T, int KW, int HS>
-__device__ __forceinline__ void reduce_dl_sums(const float* dlsum, int tid, double* acc) {
+__device__ __forceinline__ void reduce_dl_sums(const float* dlsum, int tid, double* acc, int gofs = 0) {
   static_assert(KW == 3 && HS <= 8 && NT == 256, "27 offsets x 8 segments of 32 lanes");
   constexpr int SH = Win<T>::SH, NH = HS >> SH;
   const int row = tid >> 3, seg = tid & 7;
@@ -1150,7 +1164,7 @@ __device__ __forceinline__ void reduce_dl_sums(const float* dlsum, int tid, doub
     for (int c = h << SH; c < 8; c += HS) v += cls[c];
 #pragma unroll
     for (int m = 1; m < 8; m <<= 1) v += __shfl_xor(v, m);
-    if (on && seg == 0) atomicAdd(acc + h * 27 + row, v);
+    if (on && seg == 0) atomicAdd(acc + ((gofs >> SH) + h) * 27 + row, v);
   }
 }
 
@@ -1201,7 +1215,7 @@ __device__ __forceinline__ void shared_step(typename Pol::State (&st)[Pol::KW], 
   }
   commit_staged();       // before the stores: its wait for the loads must not cover them
   if ((active & 1u) && t.lane_ok)          // role 0 has seen its whole window
-    Pol::store(st[PH % KW], p, t.col + (long long)(s - R) * p.H * p.Wh);
+    Pol::store(st[PH % KW], p, t.col + (long long)(s - R) * p.H * p.Whg);
 }
 
 template <class Pol, bool IS_DK, class Rings>
@@ -1212,16 +1226,16 @@ __device__ __forceinline__ void shared_march(const TiledParams& p, const Tile& t
   constexpr int KW = Pol::KW, HS = Pol::HS, R = KW / 2, RING = Rings::RING;
   static_assert(KW == 3, "phase rotation below is written for k = 3");
   const E* Lb = Pol::lds_operand(p) + (long long)t.b * p.D * t.plane_elems;
-  const long long pw = (long long)p.H * p.Wh;
+  const long long pw = (long long)p.H * p.Whg;
   const long long wb = (long long)t.b * p.D * pw;
   const int lbase = t.ty * P::PC + t.tx;
   float4 (*mine)[2 * P::NPOS] = IS_DK ? sh.q : sh.k;        // the ring this half fills and marches over
   float4 (*other)[2 * P::NPOS] = IS_DK ? sh.k : sh.q;       // the ring it takes its own column from
 
   Stager<KW, HS, T, float> stg;
-  stg.init(tid, t.y0, t.xs0, p.H, p.Wh);
+  stg.init(tid, t.y0, t.xs0, p.H, p.Wh, p, t.gofs);
   typename std::conditional<IS_DK, StatStager<KW, HS>, NoStats>::type sst;
-  sst.init(tid, t.y0, t.xs0, p.H, p.Wh, Win<T>::SH);
+  sst.init(tid, t.y0, t.xs0, p.H, p.Wh, p, t.gofs, Win<T>::SH);
 #pragma unroll
   for (int j = 0; j < RING; ++j) {
     stg.zero_outside(mine[j]);
@@ -1245,7 +1259,7 @@ __device__ __forceinline__ void shared_march(const TiledParams& p, const Tile& t
 #pragma unroll
   for (int j = 0; j <= R; ++j) { fetch(s_first + j); commit(j); }
   fetch(s_first + R + 1);
-  if constexpr (Pol::kBias && !IS_DK) fill_bias_table<T, typename Pol::Logit, KW, HS>(sh.bias.v, p.bias, tid, NT);
+  if constexpr (Pol::kBias && !IS_DK) fill_bias_table<T, typename Pol::Logit, KW, HS>(sh.bias.v, p.bias, tid, NT, t.gofs);
   const typename Pol::Logit* bl = lane_bias<Pol>(sh, t.xs);
   float* sums = nullptr;      // the dQ half's sums of dl, when the bias gradient is wanted
   if constexpr (Pol::kBias && !IS_DK) {
@@ -1283,7 +1297,7 @@ __device__ __forceinline__ void shared_march(const TiledParams& p, const Tile& t
   }
   if constexpr (Pol::kBias && !IS_DK) {
     if (sums != nullptr)      // (uniform; the last step ended with a barrier, so every lane's sums are visible)
-      reduce_dl_sums<T, KW, HS>(sh.dlsum, tid, p.dbias_acc);
+      reduce_dl_sums<T, KW, HS>(sh.dlsum, tid, p.dbias_acc, t.gofs);
   }
 }
 
@@ -1470,8 +1484,8 @@ __device__ __forceinline__ void fused_key_half(TiledParams p, const Tile& t,
 
   // ---- staging: K and Q planes (whole haloed patch), statistics of the ring queries (lanes < NRP)
   Stager<KW, HS, T, float> stk, stq;
-  stk.init(tid, t.y0, t.xs0, p.H, p.Wh);
-  stq.init(tid, t.y0, t.xs0, p.H, p.Wh);
+  stk.init(tid, t.y0, t.xs0, p.H, p.Wh, p, t.gofs);
+  stq.init(tid, t.y0, t.xs0, p.H, p.Wh, p, t.gofs);
   stk.zero_outside(sh.k[0]);
   stk.zero_outside(sh.k[1]);
 #pragma unroll
@@ -1741,7 +1755,7 @@ bwd_sym_kernel(TiledParams p, float* dQ, float* dK) {
 
   // ---- staging: the K plane in the stager's own registers, the Q plane (same patch geometry) in qv
   Stager<KW, HS, T, float> stg;
-  stg.init(tid, t.y0, t.xs0, p.H, p.Wh);
+  stg.init(tid, t.y0, t.xs0, p.H, p.Wh, p, t.gofs);
   stg.zero_outside(sh.k);
 #pragma unroll
   for (int j = 0; j < S::QR; ++j) stg.zero_outside(sh.q[j]);
@@ -2032,13 +2046,20 @@ int chunk_length(long long tiles, int D, int k, int wgs_per_cu) {
   return best_zc;
 }
 
-TiledParams make_params(const Geo& g, int wgs_per_cu, int wgs_per_tile = 1) {
+// hs: fused columns per voxel the kernel handles (its HS); more columns than that are split into head groups
+TiledParams make_params(const Geo& g, int wgs_per_cu, int wgs_per_tile = 1, int hs = 0) {
   TiledParams p = {};
   p.B = g.B; p.D = g.D; p.H = g.H;
-  p.Wh = g.W * g.heads * (g.d == 12 ? 2 : 1);      // twelve channels: two half-head columns per head
+  p.HSg = g.heads * (g.d == 12 ? 2 : 1);           // twelve channels: two half-head columns per head
+  p.Whg = g.W * p.HSg;
+  if (hs <= 0 || hs > p.HSg) hs = p.HSg;
+  p.ngrp = p.HSg / hs;
+  p.hs_shift = 0;
+  while ((1 << p.hs_shift) < hs) ++p.hs_shift;
+  p.Wh = g.W * hs;
   p.ntx = (p.Wh + TX - 1) / TX;
   p.nty = (g.H + TY - 1) / TY;
-  int zc = chunk_length((long long)p.ntx * p.nty * g.B * wgs_per_tile, g.D, g.k, wgs_per_cu);
+  int zc = chunk_length((long long)p.ntx * p.nty * g.B * p.ngrp * wgs_per_tile, g.D, g.k, wgs_per_cu);
   if (zc > g.D) zc = g.D;
   if (zc < 1) zc = 1;
   p.ZC = zc;
@@ -2049,7 +2070,7 @@ TiledParams make_params(const Geo& g, int wgs_per_cu, int wgs_per_tile = 1) {
   return p;
 }
 
-inline unsigned nblocks(const TiledParams& p) { return (unsigned)((long long)p.ntx * p.nty * p.B * p.nzc); }
+inline unsigned nblocks(const TiledParams& p) { return (unsigned)((long long)p.ntx * p.nty * p.B * p.nzc * p.ngrp); }
 
 // waves per SIMD the register allocator is asked to make room for: the fp64 state of the fp32-input
 // kernels and the five in-flight planes of k = 5 fit two, the all-fp32 state of k = 3 fits three
@@ -2070,7 +2091,7 @@ int resident_workgroups() {
 
 template <class Pol, int WAVES>
 void launch_march(const Geo& g, TiledParams io, hipStream_t st) {
-  TiledParams p = make_params(g, resident_workgroups<Pol, WAVES>());
+  TiledParams p = make_params(g, resident_workgroups<Pol, WAVES>(), 1, Pol::HS);
   p.Q = io.Q; p.K = io.K; p.bias = io.bias; p.phi = io.phi; p.lse = io.lse;
   p.dphi = io.dphi; p.phi_in = io.phi_in; p.lse_in = io.lse_in; p.out = io.out;
   hipLaunchKernelGGL((march_kernel<Pol, WAVES>), dim3(nblocks(p)), dim3(NT), 0, st, p);
@@ -2107,17 +2128,17 @@ void launch_march(const Geo& g, TiledParams io, hipStream_t st) {
   if (g.k == 3 && dtype == 0 && fast_logits) {                                   \
     switch (g.heads) {                                                           \
       case 4: return CALL(3, 4, float, float);                                   \
-      case 8: return CALL(3, 8, float, float);                                   \
+      case 8: case 16: case 32: return CALL(3, 8, float, float);                 \
     }                                                                            \
   } else if (g.k == 3 && dtype == 0) {                                           \
     switch (g.heads) {                                                           \
       case 4: return CALL(3, 4, float, double);                                  \
-      case 8: return CALL(3, 8, float, double);                                  \
+      case 8: case 16: case 32: return CALL(3, 8, float, double);                \
     }                                                                            \
   } else if (g.k == 3) {                                                         \
     switch (g.heads) {                                                           \
       case 4: return CALL(3, 4, bf16_t, float);                                  \
-      case 8: return CALL(3, 8, bf16_t, float);                                  \
+      case 8: case 16: case 32: return CALL(3, 8, bf16_t, float);                \
     }                                                                            \
   }
 #define MODET_DISPATCH(CALL)                                                     \
@@ -2132,7 +2153,8 @@ void launch_march(const Geo& g, TiledParams io, hipStream_t st) {
       case 1: return dtype == 0 ? CALL(3, 1, f32x6_t, double) : CALL(3, 1, bf16x6_t, float);  \
       case 2: return dtype == 0 ? CALL(3, 2, f32x6_t, double) : CALL(3, 2, bf16x6_t, float);  \
       case 4: return dtype == 0 ? CALL(3, 4, f32x6_t, double) : CALL(3, 4, bf16x6_t, float);  \
-      case 8: return dtype == 0 ? CALL(3, 8, f32x6_t, double) : CALL(3, 8, bf16x6_t, float);  \
+      case 8: case 16: case 32:                                                               \
+        return dtype == 0 ? CALL(3, 8, f32x6_t, double) : CALL(3, 8, bf16x6_t, float);        \
     }                                                                                         \
   }                                                                                           \
   return hipErrorNotSupported;
@@ -2143,7 +2165,8 @@ void launch_march(const Geo& g, TiledParams io, hipStream_t st) {
     switch (g.heads) {                                                                          \
       case 1: return dtype == 0 ? CALL(3, 2, f32x12_t, double) : CALL(3, 2, bf16x12_t, float);  \
       case 2: return dtype == 0 ? CALL(3, 4, f32x12_t, double) : CALL(3, 4, bf16x12_t, float);  \
-      case 4: return dtype == 0 ? CALL(3, 8, f32x12_t, double) : CALL(3, 8, bf16x12_t, float);  \
+      case 4: case 8: case 16: case 32:                                                         \
+        return dtype == 0 ? CALL(3, 8, f32x12_t, double) : CALL(3, 8, bf16x12_t, float);        \
     }                                                                                           \
   }                                                                                             \
   return hipErrorNotSupported;

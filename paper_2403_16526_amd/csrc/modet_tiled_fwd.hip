@@ -29,14 +29,15 @@ hipError_t launch_fwd_biased(const Geo& g, int dtype, bool fast_logits, const vo
 
 }  // namespace
 
-// Covered, with or without bias.  Head size 8:  k = 3: 1/2/4/8 heads, fp32 inputs (fp64 logits) and bf16 inputs
-// (fp32 logits: the bf16 tolerance leaves room);  k = 5: 1/2 heads, bf16 inputs.  Head size 6: k = 3, 1/2/4/8
-// heads, both input types.  Head size 12: k = 3, 1/2/4 heads, both input types.
+// Covered, with or without bias.  Head size 8:  k = 3: 1/2/4/8/16/32 heads, fp32 inputs (fp64 logits) and bf16
+// inputs (fp32 logits: the bf16 tolerance leaves room);  k = 5: 1/2 heads, bf16 inputs.  Head sizes 6 and 12
+// (the paper's small and large model, Section 4.4): k = 3, 1/2/4/8/16/32 heads, both input types.
 bool tiled_fwd_supported(int d, int heads, int k, int dtype) {
-  if (d == 6) return k == 3 && (heads == 1 || heads == 2 || heads == 4 || heads == 8);
-  if (d == 12) return k == 3 && (heads == 1 || heads == 2 || heads == 4);
+  const bool pow2 = heads == 1 || heads == 2 || heads == 4 || heads == 8 || heads == 16 || heads == 32;
+  if (d == 6) return k == 3 && pow2;      // (more than 8 fused columns per voxel run as head groups of 8)
+  if (d == 12) return k == 3 && pow2;
   if (d != 8) return false;
-  if (k == 3) return heads == 1 || heads == 2 || heads == 4 || heads == 8;
+  if (k == 3) return pow2;
   if (k == 5) return dtype == 1 && (heads == 1 || heads == 2);
   return false;
 }

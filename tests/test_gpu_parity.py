@@ -117,7 +117,7 @@ def test_small_cases_match_oracle(modet, shape, path):
 # both dtypes
 BIASED = [SMALL[1], SMALL[3], SMALL[4], SMALL[6], SMALL[8], SMALL[12], SMALL[13], SMALL[16], SMALL[17], SMALL[18],
           SMALL[19], SMALL[20], SMALL[21], SMALL[22], SMALL[23], SMALL[24], SMALL[25], SMALL[26], SMALL[27],
-          SMALL[28], SMALL[29], SMALL[30], SMALL[31], SMALL[32]]
+          SMALL[28], SMALL[29], SMALL[30], SMALL[31], SMALL[32], SMALL[33], SMALL[34], SMALL[35], SMALL[36], SMALL[37]]
 
 
 @pytest.mark.parametrize("shape", BIASED, ids=lambda s: "x".join(map(str, s)))

@@ -149,3 +149,19 @@ def test_status_strings(lib):
         seen.add(t)
     assert lib.modet_status_string(-99) == b"unknown status"
     assert lib.modet_version() >= 100
+
+
+def test_tiled_kernel_coverage(lib):
+    """The head counts of the paper's three model sizes (Section 4.4: heads of 6, 8 and 12 channels, up to 32
+    heads at the coarsest level of the large model) all run on the LDS-tiled kernels; unusual head sizes and the
+    wide windows of fp32 inputs fall to the generic ones."""
+    lib.modet_has_tiled_kernels.restype = ctypes.c_int
+    lib.modet_has_tiled_kernels.argtypes = [ctypes.c_int] * 4
+    for d in (6, 8, 12):
+        for heads in (1, 2, 4, 8, 16, 32):
+            for dt in (0, 1):
+                assert lib.modet_has_tiled_kernels(d * heads, heads, 3, dt) == 3, (d, heads, dt)
+    assert lib.modet_has_tiled_kernels(384, 32, 3, 0) == 3
+    assert lib.modet_has_tiled_kernels(8, 1, 5, 1) == 3 and lib.modet_has_tiled_kernels(8, 1, 5, 0) == 0
+    assert lib.modet_has_tiled_kernels(10, 2, 3, 0) == 0 and lib.modet_has_tiled_kernels(24, 3, 3, 0) == 0
+    assert lib.modet_has_tiled_kernels(8, 1, 7, 0) == 0
