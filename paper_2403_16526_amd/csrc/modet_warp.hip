@@ -80,6 +80,12 @@ template <> struct Vec<bf16_t, 2> {
 // clamped to the grid, so its lower coarse neighbour is (i - 1) >> 1 (0 for i = 0) and the weight of the
 // upper one is 1/4 for odd i, 3/4 for even i >= 2 (0 at i = 0 and wherever the upper neighbour is clamped).
 __device__ __forceinline__ int coarse_lo(int i) { return i > 0 ? (i - 1) >> 1 : 0; }
+// weight of coarse voxel c (of n) in the upsampled value at fine voxel i
+__device__ __forceinline__ float up_weight(int i, int c, int n) {
+  const int lo = coarse_lo(i), hi = min(lo + 1, n - 1);
+  const float t = (i == 0 || hi == lo) ? 0.f : ((i & 1) ? 0.25f : 0.75f);
+  return (c == lo ? 1.f - t : 0.f) + (c == hi ? t : 0.f);
+}
 
 // The coarse voxels a brick of fine voxels needs, staged once per workgroup in LDS: per axis the range
 // [coarse_lo(first), coarse_lo(last) + 1], at most extent/2 + 2 values.
@@ -88,11 +94,12 @@ struct CoarseTile {
   int oz, oy, ox, nz, ny, nx;     // origin and extents (clamped to the coarse grid)
 };
 
-// displacement at fine voxel (z,y,x) from the staged tile.  The interpolation runs in fp64: an fp32 result
-// would carry ~2e-7 of rounding on a displacement of a few voxels, and the warp multiplies that by the local
-// feature gradient.
-__device__ __forceinline__ void upsampled_disp(const float* __restrict__ tile, const CoarseTile& ct, int Dc, int Hc,
-                                               int Wc, int z, int y, int x, double* u) {
+// Displacement of the 2x upsampled field at fine voxel (z,y,x); at(zi, yi, xi) points at a coarse voxel's three
+// values.  The interpolation runs in fp64: an fp32 result would carry ~2e-7 of rounding on a displacement of a few
+// voxels, and the warp multiplies that by the local feature gradient.  Every caller goes through this one function,
+// so kernels that classify a voxel by its displacement agree bit for bit.
+template <class At>
+__device__ __forceinline__ void upsample_mix(int Dc, int Hc, int Wc, int z, int y, int x, double* u, At at) {
   const int z0 = coarse_lo(z), y0 = coarse_lo(y), x0 = coarse_lo(x);
   const int z1 = min(z0 + 1, Dc - 1), y1 = min(y0 + 1, Hc - 1), x1 = min(x0 + 1, Wc - 1);
   // fractions are multiples of 1/4: exact in fp32; 0 where the coordinate was clamped
@@ -102,13 +109,62 @@ __device__ __forceinline__ void upsampled_disp(const float* __restrict__ tile, c
   u[0] = u[1] = u[2] = 0.0;
 #pragma unroll
   for (int c = 0; c < 8; ++c) {
-    const int zi = ((c & 4) ? z1 : z0) - ct.oz, yi = ((c & 2) ? y1 : y0) - ct.oy, xi = ((c & 1) ? x1 : x0) - ct.ox;
     const double w = (double)(((c & 4) ? tz : 1.f - tz) * ((c & 2) ? ty : 1.f - ty) * ((c & 1) ? tx : 1.f - tx));
-    const float* p = tile + ((zi * ct.ny + yi) * ct.nx + xi) * 3;
+    const float* p = at((c & 4) ? z1 : z0, (c & 2) ? y1 : y0, (c & 1) ? x1 : x0);
     u[0] = fma(w, (double)p[0], u[0]); u[1] = fma(w, (double)p[1], u[1]); u[2] = fma(w, (double)p[2], u[2]);
   }
   u[0] *= 2.0; u[1] *= 2.0; u[2] *= 2.0;
 }
+
+// from the tile staged in LDS
+__device__ __forceinline__ void upsampled_disp(const float* __restrict__ tile, const CoarseTile& ct, int Dc, int Hc,
+                                               int Wc, int z, int y, int x, double* u) {
+  upsample_mix(Dc, Hc, Wc, z, y, x, u, [&](int zi, int yi, int xi) {
+    return tile + (((zi - ct.oz) * ct.ny + yi - ct.oy) * ct.nx + xi - ct.ox) * 3;
+  });
+}
+
+// straight from the coarse field of one batch item in global memory
+__device__ __forceinline__ void upsampled_disp_global(const float* __restrict__ fc, int Dc, int Hc, int Wc, int z,
+                                                      int y, int x, double* u) {
+  upsample_mix(Dc, Hc, Wc, z, y, x, u, [&](int zi, int yi, int xi) {
+    return fc + (((long long)zi * Hc + yi) * Wc + xi) * 3;
+  });
+}
+
+// A displacement split into whole voxels and the fraction in [0, 1) (the fraction of an fp32 value is exact in
+// fp64; the integer part is clamped far outside any volume so that adding a coordinate cannot overflow).
+struct Split { int fz, fy, fx; float tz, ty, tx; };
+__device__ __forceinline__ Split split_disp(const double* u) {
+  const double fz = floor(u[0]), fy = floor(u[1]), fx = floor(u[2]);
+  Split s;
+  s.tz = (float)(u[0] - fz); s.ty = (float)(u[1] - fy); s.tx = (float)(u[2] - fx);
+  s.fz = (int)fmin(fmax(fz, -1.0e6), 1.0e6);
+  s.fy = (int)fmin(fmax(fy, -1.0e6), 1.0e6);
+  s.fx = (int)fmin(fmax(fx, -1.0e6), 1.0e6);
+  return s;
+}
+
+// The adjoint of the warp splits dsrc into boxes of kBoxXY x kBoxXY voxels in (y, x) and 2^lshift planes in z.
+// Every box has a whole-voxel offset c: the displacement at its centre voxel, rounded to the nearest integer.  A
+// smooth field moves the voxels that land in a box by about that much, so the box's owner looks for them around
+// (box - c).  One function computes c for everybody, so that all kernels agree on it bit for bit.
+constexpr int kBoxXY = 16;
+constexpr int kNear = 3;        // a contribution p -> t is "near" if |(t - p) - c(box of t)| <= kNear on every axis
+template <bool HALF>
+__device__ __forceinline__ void box_offset(const float* __restrict__ fb, int D, int H, int W, int lshift, int bz,
+                                           int by, int bx, int* c) {
+  const int zc = min((bz << lshift) + ((1 << lshift) >> 1), D - 1);
+  const int yc = min(by * kBoxXY + kBoxXY / 2, H - 1), xc = min(bx * kBoxXY + kBoxXY / 2, W - 1);
+  // (half resolution: twice the coarse voxel under the centre; c only has to be close to the displacements
+  // around the box, and the same for everybody)
+  const float* f = HALF ? fb + (((long long)(zc >> 1) * (H / 2) + (yc >> 1)) * (W / 2) + (xc >> 1)) * 3
+                        : fb + (((long long)zc * H + yc) * W + xc) * 3;
+  const double s = HALF ? 2.0 : 1.0;
+#pragma unroll
+  for (int a = 0; a < 3; ++a) c[a] = (int)fmin(fmax(floor(s * (double)f[a] + 0.5), -1.0e6), 1.0e6);
+}
+__device__ __forceinline__ bool within(int o, int c) { return o - c >= -kNear && o - c <= kNear; }
 
 // Work mapping: a workgroup handles a brick of BX x BY x BZ voxels (x fastest, then the channel chunk
 // inside a voxel), so the 8 corners of neighbouring voxels are found in the CU's own L1 instead of being
@@ -128,7 +184,7 @@ inline Brick make_brick(int D, int H, int W, int nchunk) {
   bk.nbz = (D + bk.bz - 1) / bk.bz;
   auto lg = [](int n) { int s = 0; while ((1 << s) < n) ++s; return (1 << s) == n ? s : -1; };
   bk.sc = lg(nchunk); bk.sx = lg(bk.bx); bk.sy = lg(bk.by);
-  if (bk.sx < 0 || bk.sy < 0) bk.sc = -1;
+  if (bk.sx < 0 || bk.sy < 0 || nchunk > 64) bk.sc = -1;      // (a voxel's lanes must sit in one wavefront)
   return bk;
 }
 
@@ -234,22 +290,403 @@ hipError_t launch_t(const void* src, const float* field, void* out, int B, int D
 }
 
 // ---- adjoint of the warp --------------------------------------------------------------------------
-// Gradients of L = sum(dout * warp(src, field)).  Same work mapping as the warp: one lane per (voxel, channel
-// chunk).  The source gradient is the transpose of the gather, a scatter: each lane adds weight * dout to the
-// eight corners it would have read, with hardware fp32 atomics (the order of the additions, hence the last
-// bits of the result, is not fixed).  The field gradient differentiates the corner weights: per corner the dot
-// product of dout with the source values, signed by the side of the corner along the axis; the lanes of one
-// voxel are summed by lane shuffles when they form an aligned power-of-two group, and one of them writes
-// (full resolution) or scatters through the 2x upsampling weights (half resolution).
+// Gradients of L = sum(dout * warp(src, field)).  The source gradient is the transpose of the gather, a scatter:
+// every voxel p adds weight * dout[p] to the eight corners t it would have read.  It runs in two passes.
+//
+// Pass 1 (warp_adj_near_kernel) turns the scatter into owner-computes for the near contributions (see box_offset
+// above).  A workgroup owns one box of dsrc and walks the planes of the source voxels that can reach it near-ly:
+// its (y, x) footprint shifted by -c and widened by kNear, planes za - cz - kNear ... zb - 1 - cz + kNear.  The
+// 2 kNear + 1 target planes that the current source plane can touch live in LDS.  Per source plane: (a) one lane
+// per voxel of the widened plane splits its displacement and, if a near corner lands in the box, appends a
+// record (source index, LDS target, validity of the six corner coordinates, fractions) to a list in LDS; (b) one
+// lane per (record, channel) loads its dout value and adds the weighted copies to the planes in LDS; (c) the
+// target plane that no later source plane can reach is written to dsrc with plain, coalesced stores and its LDS
+// slot cleared.  Every element of dsrc is written exactly once here: no zero-fill pass, no global atomic.
+//
+// LDS float atomics run at a few lanes per clock on this chip (measured: ~190 clocks per wave-wide ds_add_f32,
+// against ~8 for a read, an add and a write), so the adds of step (b) are plain read-modify-writes made safe by
+// ownership: wavefront w alone touches the target rows [w kAdjRows, (w + 1) kAdjRows) of every plane in the
+// ring.  Step (a) files each record under the wave that owns both of its corner rows (list from the front of the
+// wave's bin: eight corners each) or, row by row, under the two waves that own one each (list from the back: four
+// corners each).  In step (b) a wave works through its own bin, 64 / (lanes per entry) entries per instruction, a
+// lane taking four channels (or all, if fewer).  LDS operations of one wave execute in order, so two lanes can
+// only collide inside one instruction, and only (see adj_apply) if their entries' first adds go to the same (row,
+// column): step (a) numbers the entries of a step that share one (an LDS counter per row and column), and an
+// instruction applies its entries in turns, one number at a time.
+//
+// Pass 2 (warp_adj_far_kernel, one lane per voxel) finds the contributions that are not near and adds them with
+// hardware fp32 atomics on top: for every voxel that has any, the whole wave takes one (corner, channel) pair per
+// lane, so that an atomic covers the contiguous channels of a corner.  Both passes decide from the same arithmetic
+// (split_disp of the same fp64 displacement, box_offset of the same box), so each contribution is added exactly
+// once.  The order of the additions to one element, hence the last bits of the result, is not fixed.
+//
+// The field gradient (warp_dfield_kernel, one lane per voxel and channel) differentiates the corner weights: per
+// corner the dot product of dout with the source values, signed by the side of the corner along the axis; the
+// lanes of one voxel are summed by lane shuffles when they form an aligned power-of-two group, and one of them
+// writes (full resolution) or scatters through the 2x upsampling weights (half resolution).
+constexpr int kAdjThreads = 512, kAdjWaves = kAdjThreads / 64, kAdjRows = kBoxXY / kAdjWaves;
+constexpr int kAdjCols = kBoxXY + 2;               // columns a lower corner can have: -1 ... kBoxXY
+constexpr int kAdjLastTurn = 63;
+
+struct AdjRec {
+  int vox;            // source voxel, index inside its batch item
+  unsigned bits;      // [0,6) x0 - box_x + 1, [6,12) y0 - box_y + 1, [12,16) ring slot of z0, [16,20) of z0 + 1,
+                      // [20,26) this corner coordinate is near and inside the box: z0, z0+1, y0, y0+1, x0, x0+1
+  float tz, ty, tx;
+};
+struct AdjGrid { int nbx, nby, nbz, lshift, nch; };   // boxes along x, y, z, log2 of their depth, channel chunks
+
+// Step (b) for a wave's bin.  An entry is a record index (9 bits), for the back list the corner row (bit 9), and
+// its turn (bits 10-15).  Front list: both corner rows, eight adds; back list: four adds.  Two entries of one
+// instruction whose first adds go to different (row, column) pairs can only meet where the upper-x corner of one
+// is the lower-x corner of the other, so the lower-x adds of all lanes go first, as one batch of independent
+// read-modify-writes (all reads, then all writes), and the upper-x adds follow as a second batch.  Entries that
+// share (row, column) have different turns; those past the last turn number are applied one entry at a time.
+template <int CC, bool VEC4>
+struct AdjFetch {                                  // one round of one list, fetched ahead of its adds
+  static constexpr int VW = CC >= 4 ? 4 : CC;      // channels per lane
+  unsigned ent;                                    // bit 16: there is an entry
+  AdjRec r;
+  float g[VW];
+  __device__ __forceinline__ void entry(const unsigned short* __restrict__ list, int i, int n, bool back) {
+    ent = i < n ? (unsigned)list[back ? -i : i] | 0x10000u : 0u;
+  }
+  __device__ __forceinline__ void value(const float* __restrict__ dbase, int C, int chb, int cleft) {
+    const float* gp = dbase + (long long)r.vox * C + chb;
+#pragma unroll
+    for (int j = 0; j < VW; ++j) g[j] = 0.f;
+    if (ent >> 16) {
+      if (VEC4) {                                  // (C is a multiple of 4: a lane's channels exist together)
+        if (chb < cleft) Vec<float, VW>::load(gp, g);
+      } else {
+#pragma unroll
+        for (int j = 0; j < VW; ++j)
+          if (chb + j < cleft) g[j] = gp[j];
+      }
+    }
+  }
+};
+
+template <int CC, bool ROW, bool VEC4, int PLANE>
+__device__ __forceinline__ void adj_adds(float* __restrict__ ring, const AdjFetch<CC, VEC4>& f, int lane) {
+  constexpr int T = kBoxXY;
+  constexpr int VW = CC >= 4 ? 4 : CC, LPE = CC / VW;
+  constexpr int NB = ROW ? 2 : 4;                  // adds per batch: (plane) or (plane, row) pairs
+  const int chb = (lane % LPE) * VW;
+  const bool any = (f.ent >> 16) != 0u;
+  const unsigned bits = f.r.bits;
+  const unsigned up = ROW ? (f.ent >> 9) & 1u : 0u;
+  const int turn = (int)((f.ent >> 10) & 63u);
+  const int row = (int)((bits >> 6) & 63u) - 1 + (int)up;                // of the first add
+  const int a0 = (row * T + (int)(bits & 63u) - 1) * CC + chb;
+  const int sl[2] = {(int)((bits >> 12) & 15u) * PLANE, (int)((bits >> 16) & 15u) * PLANE};
+  const float wy1 = up ? f.r.ty : 1.f - f.r.ty;
+  auto batches = [&](bool on) {
+#pragma unroll
+    for (int kx = 0; kx < 2; ++kx) {
+      const float wx = kx ? f.r.tx : 1.f - f.r.tx;
+      const bool okx = on && ((bits >> (24 + kx)) & 1u) != 0u;
+      int addr[NB];
+      bool ok[NB];
+      float val[NB][VW];
+#pragma unroll
+      for (int c = 0; c < NB; ++c) {
+        const int kz = ROW ? c : c >> 1, ky = ROW ? 0 : c & 1;
+        ok[c] = okx && ((bits >> (20 + kz)) & 1u) != 0u && (ROW || ((bits >> (22 + ky)) & 1u) != 0u);
+        addr[c] = sl[kz] + a0 + (ky * T + kx) * CC;
+        if (ok[c]) Vec<float, VW>::load(ring + addr[c], val[c]);
+      }
+#pragma unroll
+      for (int c = 0; c < NB; ++c) {
+        const int kz = ROW ? c : c >> 1, ky = ROW ? 0 : c & 1;
+        const float wy = ROW ? wy1 : (ky ? f.r.ty : 1.f - f.r.ty);
+        const float w = (kz ? f.r.tz : 1.f - f.r.tz) * wy * wx;
+        if (ok[c]) {
+#pragma unroll
+          for (int j = 0; j < VW; ++j) val[c][j] = fmaf(w, f.g[j], val[c][j]);
+          Vec<float, VW>::store(ring + addr[c], val[c]);
+        }
+      }
+      asm volatile("" ::: "memory");               // the next batch's reads stay behind these writes
+    }
+  };
+  for (int rd = 0; rd < kAdjLastTurn && __ballot(any && turn >= rd) != 0ull; ++rd) batches(any && turn == rd);
+  // (rare) entries past the last turn number, one at a time
+  for (unsigned long long m = __ballot(any && turn == kAdjLastTurn); m != 0ull;) {
+    const int l = __ffsll((long long)m) - 1;
+    batches(any && turn == kAdjLastTurn && lane / LPE == l / LPE);
+    m &= ~(((1ull << LPE) - 1ull) << (l / LPE * LPE));
+  }
+}
+
+// nf entries from `front` upwards, nb entries from `back` downwards.  The first two rounds of each list (all of it,
+// usually) are fetched together, before the first add: one wait for memory per step.
+template <int CC, bool VEC4, int PLANE>
+__device__ __forceinline__ void adj_apply(float* __restrict__ ring, const AdjRec* __restrict__ rec,
+                                          const unsigned short* __restrict__ front, int nf,
+                                          const unsigned short* __restrict__ back, int nb,
+                                          const float* __restrict__ dbase, int C, int cleft, int lane) {
+  constexpr int VW = CC >= 4 ? 4 : CC, LPE = CC / VW, EPI = 64 / LPE;    // lanes per entry, entries per instruction
+  const int slot = lane / LPE, chb = (lane % LPE) * VW;
+  AdjFetch<CC, VEC4> f[4];                         // rounds 0, 1 of the front list, rounds 0, 1 of the back list
+  for (int i0 = 0; i0 < nf || i0 < nb; i0 += 2 * EPI) {
+#pragma unroll
+    for (int k = 0; k < 4; ++k) f[k].entry(k < 2 ? front : back, i0 + (k & 1) * EPI + slot, k < 2 ? nf : nb, k >= 2);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) f[k].r = rec[f[k].ent & 511u];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) f[k].value(dbase, C, chb, cleft);
+#pragma unroll
+    for (int k = 0; k < 2; ++k)
+      if (i0 + k * EPI < nf) adj_adds<CC, false, VEC4, PLANE>(ring, f[k], lane);       // (uniform)
+#pragma unroll
+    for (int k = 0; k < 2; ++k)
+      if (i0 + k * EPI < nb) adj_adds<CC, true, VEC4, PLANE>(ring, f[2 + k], lane);
+  }
+}
+
+template <int CC, bool HALF, bool VEC4>
+__global__ void __launch_bounds__(kAdjThreads)
+warp_adj_near_kernel(const float* __restrict__ field, const float* __restrict__ dout, float* __restrict__ dsrc,
+                     int B, int D, int H, int W, int C, AdjGrid gr) {
+  constexpr int M = kNear, T = kBoxXY;
+  constexpr int NR = 2 * M + 1;                                    // target planes alive at a time
+  constexpr int DX = T + 2 * M;                                    // the widened plane of source voxels
+  constexpr int NREC = DX * DX;
+  constexpr int PLANE = T * T * CC;
+  constexpr int SC = CC == 8 ? 3 : CC == 4 ? 2 : CC == 2 ? 1 : 0;
+  constexpr int NOCC = (kAdjWaves + T) * kAdjCols;                 // counters of the front keys, then of the back keys
+  static_assert((1 << SC) == CC && NR <= 15 && T + 1 < 64 && NREC <= kAdjThreads && NREC <= 512 &&
+                NOCC <= kAdjThreads, "layout");
+  __shared__ __align__(16) float ring[NR * PLANE];
+  __shared__ AdjRec rec[NREC];
+  __shared__ unsigned short bin[kAdjWaves][NREC];    // entries: front list from [0] upwards, back list from the end
+  __shared__ int cnt[2][2 * kAdjWaves + 1];          // per parity of the step: front and back entries per wave, records
+  __shared__ int occ[2][NOCC];                       // per parity: entries so far per (row pair or row, column)
+
+  const unsigned nb = gridDim.x, xcd = blockIdx.x & 7u, q = nb >> 3, rem = nb & 7u;
+  unsigned blk = xcd * q + (xcd < rem ? xcd : rem) + (blockIdx.x >> 3);
+  const int ibx = blk % gr.nbx; blk /= gr.nbx;
+  const int iby = blk % gr.nby; blk /= gr.nby;
+  const int ibz = blk % gr.nbz; blk /= gr.nbz;
+  const int ich = blk % gr.nch;
+  const int b = blk / gr.nch;
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int tx0 = ibx * T, ty0 = iby * T, za = ibz << gr.lshift, zb = min(za + (1 << gr.lshift), D);
+  const int tw = min(T, W - tx0), th = min(T, H - ty0);
+  const int c0 = ich * CC;
+  const long long vb = (long long)b * D * H * W;
+  const int Dc = D / 2, Hc = H / 2, Wc = W / 2;
+  const float* fb = HALF ? field + (long long)b * Dc * Hc * Wc * 3 : field + vb * 3;
+  int cb[3];
+  box_offset<HALF>(fb, D, H, W, gr.lshift, ibz, iby, ibx, cb);
+  const int cz = cb[0], cy = cb[1], cx = cb[2];
+
+  for (int i = tid; i < NR * PLANE; i += kAdjThreads) ring[i] = 0.f;
+  if (tid < 2 * (2 * kAdjWaves + 1)) (&cnt[0][0])[tid] = 0;
+  if (tid < NOCC) { occ[0][tid] = 0; occ[1][tid] = 0; }
+  __syncthreads();
+
+  // this lane's voxel of the widened plane
+  const int yy = tid / DX, xx = tid - yy * DX;
+  const int y = ty0 - cy - M + yy, x = tx0 - cx - M + xx;
+  const bool mine = tid < NREC && (unsigned)y < (unsigned)H && (unsigned)x < (unsigned)W;
+  const float* dbase = dout + vb * C + c0;
+
+  // source planes that reach [za, zb) near-ly; the last 2 M steps of the walk only flush.  (Clipped: a step below
+  // plane 0, or 2 M and more beyond the last plane, has neither sources nor anything to flush but zeros.)
+  const int zs0 = max(za - cz - M, 0), zs1 = min(zb - cz + M, D + 2 * M);
+  float fu[3] = {0.f, 0.f, 0.f};                   // (full-resolution field) the displacement, one plane ahead
+  if (!HALF && mine && zs0 < D) {
+    const float* f = fb + ((long long)(zs0 * H + y) * W + x) * 3;
+    fu[0] = f[0]; fu[1] = f[1]; fu[2] = f[2];
+  }
+  for (int z = zs0; z < zs1; ++z) {
+    const bool have = z < D;                       // (uniform) is there a plane of source voxels at z?
+    const int par = (z - zs0) & 1;
+    if (have) {
+      // (a) the records of this plane
+      bool hit = false;
+      AdjRec r = {};
+      int w0 = -1, w1 = -1;                        // the waves that own the rows of its lower and upper corners
+      int ly = 0, lx = 0;
+      if (mine) {
+        const int v = (z * H + y) * W + x;
+        double u[3];
+        if (HALF) upsampled_disp_global(fb, Dc, Hc, Wc, z, y, x, u);
+        else { u[0] = fu[0]; u[1] = fu[1]; u[2] = fu[2]; }
+        const Split sp = split_disp(u);
+        const int z0 = z + sp.fz;                  // lower corner; ly, lx: box-relative
+        ly = y + sp.fy - ty0;
+        lx = x + sp.fx - tx0;
+        const unsigned vz0 = within(sp.fz, cz) && z0 >= za && z0 < zb;
+        const unsigned vz1 = within(sp.fz + 1, cz) && z0 + 1 >= za && z0 + 1 < zb;
+        const unsigned vy0 = within(sp.fy, cy) && (unsigned)ly < (unsigned)th;
+        const unsigned vy1 = within(sp.fy + 1, cy) && (unsigned)(ly + 1) < (unsigned)th;
+        const unsigned vx0 = within(sp.fx, cx) && (unsigned)lx < (unsigned)tw;
+        const unsigned vx1 = within(sp.fx + 1, cx) && (unsigned)(lx + 1) < (unsigned)tw;
+        hit = (vz0 | vz1) && (vy0 | vy1) && (vx0 | vx1);
+        if (hit) {       // (then z0 - za >= -1, ly >= -1, lx >= -1)
+          const unsigned s0 = (unsigned)(z0 - za + NR) % NR, s1 = s0 + 1 == NR ? 0u : s0 + 1;
+          r.vox = v;
+          r.bits = (unsigned)(lx + 1) | ((unsigned)(ly + 1) << 6) | (s0 << 12) | (s1 << 16) | (vz0 << 20) |
+                   (vz1 << 21) | (vy0 << 22) | (vy1 << 23) | (vx0 << 24) | (vx1 << 25);
+          r.tz = sp.tz; r.ty = sp.ty; r.tx = sp.tx;
+          if (vy0) w0 = ly / kAdjRows;
+          if (vy1) w1 = (ly + 1) / kAdjRows;
+        }
+      }
+      const unsigned long long m = __ballot(hit);
+      int at = 0;
+      if (lane == 0 && m) at = atomicAdd(&cnt[par][2 * kAdjWaves], __popcll(m));
+      at = __shfl(at, 0);
+      if (hit) {
+        const unsigned ri = (unsigned)(at + __popcll(m & ((1ull << lane) - 1ull)));
+        rec[ri] = r;
+        int* oc = &occ[par][0];
+        if (w0 == w1) {
+          const unsigned t = (unsigned)min(atomicAdd(oc + w0 * kAdjCols + lx + 1, 1), kAdjLastTurn);
+          bin[w0][atomicAdd(&cnt[par][2 * w0], 1)] = (unsigned short)(ri | (t << 10));
+        } else {
+          oc += kAdjWaves * kAdjCols;
+          if (w0 >= 0) {
+            const unsigned t = (unsigned)min(atomicAdd(oc + ly * kAdjCols + lx + 1, 1), kAdjLastTurn);
+            bin[w0][NREC - 1 - atomicAdd(&cnt[par][2 * w0 + 1], 1)] = (unsigned short)(ri | (t << 10));
+          }
+          if (w1 >= 0) {
+            const unsigned t = (unsigned)min(atomicAdd(oc + (ly + 1) * kAdjCols + lx + 1, 1), kAdjLastTurn);
+            bin[w1][NREC - 1 - atomicAdd(&cnt[par][2 * w1 + 1], 1)] = (unsigned short)(ri | (1u << 9) | (t << 10));
+          }
+        }
+      }
+    }
+    __syncthreads();
+    if (have) {
+      if (!HALF && mine && z + 1 < D) {            // the next plane's displacements arrive during step (b)
+        const float* f = fb + ((long long)((z + 1) * H + y) * W + x) * 3;
+        fu[0] = f[0]; fu[1] = f[1]; fu[2] = f[2];
+      }
+      // (b) this wave's bin
+      if (tid <= 2 * kAdjWaves) cnt[par ^ 1][tid] = 0;
+      if (tid < NOCC) occ[par ^ 1][tid] = 0;
+      adj_apply<CC, VEC4, PLANE>(ring, rec, &bin[wv][0], cnt[par][2 * wv], &bin[wv][NREC - 1], cnt[par][2 * wv + 1],
+                                 dbase, C, C - c0, lane);
+    }
+    __syncthreads();
+    // (c) target plane z + cz - M is complete: no source plane above z reaches it
+    const int zt = z + cz - M;
+    if (zt >= za && zt < zb) {
+      float* slot = ring + ((unsigned)(zt - za + NR) % NR) * PLANE;
+      float* o = dsrc + (vb + ((long long)zt * H + ty0) * W + tx0) * C + c0;
+      if (VEC4) {
+        constexpr int Q4 = CC / 4;
+        for (int e = tid; e < PLANE / 4; e += kAdjThreads) {
+          const int c4 = e % Q4, ex = (e / Q4) % T, ey = e / (Q4 * T);
+          const float4 val = *reinterpret_cast<const float4*>(slot + e * 4);
+          *reinterpret_cast<float4*>(slot + e * 4) = make_float4(0.f, 0.f, 0.f, 0.f);
+          if (ey < th && ex < tw && c0 + c4 * 4 < C)
+            *reinterpret_cast<float4*>(o + ((long long)ey * W + ex) * C + c4 * 4) = val;
+        }
+      } else {
+        for (int e = tid; e < PLANE; e += kAdjThreads) {
+          const int c = e & (CC - 1), ex = (e >> SC) % T, ey = (e >> SC) / T;
+          const float val = slot[e];
+          slot[e] = 0.f;
+          if (ey < th && ex < tw && c0 + c < C) o[((long long)ey * W + ex) * C + c] = val;
+        }
+      }
+    }
+  }
+  // target planes that no existing source plane precedes by cz - M (a box offset that points out of the volume)
+  // have received nothing and are still to be written
+  for (int zt = za; zt < zb; ++zt) {
+    const int z = zt - cz + M;                     // the source plane whose step flushes zt
+    if (z >= zs0 && z < zs1) continue;
+    float* o = dsrc + (vb + ((long long)zt * H + ty0) * W + tx0) * C + c0;
+    for (int e = tid; e < PLANE; e += kAdjThreads) {
+      const int c = e & (CC - 1), ex = (e >> SC) % T, ey = (e >> SC) / T;
+      if (ey < th && ex < tw && c0 + c < C) o[((long long)ey * W + ex) * C + c] = 0.f;
+    }
+  }
+}
+
+// Pass 2: one lane per voxel decides which of its corners are not near; the wave then scatters them together.
+template <bool HALF>
+__global__ void __launch_bounds__(kThreads)
+warp_adj_far_kernel(const float* __restrict__ field, const float* __restrict__ dout, float* __restrict__ dsrc, int B,
+                    int D, int H, int W, int C, int lshift) {
+  const long long nvox = (long long)B * D * H * W;
+  const long long v = (long long)blockIdx.x * kThreads + threadIdx.x;
+  const int lane = threadIdx.x & 63;
+  unsigned far = 0u;
+  int z0 = 0, y0 = 0, x0 = 0;
+  float tz = 0.f, ty = 0.f, tx = 0.f;
+  if (v < nvox) {
+    const int x = (int)(v % W), y = (int)((v / W) % H), z = (int)((v / ((long long)W * H)) % D);
+    const int b = (int)(v / ((long long)W * H * D));
+    const float* fb = HALF ? field + (long long)b * (D / 2) * (H / 2) * (W / 2) * 3
+                           : field + (long long)b * D * H * W * 3;
+    double u[3];
+    if (HALF) {
+      upsampled_disp_global(fb, D / 2, H / 2, W / 2, z, y, x, u);
+    } else {
+      u[0] = field[v * 3]; u[1] = field[v * 3 + 1]; u[2] = field[v * 3 + 2];
+    }
+    const Split sp = split_disp(u);
+    tz = sp.tz; ty = sp.ty; tx = sp.tx;
+    z0 = z + sp.fz; y0 = y + sp.fy; x0 = x + sp.fx;
+    int cb[3] = {0, 0, 0};
+    const int z1 = z0 + 1, y1 = y0 + 1, x1 = x0 + 1;
+    const bool inside = z0 >= 0 && z1 < D && y0 >= 0 && y1 < H && x0 >= 0 && x1 < W;
+    if (inside && (z0 >> lshift) == (z1 >> lshift) && y0 / kBoxXY == y1 / kBoxXY && x0 / kBoxXY == x1 / kBoxXY) {
+      // (most voxels) all eight corners in one box: one offset, two tests per axis
+      box_offset<HALF>(fb, D, H, W, lshift, z0 >> lshift, y0 / kBoxXY, x0 / kBoxXY, cb);
+      const unsigned nz = (within(sp.fz, cb[0]) ? 0x0Fu : 0u) | (within(sp.fz + 1, cb[0]) ? 0xF0u : 0u);
+      const unsigned ny = (within(sp.fy, cb[1]) ? 0x33u : 0u) | (within(sp.fy + 1, cb[1]) ? 0xCCu : 0u);
+      const unsigned nx = (within(sp.fx, cb[2]) ? 0x55u : 0u) | (within(sp.fx + 1, cb[2]) ? 0xAAu : 0u);
+      far = ~(nz & ny & nx) & 0xFFu;
+    } else {
+      int lbz = -1, lby = -1, lbx = -1;              // the box whose offset is at hand
+      for (int c = 0; c < 8; ++c) {
+        const int oz = sp.fz + ((c >> 2) & 1), oy = sp.fy + ((c >> 1) & 1), ox = sp.fx + (c & 1);
+        const int zt = z + oz, yt = y + oy, xt = x + ox;
+        if ((unsigned)zt < (unsigned)D && (unsigned)yt < (unsigned)H && (unsigned)xt < (unsigned)W) {
+          const int bz = zt >> lshift, by = yt / kBoxXY, bx = xt / kBoxXY;
+          if (bz != lbz || by != lby || bx != lbx) {
+            box_offset<HALF>(fb, D, H, W, lshift, bz, by, bx, cb);
+            lbz = bz; lby = by; lbx = bx;
+          }
+          if (!(within(oz, cb[0]) && within(oy, cb[1]) && within(ox, cb[2]))) far |= 1u << c;
+        }
+      }
+    }
+  }
+  // the voxels of this wave that have something to add, one after the other: lane = (corner, channel mod 8)
+  const int c = lane >> 3;
+  for (unsigned long long pend = __ballot(far != 0u); pend != 0ull; pend &= pend - 1ull) {
+    const int l = __builtin_amdgcn_readfirstlane(__ffsll((long long)pend) - 1);
+    const unsigned lfar = (unsigned)__shfl((int)far, l);
+    const int zi = __shfl(z0, l) + ((c >> 2) & 1), yi = __shfl(y0, l) + ((c >> 1) & 1), xi = __shfl(x0, l) + (c & 1);
+    const float lz = __shfl(tz, l), ly = __shfl(ty, l), lx = __shfl(tx, l);
+    if (!((lfar >> c) & 1u)) continue;             // (far corners lie inside the volume)
+    const long long lv = (v - lane) + l;           // the voxel of lane l
+    const long long bv = lv / ((long long)W * H * D) * ((long long)W * H * D);
+    const float w = ((c & 4) ? lz : 1.f - lz) * ((c & 2) ? ly : 1.f - ly) * ((c & 1) ? lx : 1.f - lx);
+    float* o = dsrc + (bv + ((long long)zi * H + yi) * W + xi) * C;
+    const float* g = dout + lv * C;
+    for (int ch = lane & 7; ch < C; ch += 8) unsafeAtomicAdd(o + ch, w * g[ch]);
+  }
+}
+
 __global__ void zero_kernel(float* p, long long n) {
   const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) p[i] = 0.f;
 }
 
-template <class T, int VEC, bool HALF, bool FIELD>
+template <class T, int VEC, bool HALF>
 __global__ void __launch_bounds__(kThreads)
-warp_bwd_kernel(const T* __restrict__ src, const float* __restrict__ field, const float* __restrict__ dout,
-                float* __restrict__ dsrc, float* __restrict__ dfield, int B, int D, int H, int W, int C, Brick bk) {
+warp_dfield_kernel(const T* __restrict__ src, const float* __restrict__ field, const float* __restrict__ dout,
+                   float* __restrict__ dfield, int B, int D, int H, int W, int C, Brick bk) {
   const unsigned nb = gridDim.x, xcd = blockIdx.x & 7u, q = nb >> 3, rem = nb & 7u;
   unsigned blk = xcd * q + (xcd < rem ? xcd : rem) + (blockIdx.x >> 3);
   int chunk, lx, ly, lz;
@@ -274,7 +711,7 @@ warp_bwd_kernel(const T* __restrict__ src, const float* __restrict__ field, cons
   const int x = ibx * bk.bx + lx, y = iby * bk.by + ly, z = ibz * bk.bz + lz;
   const bool live = lz < bk.bz && x < W && y < H && z < D;
   __shared__ float tile[HALF ? kMaxTile * 3 : 1];
-  __shared__ float dtile[(HALF && FIELD) ? kMaxTile * 3 : 1];      // gradient of the staged coarse voxels
+  __shared__ float dus[HALF ? kThreads * 3 : 1];        // every lane's sums, for the coarse voxels to collect
   CoarseTile ct = {};
   const int Dc = D / 2, Hc = H / 2, Wc = W / 2;
   if (HALF) {
@@ -289,22 +726,14 @@ warp_bwd_kernel(const T* __restrict__ src, const float* __restrict__ field, cons
       const int ex = e % ct.nx, ey = (e / ct.nx) % ct.ny, ez = e / (ct.nx * ct.ny);
       const float* p = fc + (((long long)(ct.oz + ez) * Hc + ct.oy + ey) * Wc + ct.ox + ex) * 3;
       tile[e * 3] = p[0]; tile[e * 3 + 1] = p[1]; tile[e * 3 + 2] = p[2];
-      if (FIELD) { dtile[e * 3] = 0.f; dtile[e * 3 + 1] = 0.f; dtile[e * 3 + 2] = 0.f; }
     }
     __syncthreads();
   }
-  // (nobody leaves early: the scatter below moves values between neighbouring lanes, and with a half-resolution
-  // field gradient everybody meets again at a barrier)
+  // (nobody leaves early: with a half-resolution field everybody meets again at a barrier)
   float du[3] = {0.f, 0.f, 0.f};
   bool writer = false;       // does this lane hold the voxel's whole sum?
-  bool single = false;
-  int z0 = 0, y0 = 0, x0 = 0;
-  float tz = 0.f, ty = 0.f, tx = 0.f;
-  float g[VEC];
-#pragma unroll
-  for (int i = 0; i < VEC; ++i) g[i] = 0.f;
-  const long long vol = (long long)b * D * H * W * C + chunk * VEC;
   if (live) {
+    const long long vol = (long long)b * D * H * W * C + chunk * VEC;
     const long long v = (((long long)b * D + z) * H + y) * W + x;
     double u[3];
     if (HALF) {
@@ -312,143 +741,140 @@ warp_bwd_kernel(const T* __restrict__ src, const float* __restrict__ field, cons
     } else {
       u[0] = field[v * 3]; u[1] = field[v * 3 + 1]; u[2] = field[v * 3 + 2];
     }
-    const double fz = floor(u[0]), fy = floor(u[1]), fx = floor(u[2]);
-    tz = (float)(u[0] - fz); ty = (float)(u[1] - fy); tx = (float)(u[2] - fx);
-    z0 = z + (int)fmin(fmax(fz, -1.0e6), 1.0e6);
-    y0 = y + (int)fmin(fmax(fy, -1.0e6), 1.0e6);
-    x0 = x + (int)fmin(fmax(fx, -1.0e6), 1.0e6);
+    const Split sp = split_disp(u);
+    const float tz = sp.tz, ty = sp.ty, tx = sp.tx;
+    const int z0 = z + sp.fz, y0 = y + sp.fy, x0 = x + sp.fx;
+    float g[VEC];
     Vec<float, VEC>::load(dout + v * C + chunk * VEC, g);
-    if (FIELD) {
-      float val[8][VEC];
-      bool in[8];
+    float val[8][VEC];
+    bool in[8];
 #pragma unroll
-      for (int c = 0; c < 8; ++c) {     // all corner loads first, from clamped addresses
-        const int zi = z0 + ((c >> 2) & 1), yi = y0 + ((c >> 1) & 1), xi = x0 + (c & 1);
-        in[c] = (unsigned)zi < (unsigned)D && (unsigned)yi < (unsigned)H && (unsigned)xi < (unsigned)W;
-        const int zc = min(max(zi, 0), D - 1), yc = min(max(yi, 0), H - 1), xc = min(max(xi, 0), W - 1);
-        Vec<T, VEC>::load(src + vol + (((long long)zc * H + yc) * W + xc) * C, val[c]);
-      }
-#pragma unroll
-      for (int c = 0; c < 8; ++c) {
-        const float wz = (c & 4) ? tz : 1.f - tz, wy = (c & 2) ? ty : 1.f - ty, wx = (c & 1) ? tx : 1.f - tx;
-        if (in[c]) {
-          float dot = 0.f;
-#pragma unroll
-          for (int i = 0; i < VEC; ++i) dot = fmaf(g[i], val[c][i], dot);
-          du[0] = fmaf(((c & 4) ? wy : -wy) * wx, dot, du[0]);
-          du[1] = fmaf(((c & 2) ? wz : -wz) * wx, dot, du[1]);
-          du[2] = fmaf(((c & 1) ? wz : -wz) * wy, dot, du[2]);
-        }
-      }
-      writer = true;
-      if (bk.sc >= 0) {        // (uniform) the voxel's lanes are an aligned group of 2^sc lanes
-        for (int m = 1; m < (1 << bk.sc); m <<= 1) {
-          du[0] += __shfl_xor(du[0], m); du[1] += __shfl_xor(du[1], m); du[2] += __shfl_xor(du[2], m);
-        }
-        writer = chunk == 0;
-        single = true;
-      }
-      if (!HALF && writer) {
-        float* o = dfield + v * 3;
-        if (single) {          // the only writer of this voxel's entry
-          o[0] = du[0]; o[1] = du[1]; o[2] = du[2];
-        } else {
-          unsafeAtomicAdd(o, du[0]); unsafeAtomicAdd(o + 1, du[1]); unsafeAtomicAdd(o + 2, du[2]);
-        }
-      }
+    for (int c = 0; c < 8; ++c) {     // all corner loads first, from clamped addresses
+      const int zi = z0 + ((c >> 2) & 1), yi = y0 + ((c >> 1) & 1), xi = x0 + (c & 1);
+      in[c] = (unsigned)zi < (unsigned)D && (unsigned)yi < (unsigned)H && (unsigned)xi < (unsigned)W;
+      const int zc = min(max(zi, 0), D - 1), yc = min(max(yi, 0), H - 1), xc = min(max(xi, 0), W - 1);
+      Vec<T, VEC>::load(src + vol + (((long long)zc * H + yc) * W + xc) * C, val[c]);
     }
-  }
-  // ---- the scatter: weight * dout to the eight corners.  The upper-x corner of a voxel is the lower-x corner
-  // of its x-neighbour whenever both have the same integer displacement, which a smooth field gives almost
-  // always: the neighbour's lane (2^sc lanes up, when the voxel's lanes are such an aligned group) then takes
-  // the contribution over and adds both with one atomic, which nearly halves the cache lines the atomic units
-  // have to work through.
-  const bool comb = bk.sc >= 0;                 // uniform
-  const int nch = comb ? 1 << bk.sc : 1;
-  const int lane = threadIdx.x & 63;
-  bool same_prev = false, next_same = false;
-  if (comb) {
-    const int pz = __shfl_up(z0, nch), py = __shfl_up(y0, nch), px = __shfl_up(x0, nch);
-    const int pl = __shfl_up((int)live, nch);
-    same_prev = live && pl != 0 && lane >= nch && lx > 0 && pz == z0 && py == y0 && px + 1 == x0;
-    next_same = __shfl_down((int)same_prev, nch) != 0 && lane + nch < 64;
-  }
-#pragma unroll
-  for (int r = 0; r < 4; ++r) {                 // the four (z, y) corner rows
-    const float wzy = ((r & 2) ? tz : 1.f - tz) * ((r & 1) ? ty : 1.f - ty);
-    float lo[VEC], hi[VEC];
-#pragma unroll
-    for (int i = 0; i < VEC; ++i) { lo[i] = wzy * (1.f - tx) * g[i]; hi[i] = wzy * tx * g[i]; }
-    if (comb) {
-#pragma unroll
-      for (int i = 0; i < VEC; ++i) {
-        const float from_prev = __shfl_up(hi[i], nch);
-        if (same_prev) lo[i] += from_prev;
-      }
-    }
-    const int zi = z0 + (r >> 1), yi = y0 + (r & 1);
-    if (live && (unsigned)zi < (unsigned)D && (unsigned)yi < (unsigned)H) {
-      float* row = dsrc + vol + ((long long)zi * H + yi) * W * C;
-      if ((unsigned)x0 < (unsigned)W) {
-#pragma unroll
-        for (int i = 0; i < VEC; ++i) unsafeAtomicAdd(row + (long long)x0 * C + i, lo[i]);
-      }
-      if (!next_same && (unsigned)(x0 + 1) < (unsigned)W) {
-#pragma unroll
-        for (int i = 0; i < VEC; ++i) unsafeAtomicAdd(row + (long long)(x0 + 1) * C + i, hi[i]);
-      }
-    }
-  }
-  if (!(HALF && FIELD)) return;
-  // Half resolution: u = 2 * sum of weight * coarse value over the (clamped) coarse corners of a voxel, and up to
-  // 64 fine voxels share a coarse one.  The workgroup first sums into its LDS copy of the coarse tile, then adds
-  // every tile entry to the global gradient once.
-  if (live && writer) {
-    const int cz0 = coarse_lo(z), cy0 = coarse_lo(y), cx0 = coarse_lo(x);
-    const int cz1 = min(cz0 + 1, Dc - 1), cy1 = min(cy0 + 1, Hc - 1), cx1 = min(cx0 + 1, Wc - 1);
-    const float sz = (z == 0 || cz1 == cz0) ? 0.f : ((z & 1) ? 0.25f : 0.75f);
-    const float sy = (y == 0 || cy1 == cy0) ? 0.f : ((y & 1) ? 0.25f : 0.75f);
-    const float sx = (x == 0 || cx1 == cx0) ? 0.f : ((x & 1) ? 0.25f : 0.75f);
 #pragma unroll
     for (int c = 0; c < 8; ++c) {
-      const float w = 2.f * ((c & 4) ? sz : 1.f - sz) * ((c & 2) ? sy : 1.f - sy) * ((c & 1) ? sx : 1.f - sx);
-      if (w == 0.f) continue;
-      const int zi = ((c & 4) ? cz1 : cz0) - ct.oz, yi = ((c & 2) ? cy1 : cy0) - ct.oy, xi = ((c & 1) ? cx1 : cx0) - ct.ox;
-      float* o = dtile + ((zi * ct.ny + yi) * ct.nx + xi) * 3;
+      const float wz = (c & 4) ? tz : 1.f - tz, wy = (c & 2) ? ty : 1.f - ty, wx = (c & 1) ? tx : 1.f - tx;
+      if (in[c]) {
+        float dot = 0.f;
 #pragma unroll
-      for (int a = 0; a < 3; ++a)
-        __hip_atomic_fetch_add(o + a, w * du[a], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        for (int i = 0; i < VEC; ++i) dot = fmaf(g[i], val[c][i], dot);
+        du[0] = fmaf(((c & 4) ? wy : -wy) * wx, dot, du[0]);
+        du[1] = fmaf(((c & 2) ? wz : -wz) * wx, dot, du[1]);
+        du[2] = fmaf(((c & 1) ? wz : -wz) * wy, dot, du[2]);
+      }
+    }
+    writer = true;
+    bool single = false;
+    if (bk.sc >= 0) {        // (uniform) the voxel's lanes are an aligned group of 2^sc lanes
+      for (int m = 1; m < (1 << bk.sc); m <<= 1) {
+        du[0] += __shfl_xor(du[0], m); du[1] += __shfl_xor(du[1], m); du[2] += __shfl_xor(du[2], m);
+      }
+      writer = chunk == 0;
+      single = true;
+    }
+    if (!HALF && writer) {
+      float* o = dfield + v * 3;
+      if (single) {          // the only writer of this voxel's entry
+        o[0] = du[0]; o[1] = du[1]; o[2] = du[2];
+      } else {
+        unsafeAtomicAdd(o, du[0]); unsafeAtomicAdd(o + 1, du[1]); unsafeAtomicAdd(o + 2, du[2]);
+      }
     }
   }
+  if (!HALF) return;
+  // Half resolution: u = 2 * sum of weight * coarse value over the (clamped) coarse corners of a voxel, and up to
+  // 64 fine voxels share a coarse one.  The lanes park their sums in LDS; then one lane per staged coarse voxel
+  // collects, through the upsampling weights, what the brick's fine voxels owe it (along each axis the fine voxels
+  // 2c - 1 ... 2c + 2 touch coarse voxel c) and adds it to the global gradient once.
+#pragma unroll
+  for (int a = 0; a < 3; ++a) dus[threadIdx.x * 3 + a] = writer ? du[a] : 0.f;
   __syncthreads();
+  const int nlane = bk.sc >= 0 ? 1 : C / VEC;      // lanes of a voxel that hold a part of its sum
+  const int vstride = bk.sc >= 0 ? 1 << bk.sc : C / VEC;
+  const int xf = ibx * bk.bx, yf = iby * bk.by, zf = ibz * bk.bz;
+  const int xe = min(xf + bk.bx, W), ye = min(yf + bk.by, H), ze = min(zf + bk.bz, D);
   float* dc = dfield + (long long)b * Dc * Hc * Wc * 3;
   const int n = ct.nx * ct.ny * ct.nz;
   for (int e = threadIdx.x; e < n; e += kThreads) {
-    const int ex = e % ct.nx, ey = (e / ct.nx) % ct.ny, ez = e / (ct.nx * ct.ny);
-    float* o = dc + (((long long)(ct.oz + ez) * Hc + ct.oy + ey) * Wc + ct.ox + ex) * 3;
-    unsafeAtomicAdd(o, dtile[e * 3]); unsafeAtomicAdd(o + 1, dtile[e * 3 + 1]); unsafeAtomicAdd(o + 2, dtile[e * 3 + 2]);
+    const int cx = ct.ox + e % ct.nx, cy = ct.oy + (e / ct.nx) % ct.ny, cz = ct.oz + e / (ct.nx * ct.ny);
+    float acc[3] = {0.f, 0.f, 0.f};
+    for (int fz = max(2 * cz - 1, zf); fz <= min(2 * cz + 2, ze - 1); ++fz) {
+      const float wz = up_weight(fz, cz, Dc);
+      for (int fy = max(2 * cy - 1, yf); fy <= min(2 * cy + 2, ye - 1); ++fy) {
+        const float wzy = wz * up_weight(fy, cy, Hc);
+        for (int fx = max(2 * cx - 1, xf); fx <= min(2 * cx + 2, xe - 1); ++fx) {
+          const float w = 2.f * wzy * up_weight(fx, cx, Wc);
+          const int first = (((fz - zf) * bk.by + fy - yf) * bk.bx + fx - xf) * vstride;
+          for (int j = 0; j < nlane; ++j) {
+            const float* d = dus + (first + j) * 3;
+            acc[0] = fmaf(w, d[0], acc[0]); acc[1] = fmaf(w, d[1], acc[1]); acc[2] = fmaf(w, d[2], acc[2]);
+          }
+        }
+      }
+    }
+    float* o = dc + (((long long)cz * Hc + cy) * Wc + cx) * 3;
+    unsafeAtomicAdd(o, acc[0]); unsafeAtomicAdd(o + 1, acc[1]); unsafeAtomicAdd(o + 2, acc[2]);
   }
 }
 
+template <int CC, bool HALF, bool VEC4>
+void launch_adj_near(const float* field, const float* dout, float* dsrc, int B, int D, int H, int W, int C,
+                     int lshift, hipStream_t st) {
+  AdjGrid gr;
+  gr.nbx = (W + kBoxXY - 1) / kBoxXY;
+  gr.nby = (H + kBoxXY - 1) / kBoxXY;
+  gr.lshift = lshift;
+  gr.nbz = (D + (1 << lshift) - 1) >> lshift;
+  gr.nch = (C + CC - 1) / CC;
+  const long long boxes = (long long)gr.nbx * gr.nby * gr.nbz * gr.nch * B;
+  hipLaunchKernelGGL((warp_adj_near_kernel<CC, HALF, VEC4>), dim3((unsigned)boxes), dim3(kAdjThreads), 0, st, field,
+                     dout, dsrc, B, D, H, W, C, gr);
+}
 
 template <class T, int VEC>
 hipError_t launch_bwd_t(const void* src, const float* field, const float* dout, float* dsrc, float* dfield, int B,
                         int D, int H, int W, int C, int half, hipStream_t st) {
-  const Brick bk = make_brick(D, H, W, C / VEC);
-  const long long n = (long long)B * D * H * W * C;
-  hipLaunchKernelGGL(zero_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, dsrc, n);
+  // boxes of 16 planes (8 for shallow volumes): a deeper box strays further from its centre's displacement, a
+  // shallower one spends more of its walk on the 2 kNear planes beyond its ends
+  const int lshift = D > 8 ? 4 : 3;
+  // pass 1: every element of dsrc, from the near contributions (channels in chunks of up to 8: a power of two,
+  // the last chunk masked)
+  const bool v4 = C % 4 == 0;
+#define MODET_ADJ(CC_, V4_)                                                                              \
+  do {                                                                                                   \
+    if (half) launch_adj_near<CC_, true, V4_>(field, dout, dsrc, B, D, H, W, C, lshift, st);              \
+    else launch_adj_near<CC_, false, V4_>(field, dout, dsrc, B, D, H, W, C, lshift, st);                  \
+  } while (0)
+  if (C >= 5) { if (v4) MODET_ADJ(8, true); else MODET_ADJ(8, false); }
+  else if (C >= 3) { if (v4) MODET_ADJ(4, true); else MODET_ADJ(4, false); }
+  else if (C == 2) MODET_ADJ(2, false);
+  else MODET_ADJ(1, false);
+#undef MODET_ADJ
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  // pass 2: what is not near
+  const long long nvox = (long long)B * D * H * W;
+  const dim3 fgrid((unsigned)((nvox + kThreads - 1) / kThreads)), block(kThreads);
+  if (half) hipLaunchKernelGGL((warp_adj_far_kernel<true>), fgrid, block, 0, st, field, dout, dsrc, B, D, H, W, C, lshift);
+  else hipLaunchKernelGGL((warp_adj_far_kernel<false>), fgrid, block, 0, st, field, dout, dsrc, B, D, H, W, C, lshift);
+  if (!dfield) return hipGetLastError();
   // the field gradient is accumulated with atomics unless every entry has exactly one writer
-  if (dfield && (half || bk.sc < 0)) {
-    const long long nf = half ? (long long)B * (D / 2) * (H / 2) * (W / 2) * 3 : (long long)B * D * H * W * 3;
+  const Brick bk = make_brick(D, H, W, C / VEC);
+  if (half || bk.sc < 0) {
+    const long long nf = half ? (long long)B * (D / 2) * (H / 2) * (W / 2) * 3 : nvox * 3;
     hipLaunchKernelGGL(zero_kernel, dim3((unsigned)((nf + 255) / 256)), dim3(256), 0, st, dfield, nf);
   }
-  dim3 grid((unsigned)((long long)bk.nbx * bk.nby * bk.nbz * B)), block(kThreads);
-#define MODET_WB(HALF_, FIELD_)                                                                                      \
-  hipLaunchKernelGGL((warp_bwd_kernel<T, VEC, HALF_, FIELD_>), grid, block, 0, st, (const T*)src, field, dout, dsrc, \
-                     dfield, B, D, H, W, C, bk)
-  if (half) { if (dfield) MODET_WB(true, true); else MODET_WB(true, false); }
-  else { if (dfield) MODET_WB(false, true); else MODET_WB(false, false); }
-#undef MODET_WB
+  dim3 grid((unsigned)((long long)bk.nbx * bk.nby * bk.nbz * B));
+  if (half)
+    hipLaunchKernelGGL((warp_dfield_kernel<T, VEC, true>), grid, block, 0, st, (const T*)src, field, dout, dfield, B, D,
+                       H, W, C, bk);
+  else
+    hipLaunchKernelGGL((warp_dfield_kernel<T, VEC, false>), grid, block, 0, st, (const T*)src, field, dout, dfield, B,
+                       D, H, W, C, bk);
   return hipGetLastError();
 }
 

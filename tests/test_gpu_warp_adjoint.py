@@ -22,7 +22,8 @@ def modet():
     (1, 6, 8, 10, 3, "f32", False), (1, 6, 8, 10, 3, "f32", True), (1, 8, 6, 14, 16, "bf16", True),
     (1, 4, 5, 70, 16, "bf16", False), (1, 1, 1, 1, 4, "f32", False), (1, 2, 2, 2, 4, "f32", True),
     (1, 6, 7, 19, 6, "f32", False), (1, 6, 8, 18, 6, "bf16", True), (1, 5, 6, 11, 5, "f32", False),
-    (1, 4, 6, 8, 250, "f32", True), (2, 5, 7, 9, 12, "bf16", False),
+    (1, 4, 6, 8, 250, "f32", True), (2, 5, 7, 9, 12, "bf16", False), (1, 4, 6, 8, 128, "f32", False),
+    (1, 20, 18, 35, 2, "f32", False), (1, 18, 20, 34, 1, "f32", True), (2, 17, 33, 19, 8, "f32", False),
 ])
 def test_warp_bwd_matches_oracle(modet, B, D, H, W, C, dtype, half):
     src = synth.normal(81, 0, (B, D, H, W, C))
@@ -43,6 +44,30 @@ def test_warp_bwd_matches_oracle(modet, B, D, H, W, C, dtype, half):
     # its fp32 rounding is relative to the sum of the magnitudes, not to the result
     terms = 8.0 * np.sqrt(C) * (8.0 if half else 1.0)
     assert_close(dfield.cpu().numpy() / terms, ref_dfield / terms, "f32", "dfield " + tag)
+
+
+@pytest.mark.parametrize("shift,half,std", [
+    ((5.3, -7.6, 9.2), False, 1.2), ((-3.5, 4.5, -12.0), True, 1.0), ((40.0, 0.0, 0.0), False, 1.5),
+    ((0.25, 0.5, -60.0), True, 0.5), ((-2.0, 3.0, 1.0), False, 4.0), ((0.0, 0.0, 0.0), True, 3.0),
+])
+def test_warp_bwd_large_coherent_displacement(modet, shift, half, std):
+    """A smooth field around a large common shift (also one that points out of the volume, and rough ones): the
+    source gradient's staged pass follows the local displacement, the atomic pass takes what strays from it."""
+    B, D, H, W, C = 1, 36, 40, 50, 8
+    src = synth.normal(91, 0, (B, D, H, W, C))
+    dout = synth.normal(92, 0, (B, D, H, W, C))
+    if half:
+        field = synth.smooth_real_field(93, B, D // 2, H // 2, W // 2, std / 2) + np.float32(0.5) * np.asarray(shift, np.float32)
+    else:
+        field = synth.smooth_real_field(93, B, D, H, W, std) + np.asarray(shift, np.float32)
+    field = np.ascontiguousarray(field, dtype=np.float32)
+    ref_dsrc, ref_dfield = oracle.warp_bwd(src, field, dout, field_half_res=half)
+    dsrc, dfield = modet.modet_warp_bwd(up(src), up(field), up(dout), field_half_res=half)
+    only = modet.modet_warp_bwd(up(src), up(field), up(dout), field_half_res=half, want_dfield=False)
+    assert_close(dsrc.cpu().numpy(), ref_dsrc, "f32", f"dsrc shift={shift}")
+    assert_close(only.cpu().numpy(), ref_dsrc, "f32", f"dsrc alone shift={shift}")
+    terms = 8.0 * np.sqrt(C) * (8.0 if half else 1.0)
+    assert_close(dfield.cpu().numpy() / terms, ref_dfield / terms, "f32", f"dfield shift={shift}")
 
 
 def test_warp_bwd_is_the_transpose_of_the_gpu_warp(modet):
