@@ -367,10 +367,24 @@ def main():
             oracle.modet_fwd(Qs, Ks, heads, k, dtype=dtype)
             oracle.modet_bwd(Qs, Ks, gs, heads, k, dtype=dtype, form="gather")
             best = min(best, time.perf_counter() - t0)
+        nthreads = oracle.threads()
         cpu = {"value": round(B * Ds * H * W * heads / best, 1), "unit": "voxel-neighbourhoods/s",
-               "cores": oracle.threads(), "kind": "oracle",
+               "cores": nthreads, "kind": "oracle",
                "sample": f"fwd+bwd(gather form) of the fp64 oracle on planes 0..{Ds - 1} of {D} "
                          f"({B}x{Ds}x{H}x{W}), best of 2, {best:.2f} s"}
+        # the same oracle on one thread, on a slab 1/threads as deep (about the same wall time)
+        D1 = min(Ds, max(2 * k, Ds // max(1, nthreads)))
+        Q1, K1, g1 = c["Q"][:, :D1].copy(), c["K"][:, :D1].copy(), c["dphi"][:, :D1].copy()
+        oracle.set_threads(1)
+        try:
+            t0 = time.perf_counter()
+            oracle.modet_fwd(Q1, K1, heads, k, dtype=dtype)
+            oracle.modet_bwd(Q1, K1, g1, heads, k, dtype=dtype, form="gather")
+            one = time.perf_counter() - t0
+        finally:
+            oracle.set_threads(nthreads)
+        cpu["one_thread"] = {"value": round(B * D1 * H * W * heads / one, 1), "cores": 1,
+                             "sample": f"planes 0..{D1 - 1}, one run, {one:.2f} s"}
 
     value = nvn / (wall / args.steps)
     line = {

@@ -154,7 +154,7 @@ template <> struct Ld<bf16_t> {
 };
 
 // The input type T of a kernel names the element type AND the number of channels of a head in memory.  Heads
-// of six channels (the paper's small model, Section 4.2) are padded to eight in registers and in LDS: only
+// of six channels (the paper's small model, Section 4.4) are padded to eight in registers and in LDS: only
 // the loads from and the stores to global memory know about it, the two extra channels are zeros that take
 // part in the arithmetic.
 //

@@ -1,4 +1,4 @@
-// Forward of the LDS-tiled kernels for heads of twelve channels (the paper's large model, Section 4.2):
+// Forward of the LDS-tiled kernels for heads of twelve channels (the paper's large model, Section 4.4):
 // Eq. 3-5 with a head split into two half-heads in neighbouring lanes.
 #include "modet_tiled.hpp"
 

@@ -1,4 +1,4 @@
-// Forward of the LDS-tiled kernels for heads of six channels (the paper's small model, Section 4.2):
+// Forward of the LDS-tiled kernels for heads of six channels (the paper's small model, Section 4.4):
 // Eq. 3-5 with the channels padded to eight in registers and LDS.
 #include "modet_tiled.hpp"
 
