@@ -322,8 +322,9 @@ hipError_t launch_t(const void* src, const float* field, void* out, int B, int D
 //
 // The field gradient (warp_dfield_kernel, one lane per voxel and channel) differentiates the corner weights: per
 // corner the dot product of dout with the source values, signed by the side of the corner along the axis; the
-// lanes of one voxel are summed by lane shuffles when they form an aligned power-of-two group, and one of them
-// writes (full resolution) or scatters through the 2x upsampling weights (half resolution).
+// lanes of one voxel are summed by lane shuffles when they form an aligned power-of-two group, through LDS
+// otherwise, and one lane writes (full resolution); at half resolution the coarse voxels collect from the fine
+// ones through the 2x upsampling weights.
 constexpr int kAdjThreads = 512, kAdjWaves = kAdjThreads / 64, kAdjRows = kBoxXY / kAdjWaves;
 constexpr int kAdjCols = kBoxXY + 2;               // columns a lower corner can have: -1 ... kBoxXY
 constexpr int kAdjLastTurn = 63;
@@ -711,7 +712,7 @@ warp_dfield_kernel(const T* __restrict__ src, const float* __restrict__ field, c
   const int x = ibx * bk.bx + lx, y = iby * bk.by + ly, z = ibz * bk.bz + lz;
   const bool live = lz < bk.bz && x < W && y < H && z < D;
   __shared__ float tile[HALF ? kMaxTile * 3 : 1];
-  __shared__ float dus[HALF ? kThreads * 3 : 1];        // every lane's sums, for the coarse voxels to collect
+  __shared__ float dus[kThreads * 3];                   // every lane's sums, to be collected per (coarse) voxel
   CoarseTile ct = {};
   const int Dc = D / 2, Hc = H / 2, Wc = W / 2;
   if (HALF) {
@@ -768,31 +769,42 @@ warp_dfield_kernel(const T* __restrict__ src, const float* __restrict__ field, c
       }
     }
     writer = true;
-    bool single = false;
     if (bk.sc >= 0) {        // (uniform) the voxel's lanes are an aligned group of 2^sc lanes
       for (int m = 1; m < (1 << bk.sc); m <<= 1) {
         du[0] += __shfl_xor(du[0], m); du[1] += __shfl_xor(du[1], m); du[2] += __shfl_xor(du[2], m);
       }
       writer = chunk == 0;
-      single = true;
-    }
-    if (!HALF && writer) {
-      float* o = dfield + v * 3;
-      if (single) {          // the only writer of this voxel's entry
+      if (!HALF && writer) {     // the only writer of this voxel's entry
+        float* o = dfield + v * 3;
         o[0] = du[0]; o[1] = du[1]; o[2] = du[2];
-      } else {
-        unsafeAtomicAdd(o, du[0]); unsafeAtomicAdd(o + 1, du[1]); unsafeAtomicAdd(o + 2, du[2]);
       }
     }
   }
-  if (!HALF) return;
+  if (!HALF && bk.sc >= 0) return;               // (uniform)
+  // the lanes park their sums in LDS
+#pragma unroll
+  for (int a = 0; a < 3; ++a) dus[threadIdx.x * 3 + a] = writer ? du[a] : 0.f;
+  __syncthreads();
+  if (!HALF) {
+    // a voxel's lanes are no lane group (its channel count is no power of two): one lane per voxel adds their
+    // parts up and writes
+    const int nchunk = C / VEC, t = threadIdx.x;
+    const int vx = ibx * bk.bx + t % bk.bx, vy = iby * bk.by + (t / bk.bx) % bk.by, vz = ibz * bk.bz + t / (bk.bx * bk.by);
+    if (t < kThreads / nchunk && t / (bk.bx * bk.by) < bk.bz && vx < W && vy < H && vz < D) {
+      float acc[3] = {0.f, 0.f, 0.f};
+      for (int j = 0; j < nchunk; ++j) {
+        const float* d = dus + (t * nchunk + j) * 3;
+        acc[0] += d[0]; acc[1] += d[1]; acc[2] += d[2];
+      }
+      float* o = dfield + ((((long long)b * D + vz) * H + vy) * W + vx) * 3;
+      o[0] = acc[0]; o[1] = acc[1]; o[2] = acc[2];
+    }
+    return;
+  }
   // Half resolution: u = 2 * sum of weight * coarse value over the (clamped) coarse corners of a voxel, and up to
   // 64 fine voxels share a coarse one.  The lanes park their sums in LDS; then one lane per staged coarse voxel
   // collects, through the upsampling weights, what the brick's fine voxels owe it (along each axis the fine voxels
   // 2c - 1 ... 2c + 2 touch coarse voxel c) and adds it to the global gradient once.
-#pragma unroll
-  for (int a = 0; a < 3; ++a) dus[threadIdx.x * 3 + a] = writer ? du[a] : 0.f;
-  __syncthreads();
   const int nlane = bk.sc >= 0 ? 1 : C / VEC;      // lanes of a voxel that hold a part of its sum
   const int vstride = bk.sc >= 0 ? 1 << bk.sc : C / VEC;
   const int xf = ibx * bk.bx, yf = iby * bk.by, zf = ibz * bk.bz;
@@ -862,10 +874,10 @@ hipError_t launch_bwd_t(const void* src, const float* field, const float* dout, 
   if (half) hipLaunchKernelGGL((warp_adj_far_kernel<true>), fgrid, block, 0, st, field, dout, dsrc, B, D, H, W, C, lshift);
   else hipLaunchKernelGGL((warp_adj_far_kernel<false>), fgrid, block, 0, st, field, dout, dsrc, B, D, H, W, C, lshift);
   if (!dfield) return hipGetLastError();
-  // the field gradient is accumulated with atomics unless every entry has exactly one writer
+  // the half-resolution field gradient is accumulated with atomics (a coarse voxel collects from several bricks)
   const Brick bk = make_brick(D, H, W, C / VEC);
-  if (half || bk.sc < 0) {
-    const long long nf = half ? (long long)B * (D / 2) * (H / 2) * (W / 2) * 3 : nvox * 3;
+  if (half) {
+    const long long nf = (long long)B * (D / 2) * (H / 2) * (W / 2) * 3;
     hipLaunchKernelGGL(zero_kernel, dim3((unsigned)((nf + 255) / 256)), dim3(256), 0, st, dfield, nf);
   }
   dim3 grid((unsigned)((long long)bk.nbx * bk.nby * bk.nbz * B));
