@@ -616,22 +616,23 @@ template <bool HALF>
 __global__ void __launch_bounds__(kThreads)
 warp_adj_far_kernel(const float* __restrict__ field, const float* __restrict__ dout, float* __restrict__ dsrc, int B,
                     int D, int H, int W, int C, int lshift) {
-  const long long nvox = (long long)B * D * H * W;
-  const long long v = (long long)blockIdx.x * kThreads + threadIdx.x;
+  const unsigned nvox = (unsigned)B * D * H * W;  // (the host checks that B D H W C fits 31 bits)
+  const unsigned v = blockIdx.x * kThreads + threadIdx.x;
   const int lane = threadIdx.x & 63;
   unsigned far = 0u;
   int z0 = 0, y0 = 0, x0 = 0;
   float tz = 0.f, ty = 0.f, tx = 0.f;
   if (v < nvox) {
-    const int x = (int)(v % W), y = (int)((v / W) % H), z = (int)((v / ((long long)W * H)) % D);
-    const int b = (int)(v / ((long long)W * H * D));
+    const unsigned row = v / (unsigned)W, pl = row / (unsigned)H;
+    const int x = (int)(v - row * W), y = (int)(row - pl * H), b = (int)(pl / (unsigned)D), z = (int)(pl - b * D);
     const float* fb = HALF ? field + (long long)b * (D / 2) * (H / 2) * (W / 2) * 3
                            : field + (long long)b * D * H * W * 3;
     double u[3];
     if (HALF) {
       upsampled_disp_global(fb, D / 2, H / 2, W / 2, z, y, x, u);
     } else {
-      u[0] = field[v * 3]; u[1] = field[v * 3 + 1]; u[2] = field[v * 3 + 2];
+      const float* f = field + (long long)v * 3;
+      u[0] = f[0]; u[1] = f[1]; u[2] = f[2];
     }
     const Split sp = split_disp(u);
     tz = sp.tz; ty = sp.ty; tx = sp.tx;
@@ -670,11 +671,11 @@ warp_adj_far_kernel(const float* __restrict__ field, const float* __restrict__ d
     const int zi = __shfl(z0, l) + ((c >> 2) & 1), yi = __shfl(y0, l) + ((c >> 1) & 1), xi = __shfl(x0, l) + (c & 1);
     const float lz = __shfl(tz, l), ly = __shfl(ty, l), lx = __shfl(tx, l);
     if (!((lfar >> c) & 1u)) continue;             // (far corners lie inside the volume)
-    const long long lv = (v - lane) + l;           // the voxel of lane l
-    const long long bv = lv / ((long long)W * H * D) * ((long long)W * H * D);
+    const unsigned lv = (v - lane) + l;            // the voxel of lane l
+    const long long bv = (long long)(lv / ((unsigned)W * H * D)) * ((long long)W * H * D);
     const float w = ((c & 4) ? lz : 1.f - lz) * ((c & 2) ? ly : 1.f - ly) * ((c & 1) ? lx : 1.f - lx);
     float* o = dsrc + (bv + ((long long)zi * H + yi) * W + xi) * C;
-    const float* g = dout + lv * C;
+    const float* g = dout + (long long)lv * C;
     for (int ch = lane & 7; ch < C; ch += 8) unsafeAtomicAdd(o + ch, w * g[ch]);
   }
 }
