@@ -63,6 +63,8 @@ SMALL = [
     (1, 9, 8, 13, 96, 8, 3, "f32"),
     (1, 6, 5, 12, 128, 16, 3, "f32"),
     (1, 4, 6, 10, 256, 32, 3, "bf16"),
+    # head groups with two batch items and ragged tiles along W and H
+    (2, 4, 5, 33, 96, 16, 3, "f32"), (2, 3, 9, 7, 192, 16, 3, "bf16"), (2, 5, 11, 6, 128, 16, 3, "f32"),
 ]
 
 
@@ -117,7 +119,8 @@ def test_small_cases_match_oracle(modet, shape, path):
 # both dtypes
 BIASED = [SMALL[1], SMALL[3], SMALL[4], SMALL[6], SMALL[8], SMALL[12], SMALL[13], SMALL[16], SMALL[17], SMALL[18],
           SMALL[19], SMALL[20], SMALL[21], SMALL[22], SMALL[23], SMALL[24], SMALL[25], SMALL[26], SMALL[27],
-          SMALL[28], SMALL[29], SMALL[30], SMALL[31], SMALL[32], SMALL[33], SMALL[34], SMALL[35], SMALL[36], SMALL[37]]
+          SMALL[28], SMALL[29], SMALL[30], SMALL[31], SMALL[32], SMALL[33], SMALL[34], SMALL[35], SMALL[36], SMALL[37],
+          SMALL[38], SMALL[39], SMALL[40]]
 
 
 @pytest.mark.parametrize("shape", BIASED, ids=lambda s: "x".join(map(str, s)))
