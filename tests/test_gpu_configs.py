@@ -220,3 +220,35 @@ def test_config4_free_running_against_oracle_loop(modet, nlev, iters):
           f"max abs difference {err.max():.3g}")
     assert drift_loss.max() <= 1e-3
     assert (err <= 1e-3 * np.abs(ref_phi) + 1e-4).all()
+
+
+@pytest.mark.parametrize("name,d,heads_per_level,vol", [
+    ("small", 6, (8, 4, 2, 1, 1), (160, 192, 160)),
+    ("large", 12, (32, 16, 8, 4, 1), (160, 160, 192)),
+])
+def test_paper_model_shapes_sampled(modet, name, d, heads_per_level, vol):
+    """The shapes of the paper's own models (Section 4.4: heads of 6 channels with 8, 4, 2, 1, 1 heads, heads of 12
+    with 32, 16, 8, 4, 1, coarse to fine) on its two volume sizes (Section 4.1), every pyramid level: forward and
+    backward with bias on the automatic kernel path (all of them tiled), sampled windows against the oracle."""
+    for lvl, heads in enumerate(heads_per_level):
+        D, H, W = (n >> (4 - lvl) for n in vol)
+        C = d * heads
+        assert modet.modet_has_tiled_kernels(C, heads, 3) == 3
+        seed = 900 + 10 * lvl + (0 if name == "small" else 5)
+        Q = synth.normal(seed, 0, (1, D, H, W, C))
+        K = (0.8 * np.roll(Q, (1, -1, 1), axis=(1, 2, 3)) + 0.6 * synth.normal(seed, 1, (1, D, H, W, C))).astype(np.float32)
+        g = synth.normal(seed, 2, (1, D, H, W, heads, 3))
+        bias = (0.5 * synth.normal(seed, 3, (heads, 27))).astype(np.float32)
+        Qg, Kg = up(Q), up(K)
+        phi, lse = modet.modet_fwd(Qg, Kg, heads, 3, bias=up(bias), want_lse=True)
+        dQ, dK = modet.modet_bwd(Qg, Kg, up(g), heads, 3, bias=up(bias), phi=phi, lse=lse)
+        idx = sample_windows(1, D, H, W, heads, 3000, seed=seed, r=1)
+        ref_phi, ref_lse = oracle.modet_fwd_at(Q, K, idx, heads, 3, bias=bias)
+        ref_dQ, ref_dK = oracle.modet_bwd_at(Q, K, g, idx, heads, 3, bias=bias)
+        t = torch.from_numpy(idx).cuda()
+        tag = f"{name} model, level {lvl + 1} ({D}x{H}x{W}, C={C}, {heads} heads)"
+        assert_close(phi.reshape(-1, 3)[t].cpu().numpy(), ref_phi, "f32", "phi " + tag)
+        assert_close(lse.reshape(-1)[t].cpu().numpy(), ref_lse, "f32", "lse " + tag)
+        assert_close(dQ.reshape(-1, d)[t].cpu().numpy(), ref_dQ, "f32", "dQ " + tag)
+        assert_close(dK.reshape(-1, d)[t].cpu().numpy(), ref_dK, "f32", "dK " + tag)
+        del Qg, Kg, phi, lse, dQ, dK
