@@ -685,10 +685,13 @@ __global__ void zero_kernel(float* p, long long n) {
   if (i < n) p[i] = 0.f;
 }
 
+// A workgroup works through my x mz bricks, one after the other (a super-brick; 1 x 1 at full resolution): at half
+// resolution the coarse voxels it touches are staged once, and each collects from all of those bricks before
+// it is added to the global gradient.
 template <class T, int VEC, bool HALF>
 __global__ void __launch_bounds__(kThreads)
 warp_dfield_kernel(const T* __restrict__ src, const float* __restrict__ field, const float* __restrict__ dout,
-                   float* __restrict__ dfield, int B, int D, int H, int W, int C, Brick bk) {
+                   float* __restrict__ dfield, int B, int D, int H, int W, int C, Brick bk, int my, int mz) {
   const unsigned nb = gridDim.x, xcd = blockIdx.x & 7u, q = nb >> 3, rem = nb & 7u;
   unsigned blk = xcd * q + (xcd < rem ? xcd : rem) + (blockIdx.x >> 3);
   int chunk, lx, ly, lz;
@@ -706,22 +709,22 @@ warp_dfield_kernel(const T* __restrict__ src, const float* __restrict__ field, c
     ly = t % bk.by;
     lz = t / bk.by;
   }
+  const int nsy = (bk.nby + my - 1) / my, nsz = (bk.nbz + mz - 1) / mz;
   const int ibx = blk % bk.nbx; blk /= bk.nbx;
-  const int iby = blk % bk.nby; blk /= bk.nby;
-  const int ibz = blk % bk.nbz;
-  const int b = blk / bk.nbz;
-  const int x = ibx * bk.bx + lx, y = iby * bk.by + ly, z = ibz * bk.bz + lz;
-  const bool live = lz < bk.bz && x < W && y < H && z < D;
+  const int isy = blk % nsy; blk /= nsy;
+  const int isz = blk % nsz;
+  const int b = blk / nsz;
   __shared__ float tile[HALF ? kMaxTile * 3 : 1];
   __shared__ float dus[kThreads * 3];                   // every lane's sums, to be collected per (coarse) voxel
   CoarseTile ct = {};
   const int Dc = D / 2, Hc = H / 2, Wc = W / 2;
   if (HALF) {
-    const int xf = ibx * bk.bx, yf = iby * bk.by, zf = ibz * bk.bz;
-    ct.ox = coarse_lo(xf); ct.oy = coarse_lo(yf); ct.oz = coarse_lo(zf);
+    // the coarse voxels of the whole super-brick (the host keeps them within kMaxTile)
+    const int xf = ibx * bk.bx, yf = isy * my * bk.by, zf = isz * mz * bk.bz;
+    ct.ox = coarse_lo(xf); ct.oy = coarse_lo(min(yf, H - 1)); ct.oz = coarse_lo(min(zf, D - 1));
     ct.nx = min(coarse_lo(min(xf + bk.bx, W) - 1) + 1, Wc - 1) - ct.ox + 1;
-    ct.ny = min(coarse_lo(min(yf + bk.by, H) - 1) + 1, Hc - 1) - ct.oy + 1;
-    ct.nz = min(coarse_lo(min(zf + bk.bz, D) - 1) + 1, Dc - 1) - ct.oz + 1;
+    ct.ny = min(coarse_lo(max(min(yf + my * bk.by, H), 1) - 1) + 1, Hc - 1) - ct.oy + 1;
+    ct.nz = min(coarse_lo(max(min(zf + mz * bk.bz, D), 1) - 1) + 1, Dc - 1) - ct.oz + 1;
     const float* fc = field + (long long)b * Dc * Hc * Wc * 3;
     const int n = ct.nx * ct.ny * ct.nz;
     for (int e = threadIdx.x; e < n; e += kThreads) {
@@ -731,105 +734,114 @@ warp_dfield_kernel(const T* __restrict__ src, const float* __restrict__ field, c
     }
     __syncthreads();
   }
-  // (nobody leaves early: with a half-resolution field everybody meets again at a barrier)
-  float du[3] = {0.f, 0.f, 0.f};
-  bool writer = false;       // does this lane hold the voxel's whole sum?
-  if (live) {
-    const long long vol = (long long)b * D * H * W * C + chunk * VEC;
-    const long long v = (((long long)b * D + z) * H + y) * W + x;
-    double u[3];
-    if (HALF) {
-      upsampled_disp(tile, ct, Dc, Hc, Wc, z, y, x, u);
-    } else {
-      u[0] = field[v * 3]; u[1] = field[v * 3 + 1]; u[2] = field[v * 3 + 2];
-    }
-    const Split sp = split_disp(u);
-    const float tz = sp.tz, ty = sp.ty, tx = sp.tx;
-    const int z0 = z + sp.fz, y0 = y + sp.fy, x0 = x + sp.fx;
-    float g[VEC];
-    Vec<float, VEC>::load(dout + v * C + chunk * VEC, g);
-    float val[8][VEC];
-    bool in[8];
+  // half resolution: this lane's coarse voxel (one per lane) and what it has collected so far
+  const int ncoarse = HALF ? ct.nx * ct.ny * ct.nz : 0;
+  const int ce = threadIdx.x;
+  const int cx = ct.ox + ce % max(ct.nx, 1), cy = ct.oy + (ce / max(ct.nx, 1)) % max(ct.ny, 1);
+  const int cz = ct.oz + ce / max(ct.nx * ct.ny, 1);
+  float acc[3] = {0.f, 0.f, 0.f};
+  // (nobody leaves the loop early: everybody meets at its barriers)
+  for (int sub = 0; sub < my * mz; ++sub) {
+    const int iby = isy * my + sub % my, ibz = isz * mz + sub / my;
+    const int x = ibx * bk.bx + lx, y = iby * bk.by + ly, z = ibz * bk.bz + lz;
+    const bool live = lz < bk.bz && x < W && y < H && z < D;
+    float du[3] = {0.f, 0.f, 0.f};
+    bool writer = false;       // does this lane hold the voxel's whole sum?
+    if (live) {
+      const long long vol = (long long)b * D * H * W * C + chunk * VEC;
+      const long long v = (((long long)b * D + z) * H + y) * W + x;
+      double u[3];
+      if (HALF) {
+        upsampled_disp(tile, ct, Dc, Hc, Wc, z, y, x, u);
+      } else {
+        u[0] = field[v * 3]; u[1] = field[v * 3 + 1]; u[2] = field[v * 3 + 2];
+      }
+      const Split sp = split_disp(u);
+      const float tz = sp.tz, ty = sp.ty, tx = sp.tx;
+      const int z0 = z + sp.fz, y0 = y + sp.fy, x0 = x + sp.fx;
+      float g[VEC];
+      Vec<float, VEC>::load(dout + v * C + chunk * VEC, g);
+      float val[8][VEC];
+      bool in[8];
 #pragma unroll
-    for (int c = 0; c < 8; ++c) {     // all corner loads first, from clamped addresses
-      const int zi = z0 + ((c >> 2) & 1), yi = y0 + ((c >> 1) & 1), xi = x0 + (c & 1);
-      in[c] = (unsigned)zi < (unsigned)D && (unsigned)yi < (unsigned)H && (unsigned)xi < (unsigned)W;
-      const int zc = min(max(zi, 0), D - 1), yc = min(max(yi, 0), H - 1), xc = min(max(xi, 0), W - 1);
-      Vec<T, VEC>::load(src + vol + (((long long)zc * H + yc) * W + xc) * C, val[c]);
-    }
+      for (int c = 0; c < 8; ++c) {     // all corner loads first, from clamped addresses
+        const int zi = z0 + ((c >> 2) & 1), yi = y0 + ((c >> 1) & 1), xi = x0 + (c & 1);
+        in[c] = (unsigned)zi < (unsigned)D && (unsigned)yi < (unsigned)H && (unsigned)xi < (unsigned)W;
+        const int zc = min(max(zi, 0), D - 1), yc = min(max(yi, 0), H - 1), xc = min(max(xi, 0), W - 1);
+        Vec<T, VEC>::load(src + vol + (((long long)zc * H + yc) * W + xc) * C, val[c]);
+      }
 #pragma unroll
-    for (int c = 0; c < 8; ++c) {
-      const float wz = (c & 4) ? tz : 1.f - tz, wy = (c & 2) ? ty : 1.f - ty, wx = (c & 1) ? tx : 1.f - tx;
-      if (in[c]) {
-        float dot = 0.f;
+      for (int c = 0; c < 8; ++c) {
+        const float wz = (c & 4) ? tz : 1.f - tz, wy = (c & 2) ? ty : 1.f - ty, wx = (c & 1) ? tx : 1.f - tx;
+        if (in[c]) {
+          float dot = 0.f;
 #pragma unroll
-        for (int i = 0; i < VEC; ++i) dot = fmaf(g[i], val[c][i], dot);
-        du[0] = fmaf(((c & 4) ? wy : -wy) * wx, dot, du[0]);
-        du[1] = fmaf(((c & 2) ? wz : -wz) * wx, dot, du[1]);
-        du[2] = fmaf(((c & 1) ? wz : -wz) * wy, dot, du[2]);
+          for (int i = 0; i < VEC; ++i) dot = fmaf(g[i], val[c][i], dot);
+          du[0] = fmaf(((c & 4) ? wy : -wy) * wx, dot, du[0]);
+          du[1] = fmaf(((c & 2) ? wz : -wz) * wx, dot, du[1]);
+          du[2] = fmaf(((c & 1) ? wz : -wz) * wy, dot, du[2]);
+        }
+      }
+      writer = true;
+      if (bk.sc >= 0) {        // (uniform) the voxel's lanes are an aligned group of 2^sc lanes
+        for (int m = 1; m < (1 << bk.sc); m <<= 1) {
+          du[0] += __shfl_xor(du[0], m); du[1] += __shfl_xor(du[1], m); du[2] += __shfl_xor(du[2], m);
+        }
+        writer = chunk == 0;
+        if (!HALF && writer) {     // the only writer of this voxel's entry
+          float* o = dfield + v * 3;
+          o[0] = du[0]; o[1] = du[1]; o[2] = du[2];
+        }
       }
     }
-    writer = true;
-    if (bk.sc >= 0) {        // (uniform) the voxel's lanes are an aligned group of 2^sc lanes
-      for (int m = 1; m < (1 << bk.sc); m <<= 1) {
-        du[0] += __shfl_xor(du[0], m); du[1] += __shfl_xor(du[1], m); du[2] += __shfl_xor(du[2], m);
-      }
-      writer = chunk == 0;
-      if (!HALF && writer) {     // the only writer of this voxel's entry
-        float* o = dfield + v * 3;
-        o[0] = du[0]; o[1] = du[1]; o[2] = du[2];
-      }
-    }
-  }
-  if (!HALF && bk.sc >= 0) return;               // (uniform)
-  // the lanes park their sums in LDS
+    if (!HALF && bk.sc >= 0) return;               // (uniform; full resolution runs one brick per workgroup)
+    // the lanes park their sums in LDS
 #pragma unroll
-  for (int a = 0; a < 3; ++a) dus[threadIdx.x * 3 + a] = writer ? du[a] : 0.f;
-  __syncthreads();
-  if (!HALF) {
-    // a voxel's lanes are no lane group (its channel count is no power of two): one lane per voxel adds their
-    // parts up and writes
-    const int nchunk = C / VEC, t = threadIdx.x;
-    const int vx = ibx * bk.bx + t % bk.bx, vy = iby * bk.by + (t / bk.bx) % bk.by, vz = ibz * bk.bz + t / (bk.bx * bk.by);
-    if (t < kThreads / nchunk && t / (bk.bx * bk.by) < bk.bz && vx < W && vy < H && vz < D) {
-      float acc[3] = {0.f, 0.f, 0.f};
-      for (int j = 0; j < nchunk; ++j) {
-        const float* d = dus + (t * nchunk + j) * 3;
-        acc[0] += d[0]; acc[1] += d[1]; acc[2] += d[2];
+    for (int a = 0; a < 3; ++a) dus[threadIdx.x * 3 + a] = writer ? du[a] : 0.f;
+    __syncthreads();
+    if (!HALF) {
+      // a voxel's lanes are no lane group (its channel count is no power of two): one lane per voxel adds their
+      // parts up and writes
+      const int nchunk = C / VEC, t = threadIdx.x;
+      const int vx = ibx * bk.bx + t % bk.bx, vy = iby * bk.by + (t / bk.bx) % bk.by, vz = ibz * bk.bz + t / (bk.bx * bk.by);
+      if (t < kThreads / nchunk && t / (bk.bx * bk.by) < bk.bz && vx < W && vy < H && vz < D) {
+        float sum[3] = {0.f, 0.f, 0.f};
+        for (int j = 0; j < nchunk; ++j) {
+          const float* d = dus + (t * nchunk + j) * 3;
+          sum[0] += d[0]; sum[1] += d[1]; sum[2] += d[2];
+        }
+        float* o = dfield + ((((long long)b * D + vz) * H + vy) * W + vx) * 3;
+        o[0] = sum[0]; o[1] = sum[1]; o[2] = sum[2];
       }
-      float* o = dfield + ((((long long)b * D + vz) * H + vy) * W + vx) * 3;
-      o[0] = acc[0]; o[1] = acc[1]; o[2] = acc[2];
+      return;
     }
-    return;
-  }
-  // Half resolution: u = 2 * sum of weight * coarse value over the (clamped) coarse corners of a voxel, and up to
-  // 64 fine voxels share a coarse one.  The lanes park their sums in LDS; then one lane per staged coarse voxel
-  // collects, through the upsampling weights, what the brick's fine voxels owe it (along each axis the fine voxels
-  // 2c - 1 ... 2c + 2 touch coarse voxel c) and adds it to the global gradient once.
-  const int nlane = bk.sc >= 0 ? 1 : C / VEC;      // lanes of a voxel that hold a part of its sum
-  const int vstride = bk.sc >= 0 ? 1 << bk.sc : C / VEC;
-  const int xf = ibx * bk.bx, yf = iby * bk.by, zf = ibz * bk.bz;
-  const int xe = min(xf + bk.bx, W), ye = min(yf + bk.by, H), ze = min(zf + bk.bz, D);
-  float* dc = dfield + (long long)b * Dc * Hc * Wc * 3;
-  const int n = ct.nx * ct.ny * ct.nz;
-  for (int e = threadIdx.x; e < n; e += kThreads) {
-    const int cx = ct.ox + e % ct.nx, cy = ct.oy + (e / ct.nx) % ct.ny, cz = ct.oz + e / (ct.nx * ct.ny);
-    float acc[3] = {0.f, 0.f, 0.f};
-    for (int fz = max(2 * cz - 1, zf); fz <= min(2 * cz + 2, ze - 1); ++fz) {
-      const float wz = up_weight(fz, cz, Dc);
-      for (int fy = max(2 * cy - 1, yf); fy <= min(2 * cy + 2, ye - 1); ++fy) {
-        const float wzy = wz * up_weight(fy, cy, Hc);
-        for (int fx = max(2 * cx - 1, xf); fx <= min(2 * cx + 2, xe - 1); ++fx) {
-          const float w = 2.f * wzy * up_weight(fx, cx, Wc);
-          const int first = (((fz - zf) * bk.by + fy - yf) * bk.bx + fx - xf) * vstride;
-          for (int j = 0; j < nlane; ++j) {
-            const float* d = dus + (first + j) * 3;
-            acc[0] = fmaf(w, d[0], acc[0]); acc[1] = fmaf(w, d[1], acc[1]); acc[2] = fmaf(w, d[2], acc[2]);
+    // Half resolution: u = 2 * sum of weight * coarse value over the (clamped) coarse corners of a voxel, and up
+    // to 64 fine voxels share a coarse one: every staged coarse voxel collects, through the upsampling weights,
+    // what this brick's fine voxels owe it (along each axis the fine voxels 2c - 1 ... 2c + 2 touch coarse voxel c).
+    if (ce < ncoarse) {
+      const int nlane = bk.sc >= 0 ? 1 : C / VEC;      // lanes of a voxel that hold a part of its sum
+      const int vstride = bk.sc >= 0 ? 1 << bk.sc : C / VEC;
+      const int xf = ibx * bk.bx, yf = iby * bk.by, zf = ibz * bk.bz;
+      const int xe = min(xf + bk.bx, W), ye = min(yf + bk.by, H), ze = min(zf + bk.bz, D);
+      for (int fz = max(2 * cz - 1, zf); fz <= min(2 * cz + 2, ze - 1); ++fz) {
+        const float wz = up_weight(fz, cz, Dc);
+        for (int fy = max(2 * cy - 1, yf); fy <= min(2 * cy + 2, ye - 1); ++fy) {
+          const float wzy = wz * up_weight(fy, cy, Hc);
+          for (int fx = max(2 * cx - 1, xf); fx <= min(2 * cx + 2, xe - 1); ++fx) {
+            const float w = 2.f * wzy * up_weight(fx, cx, Wc);
+            const int first = (((fz - zf) * bk.by + fy - yf) * bk.bx + fx - xf) * vstride;
+            for (int j = 0; j < nlane; ++j) {
+              const float* d = dus + (first + j) * 3;
+              acc[0] = fmaf(w, d[0], acc[0]); acc[1] = fmaf(w, d[1], acc[1]); acc[2] = fmaf(w, d[2], acc[2]);
+            }
           }
         }
       }
     }
-    float* o = dc + (((long long)cz * Hc + cy) * Wc + cx) * 3;
+    __syncthreads();                               // (the next brick parks its sums in the same place)
+  }
+  if (HALF && ce < ncoarse) {                      // one addition per coarse voxel and workgroup
+    float* o = dfield + (long long)b * Dc * Hc * Wc * 3 + (((long long)cz * Hc + cy) * Wc + cx) * 3;
     unsafeAtomicAdd(o, acc[0]); unsafeAtomicAdd(o + 1, acc[1]); unsafeAtomicAdd(o + 2, acc[2]);
   }
 }
@@ -881,13 +893,21 @@ hipError_t launch_bwd_t(const void* src, const float* field, const float* dout, 
     const long long nf = (long long)B * (D / 2) * (H / 2) * (W / 2) * 3;
     hipLaunchKernelGGL(zero_kernel, dim3((unsigned)((nf + 255) / 256)), dim3(256), 0, st, dfield, nf);
   }
-  dim3 grid((unsigned)((long long)bk.nbx * bk.nby * bk.nbz * B));
+  // half resolution: bricks per workgroup, as many (up to 2 x 4 in y, z) as keep the staged coarse voxels, at
+  // most n/2 + 2 per axis, within kMaxTile
+  int my = 1, mz = 1;
+  if (half) {
+    auto staged = [&](int a, int c) { return (bk.bx / 2 + 2) * (bk.by * a / 2 + 2) * (bk.bz * c / 2 + 2); };
+    while (mz < 4 && staged(my, mz * 2) <= kMaxTile) mz *= 2;
+    while (my < 2 && staged(my * 2, mz) <= kMaxTile) my *= 2;
+  }
+  dim3 grid((unsigned)((long long)bk.nbx * ((bk.nby + my - 1) / my) * ((bk.nbz + mz - 1) / mz) * B));
   if (half)
     hipLaunchKernelGGL((warp_dfield_kernel<T, VEC, true>), grid, block, 0, st, (const T*)src, field, dout, dfield, B, D,
-                       H, W, C, bk);
+                       H, W, C, bk, my, mz);
   else
     hipLaunchKernelGGL((warp_dfield_kernel<T, VEC, false>), grid, block, 0, st, (const T*)src, field, dout, dfield, B,
-                       D, H, W, C, bk);
+                       D, H, W, C, bk, my, mz);
   return hipGetLastError();
 }
 
