@@ -145,9 +145,10 @@ int modet_warp(const void* src, const float* field, void* out,
  *   src     in   dtype; only read for dfield (may be NULL when dfield is NULL)
  *   field   in   as in modet_warp
  *   dout    in   fp32 [B, D, H, W, C]
- *   dsrc    out  fp32 [B, D, H, W, C], fully overwritten: zeroed, then accumulated with fp32 atomics, so the
- *                last bits depend on the order of the additions
- *   dfield  out  nullable, fp32, fully overwritten
+ *   dsrc    out  fp32 [B, D, H, W, C], fully overwritten.  The additions to one element happen in no fixed
+ *                order (on chip for contributions that follow the local displacement, with fp32 atomics
+ *                for the rest), so the last bits can differ from run to run
+ *   dfield  out  nullable, fp32, fully overwritten (half resolution: accumulated with fp32 atomics, same remark)
  *   shapes and dtypes as in modet_warp
  */
 int modet_warp_bwd(const void* src, const float* field, const float* dout, float* dsrc, float* dfield,
