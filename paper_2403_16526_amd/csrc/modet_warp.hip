@@ -970,8 +970,8 @@ compose_kernel(const float* __restrict__ outer, const float* __restrict__ inner,
 // The same with the outer field given at half resolution [B, D/2, H/2, W/2, 3]: the value of the 2x upsampled
 // field (values doubled) at each of the eight fine corners around p + inner(p) is itself a trilinear mix of
 // coarse voxels, and per axis the two fine corners together touch at most three consecutive coarse voxels.  The
-// two interpolations are folded into one table of three weights per axis (fp64: the factors are exact, the
-// result is rounded once) over a 3 x 3 x 3 coarse neighbourhood, so the upsampled field is never materialised.
+// two interpolations are folded into one table of three weights per axis (built in fp64: the factors are exact)
+// over a 3 x 3 x 3 coarse neighbourhood, so the upsampled field is never materialised.
 // Fine corners outside the volume contribute nothing (zero padding of the fine field); inside, the upsampling
 // clamps its coarse coordinates like the warp's.
 __device__ __forceinline__ void axis_table(int i0, float t, int N, int& base, double (&w)[3]) {
@@ -1022,17 +1022,25 @@ compose_up_kernel(const float* __restrict__ outer_c, const float* __restrict__ i
     const int zi = min(bz + c / 9, Dc - 1), yi = min(by + (c / 3) % 3, Hc - 1), xi = min(bx + c % 3, Wc - 1);
     val[c] = *reinterpret_cast<const Disp*>(ob + ((zi * Hc + yi) * Wc + xi) * 3);
   }
-  double acc[3] = {0.0, 0.0, 0.0};
+  // the 27-term sum itself runs in fp32, x innermost (its rounding, ~3e-7 of the displacement, is far inside the
+  // tolerance of a field; the fp64 of the tables keeps the weights of clamped and outside corners exact)
+  float fwz[3], fwy[3], fwx[3];
 #pragma unroll
-  for (int c = 0; c < 27; ++c) {
-    const double w = wz[c / 9] * wy[(c / 3) % 3] * wx[c % 3];
-    acc[0] = fma(w, (double)val[c].z, acc[0]);
-    acc[1] = fma(w, (double)val[c].y, acc[1]);
-    acc[2] = fma(w, (double)val[c].x, acc[2]);
+  for (int j = 0; j < 3; ++j) { fwz[j] = (float)wz[j]; fwy[j] = (float)wy[j]; fwx[j] = (float)wx[j]; }
+  float acc[3] = {0.f, 0.f, 0.f};
+#pragma unroll
+  for (int zy = 0; zy < 9; ++zy) {
+    float row[3] = {0.f, 0.f, 0.f};
+#pragma unroll
+    for (int j = 0; j < 3; ++j) {
+      const Disp& d = val[zy * 3 + j];
+      row[0] = fmaf(fwx[j], d.z, row[0]); row[1] = fmaf(fwx[j], d.y, row[1]); row[2] = fmaf(fwx[j], d.x, row[2]);
+    }
+    const float w = fwz[zy / 3] * fwy[zy % 3];
+    acc[0] = fmaf(w, row[0], acc[0]); acc[1] = fmaf(w, row[1], acc[1]); acc[2] = fmaf(w, row[2], acc[2]);
   }
   Disp r;
-  r.z = (float)((double)iv.z + 2.0 * acc[0]); r.y = (float)((double)iv.y + 2.0 * acc[1]);
-  r.x = (float)((double)iv.x + 2.0 * acc[2]);
+  r.z = fmaf(2.f, acc[0], iv.z); r.y = fmaf(2.f, acc[1], iv.y); r.x = fmaf(2.f, acc[2], iv.x);
   *reinterpret_cast<Disp*>(out + v * 3) = r;
 }
 
