@@ -327,7 +327,7 @@ hipError_t launch_t(const void* src, const float* field, void* out, int B, int D
 // ones through the 2x upsampling weights.
 constexpr int kAdjThreads = 512, kAdjWaves = kAdjThreads / 64, kAdjRows = kBoxXY / kAdjWaves;
 constexpr int kAdjCols = kBoxXY + 2;               // columns a lower corner can have: -1 ... kBoxXY
-constexpr int kAdjLastTurn = 63;
+constexpr int kAdjLastTurn = 63;                   // (a column can collect (2 kNear + 1)^2 = 49 entries per step: a safeguard)
 
 struct AdjRec {
   int vox;            // source voxel, index inside its batch item

@@ -70,6 +70,27 @@ def test_warp_bwd_large_coherent_displacement(modet, shift, half, std):
     assert_close(dfield.cpu().numpy() / terms, ref_dfield / terms, "f32", f"dfield shift={shift}")
 
 
+@pytest.mark.parametrize("rate,half", [(0.8, False), (0.95, False), (0.6, True), (1.0, False)])
+def test_warp_bwd_contracting_field(modet, rate, half):
+    """A field that pulls every voxel towards one point (rate 1: exactly onto it): many source voxels share
+    their target voxels, so the staged pass has to apply entries of one column in turns."""
+    B, D, H, W, C = 1, 20, 36, 40, 8
+    src = synth.normal(94, 0, (B, D, H, W, C))
+    dout = synth.normal(95, 0, (B, D, H, W, C))
+    shape = (D // 2, H // 2, W // 2) if half else (D, H, W)
+    grid = np.stack(np.meshgrid(*[np.arange(n, dtype=np.float64) for n in shape], indexing="ij"), axis=-1)
+    centre = np.array([0.45 * n for n in shape])
+    field = (-rate * (grid - centre) + 0.13)[None].astype(np.float32)      # (coarse voxels for the half-resolution case)
+    field = np.ascontiguousarray(field)
+    ref_dsrc, ref_dfield = oracle.warp_bwd(src, field, dout, field_half_res=half)
+    dsrc, dfield = modet.modet_warp_bwd(up(src), up(field), up(dout), field_half_res=half)
+    # up to a few thousand terms of either sign per element: compare relative to what was summed
+    terms = np.sqrt(max(1.0, float(np.abs(ref_dsrc).max())))
+    assert_close(dsrc.cpu().numpy() / terms, ref_dsrc / terms, "f32", f"dsrc rate={rate}", scale=4.0)
+    t = 8.0 * np.sqrt(C) * (8.0 if half else 1.0)
+    assert_close(dfield.cpu().numpy() / t, ref_dfield / t, "f32", f"dfield rate={rate}")
+
+
 def test_warp_bwd_is_the_transpose_of_the_gpu_warp(modet):
     """<warp(x), y> = <x, warp_bwd(y)> with both sides computed on the GPU (fp32: 1e-5 of the magnitudes)."""
     B, D, H, W, C = 1, 12, 14, 40, 8
