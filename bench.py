@@ -41,6 +41,39 @@ def traffic_from_profile(kernel):
     return None
 
 
+def sclk_under(step, torch, seconds=1.2):
+    """Shader clock in MHz as `rocm-smi --showclocks` reports it while `step` loops (median of the samples), or
+    None if the tool is missing or prints something else.  Context for the roofline figures: the published peaks
+    assume 2.4 GHz, the box lowers the clock under sustained vector load."""
+    import re
+    import subprocess
+    import threading
+    samples, stop = [], threading.Event()
+
+    def watch():
+        while not stop.is_set():
+            try:
+                out = subprocess.run(["rocm-smi", "--showclocks"], capture_output=True, text=True, timeout=5).stdout
+            except Exception:
+                return
+            m = re.search(r"sclk clock level: \d+: \((\d+)Mhz\)", out)
+            if m:
+                samples.append(int(m.group(1)))
+            stop.wait(0.2)
+
+    th = threading.Thread(target=watch, daemon=True)
+    th.start()
+    t0 = time.perf_counter()
+    while time.perf_counter() - t0 < seconds:
+        for _ in range(20):
+            step()
+        torch.cuda.synchronize()
+    stop.set()
+    th.join(timeout=10)
+    samples = sorted(samples[1:] or samples)          # (the first sample may predate the load)
+    return samples[len(samples) // 2] if samples else None
+
+
 def bench_pyramid(args, np, torch, modet, synth):
     """Config 4: the five-level coarse-to-fine loop for a 160x192x224 pair (Section 3.1); a step is one
     iteration over all levels (warp, forward, composition, backward, update), `--steps` of them are timed (50
@@ -160,6 +193,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=None, help="default: 100 (config 4: 5)")
     ap.add_argument("--config", type=int, default=3, choices=[1, 2, 3, 4, 5])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-clock-sample", action="store_true", help="do not sample the shader clock under load")
     ap.add_argument("--generic", action="store_true", help="force the generic kernels")
     ap.add_argument("--fast-logits", action="store_true",
                     help="fp32 instead of fp64 logits (does not meet the parity tolerance; for information)")
@@ -258,6 +292,7 @@ def main():
     t_fwd = sum(e[0].elapsed_time(e[1]) for e in ev) / args.steps          # ms
     t_bwd = sum(e[1].elapsed_time(e[2]) for e in ev) / args.steps
     ms_per_step = wall * 1e3 / args.steps
+    sclk = None if args.no_clock_sample else sclk_under(lambda: (fwd(), bwd()), torch)
 
     # algorithmic bytes (each tensor moved once, no stored attention)
     fwd_bytes = nvox * (2 * C * esz + 12 * heads)
@@ -402,7 +437,7 @@ def main():
         "roofline": roofline,
         roofline_other[0]: roofline_other[1],
         "cpu_baseline": cpu,
-        "fwd_ms": round(t_fwd, 4), "bwd_ms": round(t_bwd, 4),
+        "fwd_ms": round(t_fwd, 4), "bwd_ms": round(t_bwd, 4), "sclk_mhz_under_load": sclk,
         "hbm_gbs_fwd_bwd": round((fwd_bytes + bwd_bytes) / ((t_fwd + t_bwd) * 1e-3) / 1e9, 1),
         "hbm_frac_fwd_bwd": round((fwd_bytes + bwd_bytes) / ((t_fwd + t_bwd) * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
         "hbm_gbs_fwd": round(fwd_bytes / (t_fwd * 1e-3) / 1e9, 1),
