@@ -298,8 +298,8 @@ hipError_t launch_t(const void* src, const float* field, void* out, int B, int D
 // its (y, x) footprint shifted by -c and widened by kNear, planes za - cz - kNear ... zb - 1 - cz + kNear.  The
 // 2 kNear + 1 target planes that the current source plane can touch live in LDS.  Per source plane: (a) one lane
 // per voxel of the widened plane splits its displacement and, if a near corner lands in the box, appends a
-// record (source index, LDS target, validity of the six corner coordinates, fractions) to a list in LDS; (b) one
-// lane per (record, channel) loads its dout value and adds the weighted copies to the planes in LDS; (c) the
+// record (source index, LDS target, validity of the six corner coordinates, fractions) to a list in LDS; (b) the
+// lanes load the records' dout values and add the weighted copies to the planes in LDS; (c) the
 // target plane that no later source plane can reach is written to dsrc with plain, coalesced stores and its LDS
 // slot cleared.  Every element of dsrc is written exactly once here: no zero-fill pass, no global atomic.
 //
@@ -310,7 +310,7 @@ hipError_t launch_t(const void* src, const float* field, void* out, int B, int D
 // wave's bin: eight corners each) or, row by row, under the two waves that own one each (list from the back: four
 // corners each).  In step (b) a wave works through its own bin, 64 / (lanes per entry) entries per instruction, a
 // lane taking four channels (or all, if fewer).  LDS operations of one wave execute in order, so two lanes can
-// only collide inside one instruction, and only (see adj_apply) if their entries' first adds go to the same (row,
+// only collide inside one instruction, and only (see adj_adds) if their entries' first adds go to the same (row,
 // column): step (a) numbers the entries of a step that share one (an LDS counter per row and column), and an
 // instruction applies its entries in turns, one number at a time.
 //
